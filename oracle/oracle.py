@@ -1,0 +1,231 @@
+"""ctypes front end of ``sage_oracle.c`` (fp64 CPU oracle; test infrastructure only).
+
+Every function here only marshals arguments; the arithmetic lives in the C file, which cites the passages of
+the paper (arxiv 2510.02470) it follows.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sage_oracle.c")
+_LIB = os.path.join(_HERE, "libsage_oracle.so")
+_lib = None
+
+
+def build_oracle(force=False):
+    """Compile the oracle with gcc (no arch-specific flags: the library also runs on another host)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build_oracle()
+    L = C.CDLL(_LIB)
+    vp, i64, dbl, i32 = C.c_void_p, C.c_int64, C.c_double, C.c_int
+    L.orc_create.restype = vp
+    L.orc_create.argtypes = [i32, i64, i32]
+    L.orc_destroy.argtypes = [vp]
+    for name in ("orc_update_f32", "orc_update_bf16", "orc_score_f32", "orc_score_bf16"):
+        getattr(L, name).argtypes = [vp, vp, i64]
+        getattr(L, name).restype = i32
+    L.orc_basis.argtypes = [vp, i32]
+    L.orc_set_basis.argtypes = [vp, vp, i32]
+    L.orc_select.argtypes = [vp, dbl, vp, i64, vp]
+    L.orc_topm_f32.argtypes = [vp, i64, i64, vp]
+    L.orc_keep_count.argtypes = [dbl, i64]
+    L.orc_keep_count.restype = i64
+    L.orc_hestenes_rows.argtypes = [vp, i32, i64, vp]
+    L.orc_sym_jacobi.argtypes = [vp, i32, vp, vp]
+    for name in ("orc_B", "orc_V", "orc_sig2", "orc_alpha", "orc_zhat", "orc_u", "orc_ssum"):
+        getattr(L, name).argtypes = [vp]
+        getattr(L, name).restype = C.POINTER(C.c_double)
+    for name in ("orc_fill", "orc_n_shrinks", "orc_last_sweeps"):
+        getattr(L, name).argtypes = [vp]
+        getattr(L, name).restype = i32
+    for name in ("orc_n_scored", "orc_rows_seen"):
+        getattr(L, name).argtypes = [vp]
+        getattr(L, name).restype = i64
+    for name in ("orc_sum_delta", "orc_last_delta", "orc_frob2"):
+        getattr(L, name).argtypes = [vp]
+        getattr(L, name).restype = dbl
+    L.orc_threads.restype = i32
+    _lib = L
+    return L
+
+
+def oracle_threads():
+    return int(_load().orc_threads())
+
+
+def _as_rows(G):
+    """Accept float32 rows, or bf16 rows given as uint16 bit patterns. Returns (array, is_bf16)."""
+    G = np.ascontiguousarray(G)
+    if G.dtype == np.uint16:
+        return G, True
+    if G.dtype != np.float32:
+        raise TypeError("rows must be float32, or uint16 holding bf16 bit patterns")
+    return G, False
+
+
+class Oracle:
+    """The four calls of the path on the CPU in fp64. mode 0 = Hestenes on rows, mode 1 = Gram route."""
+
+    def __init__(self, ell, D, mode=0):
+        self.L = _load()
+        self.ell, self.n, self.D, self.mode = int(ell), 2 * int(ell), int(D), int(mode)
+        self.h = self.L.orc_create(self.ell, self.D, self.mode)
+        if not self.h:
+            raise ValueError("bad ell / D / mode")
+        self.k = 0
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            self.L.orc_destroy(self.h)
+            self.h = None
+
+    def update(self, G):
+        G, bf = _as_rows(G)
+        assert G.ndim == 2 and G.shape[1] == self.D
+        fn = self.L.orc_update_bf16 if bf else self.L.orc_update_f32
+        rc = fn(self.h, G.ctypes.data, G.shape[0])
+        assert rc == 0
+
+    def basis(self, k):
+        rc = self.L.orc_basis(self.h, int(k))
+        if rc != 0:
+            raise ValueError("basis: need 1 <= k <= ell-1")
+        self.k = int(k)
+
+    def set_basis(self, Vt):
+        Vt = np.ascontiguousarray(Vt, dtype=np.float64)
+        assert Vt.ndim == 2 and Vt.shape[1] == self.D
+        rc = self.L.orc_set_basis(self.h, Vt.ctypes.data, Vt.shape[0])
+        assert rc == 0
+        self.k = Vt.shape[0]
+
+    def score(self, G):
+        G, bf = _as_rows(G)
+        assert G.ndim == 2 and G.shape[1] == self.D
+        fn = self.L.orc_score_bf16 if bf else self.L.orc_score_f32
+        rc = fn(self.h, G.ctypes.data, G.shape[0])
+        if rc != 0:
+            raise RuntimeError("score before basis")
+
+    def select(self, keep_rate):
+        N = self.n_scored
+        out = np.empty(max(N, 1), dtype=np.int64)
+        m = C.c_int64(0)
+        rc = self.L.orc_select(self.h, float(keep_rate), out.ctypes.data, N, C.byref(m))
+        if rc != 0:
+            raise RuntimeError("select failed rc=%d" % rc)
+        return out[: m.value].copy()
+
+    # ---- views (copies) ----
+    def _arr(self, ptr, shape):
+        n = int(np.prod(shape))
+        if n == 0:
+            return np.zeros(shape)
+        return np.ctypeslib.as_array(ptr, shape=(n,)).reshape(shape).copy()
+
+    @property
+    def B(self):
+        return self._arr(self.L.orc_B(self.h), (self.n, self.D))
+
+    @property
+    def V(self):
+        return self._arr(self.L.orc_V(self.h), (self.k, self.D))
+
+    @property
+    def sig2(self):
+        return self._arr(self.L.orc_sig2(self.h), (self.n,))
+
+    @property
+    def alpha(self):
+        return self._arr(self.L.orc_alpha(self.h), (self.n_scored,))
+
+    @property
+    def zhat(self):
+        return self._arr(self.L.orc_zhat(self.h), (self.n_scored, self.k))
+
+    @property
+    def u(self):
+        return self._arr(self.L.orc_u(self.h), (self.k,))
+
+    @property
+    def ssum(self):
+        return self._arr(self.L.orc_ssum(self.h), (self.k,))
+
+    @property
+    def fill(self):
+        return int(self.L.orc_fill(self.h))
+
+    @property
+    def n_scored(self):
+        return int(self.L.orc_n_scored(self.h))
+
+    @property
+    def rows_seen(self):
+        return int(self.L.orc_rows_seen(self.h))
+
+    @property
+    def sum_delta(self):
+        return float(self.L.orc_sum_delta(self.h))
+
+    @property
+    def last_delta(self):
+        return float(self.L.orc_last_delta(self.h))
+
+    @property
+    def frob2(self):
+        return float(self.L.orc_frob2(self.h))
+
+    @property
+    def n_shrinks(self):
+        return int(self.L.orc_n_shrinks(self.h))
+
+    @property
+    def last_sweeps(self):
+        return int(self.L.orc_last_sweeps(self.h))
+
+
+def hestenes_rows(A):
+    """One-sided Jacobi on the rows of A. Returns (rows = sigma_j v_j^T sorted descending, sigma^2, sweeps)."""
+    L = _load()
+    A = np.array(A, dtype=np.float64, order="C", copy=True)
+    n, D = A.shape
+    s2 = np.zeros(n)
+    sweeps = L.orc_hestenes_rows(A.ctypes.data, n, D, s2.ctypes.data)
+    return A, s2, int(sweeps)
+
+
+def sym_jacobi(Cm):
+    """Cyclic two-sided Jacobi of a symmetric matrix. Returns (lam descending, Y with eigenvectors in columns)."""
+    L = _load()
+    Cm = np.array(Cm, dtype=np.float64, order="C", copy=True)
+    n = Cm.shape[0]
+    Y = np.zeros((n, n))
+    lam = np.zeros(n)
+    L.orc_sym_jacobi(Cm.ctypes.data, n, Y.ctypes.data, lam.ctypes.data)
+    return lam, Y
+
+
+def topm_f32(alpha, m):
+    L = _load()
+    alpha = np.ascontiguousarray(alpha, dtype=np.float32)
+    out = np.empty(max(int(m), 1), dtype=np.int64)
+    rc = L.orc_topm_f32(alpha.ctypes.data, alpha.shape[0], int(m), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("need 0 <= m <= N")
+    return out[: int(m)].copy()
+
+
+def keep_count(keep_rate, N):
+    return int(_load().orc_keep_count(float(keep_rate), int(N)))
