@@ -1,0 +1,184 @@
+/*
+ * sage.h -- C ABI of the MI355X (gfx950) SAGE hot-path library.
+ *
+ * SAGE (arxiv 2510.02470) selects a training subset in two streaming passes over per-example gradient rows
+ * g_i in R^D:  pass 1 keeps a Frequent Directions (FD) sketch of the rows (Method, FD paragraph; Algorithm 1,
+ * Phase I); pass 2 projects each row on the frozen sketch, normalises, forms the consensus direction and scores
+ * each row by its cosine to it, then keeps the top fraction (Method, "Two-pass scoring"; Algorithm 1, Phase II
+ * and the "Select top-k" line).
+ *
+ * Conventions
+ *   - Every pointer argument says whether it is HOST or DEVICE memory. DEVICE means memory of the GPU that was
+ *     current when the context was created. The library owns the sketch, the basis, the score store and all
+ *     work space; the caller owns every G_batch, every output array and keeps them valid until the call's work
+ *     has completed on the context's stream (sage_sync, sage_select, sage_stats and the export calls wait).
+ *   - Work is enqueued on one HIP stream per context, given at creation (NULL = the default stream). Calls on
+ *     one context must not overlap in time.
+ *   - Rows are row-major with leading dimension D (no padding): element (i, d) of a batch is at i*D + d.
+ *   - ell is the sketch size; the buffer holds n = 2*ell rows; k is the rank of the scoring basis; the example
+ *     index of a scored row is its 0-based arrival order within the scoring pass.
+ *   - Every call returns 0 on success or a negative sage_status; nothing throws. Non-finite input is not
+ *     detected and gives unspecified (but memory-safe) results.
+ */
+#ifndef SAGE_H
+#define SAGE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sage_ctx sage_ctx;
+
+typedef enum {
+    SAGE_F32 = 0, /* rows are IEEE binary32 */
+    SAGE_BF16 = 1 /* rows are bfloat16 (upper half of a binary32); widened exactly, all arithmetic in fp32 */
+} sage_dtype;
+
+typedef enum {
+    SAGE_OK = 0,
+    SAGE_ERR_ARG = -1,      /* bad argument (null pointer, size out of range) */
+    SAGE_ERR_STATE = -2,    /* call not allowed in the context's current state */
+    SAGE_ERR_ALLOC = -3,    /* device or host allocation failed */
+    SAGE_ERR_HIP = -4,      /* a HIP runtime call or kernel launch failed */
+    SAGE_ERR_CAPACITY = -5  /* fixed-capacity store or output array too small */
+} sage_status;
+
+typedef struct {
+    int64_t rows_seen;   /* rows given to sage_fd_update so far */
+    int64_t n_shrinks;   /* shrink steps performed */
+    int64_t n_scored;    /* rows given to sage_score since the last sage_fd_basis / sage_set_basis */
+    double sum_delta;    /* sum of the delta of every shrink: upper bound on ||A^T A - B^T B||_2 */
+    double frob2;        /* ||A||_F^2 of the rows seen, fp32 products accumulated in fp32/fp64 */
+    double last_delta;   /* delta of the most recent shrink */
+    int last_sweeps;     /* Jacobi sweeps used by the most recent eigensolve */
+    int fill;            /* buffer rows in use, 0..2*ell-1 */
+} sage_stats_t;
+
+/* ---- the five calls of the path --------------------------------------------------------------------------- */
+
+/*
+ * Create a context for an FD sketch of fp32 rows on the default stream: a zeroed buffer of 2*ell rows by D
+ * columns, fill pointer 0 (Algorithm 1, "Initialize S <- 0, row counter r <- 0"; the buffer has 2*ell rows so
+ * that new rows only ever land in zero rows, Liberty's form of FD).
+ * out: HOST pointer receiving the handle. 2 <= ell <= 256, D >= 1. Device memory: about 2*ell*D*4 bytes for the
+ * sketch plus work space; SAGE_ERR_ALLOC if it does not fit.
+ */
+int sage_fd_create(sage_ctx** out, int ell, int64_t D);
+
+/*
+ * As above with the row type, a score-store capacity and a stream. max_rows > 0 fixes the number of rows one
+ * scoring pass may hold (sage_score returns SAGE_ERR_CAPACITY beyond it); 0 lets the store grow by doubling.
+ * hip_stream: a hipStream_t passed as void* (NULL = default stream); it must outlive the context.
+ */
+int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, int64_t max_rows,
+                      void* hip_stream);
+
+/*
+ * Pass 1 (Algorithm 1, Phase I): append `rows` rows to the sketch. Each row is copied into the next free buffer
+ * row; whenever the buffer becomes full the shrink step runs: with sigma_j, v_j the singular values / right
+ * singular vectors of the buffer, delta = sigma_ell^2 and row j becomes sqrt(max(sigma_j^2 - delta, 0)) v_j^T
+ * (Method, FD paragraph). It is computed as: Gram C = B B^T (fp32 matrix cores, split over D, partial sums added
+ * in fp64) -> Jacobi eigensolve C = Y Lambda Y^T (fp64) -> B[0:ell] <- diag(w) Y^T B with
+ * w_j = sqrt(max(lambda_j - delta, 0) / lambda_j) (fp32 matrix cores), rows ell.. zeroed.
+ * G_batch: DEVICE, rows x D of the context's dtype. rows >= 0 (0 is a no-op). Asynchronous on the context's
+ * stream. Invalidates a basis made earlier. The host never reads device data in this call.
+ */
+int sage_fd_update(sage_ctx* ctx, const void* G_batch, int64_t rows);
+
+/*
+ * Freeze the sketch (Algorithm 1, "Freeze S for scoring") and form the scoring basis: the top-k right singular
+ * vectors of the buffer as it stands (filled rows and zero rows; no shrink; the sketch is left unchanged).
+ * A direction whose sigma_j^2 <= 2*ell * 2^-23 * sigma_1^2 is returned as the zero vector. 1 <= k <= ell-1.
+ * Resets the scoring pass (row count, consensus sum, score store). Asynchronous.
+ */
+int sage_fd_basis(sage_ctx* ctx, int k);
+
+/*
+ * Pass 2 (Algorithm 1, Phase II, first line): for each row g of the batch z = V_k^T g, zhat = z/||z||_2 (0 if
+ * z = 0); zhat is stored at the row's example index and added to the consensus sum.
+ * G_batch: DEVICE, rows x D of the context's dtype. Needs a basis (else SAGE_ERR_STATE). Asynchronous.
+ */
+int sage_score(sage_ctx* ctx, const void* G_batch, int64_t rows);
+
+/*
+ * Finish pass 2 (Algorithm 1, Phase II: "zbar", "u", "alpha_i", "Select top-k by alpha_i"): u = sum(zhat) /
+ * ||sum(zhat)||_2 (0 if the sum is 0; the 1/N factor cancels), alpha_i = <zhat_i, u> clamped to [-1, 1] with -0
+ * stored as +0, m = floor(keep_rate*N + 0.5) clipped to [0, N], and the m indices that are greatest under
+ * (alpha descending, index ascending) are written in ascending index order.
+ * keep_rate in [0, 1]. out_idx: DEVICE, room for `cap` int64 (SAGE_ERR_CAPACITY if m > cap; may be NULL when
+ * cap = 0 and m = 0). out_m: HOST, receives m. Waits for the stream. May be called again (e.g. another rate).
+ */
+int sage_select(sage_ctx* ctx, double keep_rate, int64_t* out_idx, int64_t cap, int64_t* out_m);
+
+/* Release the context and everything it owns (waits for its stream). NULL is allowed. */
+void sage_destroy(sage_ctx* ctx);
+
+/* ---- auxiliaries for tests, harnesses and callers that need the intermediate results ---------------------- */
+
+/* Wait until all work enqueued by this context has completed. */
+int sage_sync(sage_ctx* ctx);
+
+/*
+ * Copy the sketch buffer to B_out as a plain row-major (2*ell) x D fp32 matrix (the library keeps it in a
+ * column-slab layout internally). B_out: DEVICE, 2*ell*D floats. Rows >= fill are zero. Waits for the stream.
+ */
+int sage_fd_sketch_export(sage_ctx* ctx, float* B_out);
+
+/* Copy the scoring basis to Vt_out, row-major k x D fp32, row j = v_j^T. Vt_out: DEVICE. Needs a basis. Waits. */
+int sage_basis_export(sage_ctx* ctx, float* Vt_out);
+
+/*
+ * Install a basis given by the caller instead of the sketch's (stage-isolated tests; also lets a caller score
+ * against a basis saved earlier). Vt: DEVICE, row-major k x D fp32, 1 <= k <= 128. Resets the scoring pass.
+ */
+int sage_set_basis(sage_ctx* ctx, const float* Vt, int k);
+
+/* View of the scores of the last sage_select: *alpha receives a DEVICE pointer to N fp32 owned by the library,
+ * valid until the next scoring call; *n receives N. HOST pointers. */
+int sage_scores(sage_ctx* ctx, const float** alpha, int64_t* n);
+
+/* Copy the scores of the last sage_select (N fp32) to alpha_out (DEVICE, N floats). Waits. */
+int sage_scores_export(sage_ctx* ctx, float* alpha_out);
+
+/* Copy the stored normalised projections of the current scoring pass (N x k fp32 row-major) to zhat_out
+ * (DEVICE, N*k floats). Waits. */
+int sage_zhat_export(sage_ctx* ctx, float* zhat_out);
+
+/* Counters of the context (HOST struct). Waits for the stream. */
+int sage_stats(sage_ctx* ctx, sage_stats_t* out);
+
+/*
+ * Stand-alone top-m (Algorithm 1, "Select top-k by alpha_i") of any fp32 score vector: the m indices greatest
+ * under (alpha descending, index ascending), written ascending. alpha: DEVICE, N floats (NaN not allowed);
+ * out_idx: DEVICE, m int64; 0 <= m <= N; hip_stream as in sage_fd_create_ex. Allocates and frees its own work
+ * space; returns after the result is complete.
+ */
+int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* hip_stream);
+
+/*
+ * Stage probes for tests: run the Gram of the current buffer (C_out: DEVICE, n_pad*n_pad doubles, row-major,
+ * n_pad returned in *n_pad) and, if eig != 0, the Jacobi eigensolve of it (Y_out: DEVICE n_pad*n_pad doubles
+ * with eigenvectors in columns, lam_out: DEVICE n_pad doubles, unsorted). Any output pointer may be NULL.
+ * The sketch is not modified. Waits.
+ */
+int sage_probe_gram_eig(sage_ctx* ctx, double* C_out, int eig, double* Y_out, double* lam_out, int* n_pad);
+
+/*
+ * Per-kernel timing for harnesses: when enabled, every kernel launch is bracketed by HIP events on the
+ * context's stream (this serialises host and device, so whole-call timings taken while it is on are not
+ * representative). sage_profile_read waits, then reports the accumulated milliseconds and launch count of
+ * the kernel class `which` (0 gram, 1 gram reduce, 2 eigensolve, 3 coefficients, 4 rebuild/basis, 5 insert,
+ * 6 project, 7 score finalise, 8 select) and clears that class.
+ */
+int sage_profile_enable(sage_ctx* ctx, int on);
+int sage_profile_read(sage_ctx* ctx, int which, double* ms, int64_t* launches);
+
+/* Static description of a status code (HOST string, never NULL). */
+const char* sage_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGE_H */

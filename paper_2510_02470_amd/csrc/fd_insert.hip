@@ -1,0 +1,91 @@
+// Row movement between the caller's row-major batches and the library's column-slab layout.
+// Algorithm 1, Phase I, "S[r mod ell, :] <- g": a row is placed into a free (zero) buffer row.
+#include "sage_internal.h"
+
+namespace sage {
+
+// One thread moves one 16-byte piece (4 columns) of one row. grid = (ceil(4*S / 256), rows).
+// Columns >= D are written as zero so that padding never carries data.
+template <typename T>
+__global__ __launch_bounds__(256) void insert_kernel(const T* __restrict__ G, int row0, float* __restrict__ B,
+                                                     int NP, int64_t D, int64_t S) {
+    int64_t piece = (int64_t)blockIdx.x * 256 + threadIdx.x;  // piece index along the row
+    if (piece >= S * 4) return;
+    int64_t r = blockIdx.y;
+    int64_t d0 = piece * 4;
+    const T* g = G + r * D + d0;
+    float v[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float x = 0.f;
+        if (d0 + c < D) {
+            if constexpr (sizeof(T) == 2) x = bf16_to_f32(g[c]);
+            else x = g[c];
+        }
+        v[c] = x;
+    }
+    float4* dst = reinterpret_cast<float4*>(B + blk_off(d0, row0 + (int)r, NP));
+    *dst = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* B, const Dims& d, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    dim3 grid((unsigned)((d.S * 4 + 255) / 256), (unsigned)rows);
+    if (dtype == SAGE_BF16)
+        hipLaunchKernelGGL(insert_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)G, row0, B, d.NP, d.D, d.S);
+    else
+        hipLaunchKernelGGL(insert_kernel<float>, grid, dim3(256), 0, st, (const float*)G, row0, B, d.NP, d.D, d.S);
+    return hipGetLastError();
+}
+
+// slab layout (NPsrc rows) -> row-major nrows x D
+__global__ __launch_bounds__(256) void export_kernel(const float* __restrict__ Bblk, int NPsrc, float* __restrict__ out,
+                                                     int64_t D) {
+    int64_t dcol = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (dcol >= D) return;
+    int r = blockIdx.y;
+    out[(int64_t)r * D + dcol] = Bblk[blk_off(dcol, r, NPsrc)];
+}
+
+hipError_t launch_export_rows(const float* Bblk, int NPsrc, int nrows, float* out, const Dims& d, hipStream_t st) {
+    if (nrows <= 0) return hipSuccess;
+    dim3 grid((unsigned)((d.D + 255) / 256), (unsigned)nrows);
+    hipLaunchKernelGGL(export_kernel, grid, dim3(256), 0, st, Bblk, NPsrc, out, d.D);
+    return hipGetLastError();
+}
+
+// row-major nrows x D -> slab layout with NPdst rows; rows nrows..NPdst-1 and columns >= D are zeroed.
+__global__ __launch_bounds__(256) void import_kernel(const float* __restrict__ in, int nrows, float* __restrict__ Bblk,
+                                                     int NPdst, int64_t D, int64_t Dp) {
+    int64_t dcol = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (dcol >= Dp) return;
+    int r = blockIdx.y;
+    float v = (r < nrows && dcol < D) ? in[(int64_t)r * D + dcol] : 0.f;
+    Bblk[blk_off(dcol, r, NPdst)] = v;
+}
+
+hipError_t launch_import_rows(const float* in, int nrows, float* Bblk, int NPdst, const Dims& d, hipStream_t st) {
+    dim3 grid((unsigned)((d.Dp + 255) / 256), (unsigned)NPdst);
+    hipLaunchKernelGGL(import_kernel, grid, dim3(256), 0, st, in, nrows, Bblk, NPdst, d.D, d.Dp);
+    return hipGetLastError();
+}
+
+// zero buffer rows [r0, r1) in every slab
+__global__ __launch_bounds__(256) void zero_rows_kernel(float* __restrict__ Bblk, int NP, int r0, int r1, int64_t S) {
+    int per_slab = (r1 - r0) * 4;  // float4 pieces per slab
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= S * per_slab) return;
+    int64_t s = i / per_slab;
+    int rem = (int)(i % per_slab);
+    float4* p = reinterpret_cast<float4*>(Bblk + (s * NP + r0) * DC) + rem;
+    *p = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+hipError_t launch_zero_rows(float* Bblk, int NP, int r0, int r1, const Dims& d, hipStream_t st) {
+    if (r1 <= r0) return hipSuccess;
+    int64_t total = d.S * (int64_t)(r1 - r0) * 4;
+    hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, Bblk, NP, r0, r1, d.S);
+    return hipGetLastError();
+}
+
+}  // namespace sage

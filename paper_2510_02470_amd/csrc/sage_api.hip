@@ -1,0 +1,533 @@
+// C ABI of the SAGE hot-path library: context, state machine and kernel sequencing. See include/sage.h.
+#include <math.h>
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+
+#include "sage_internal.h"
+
+using namespace sage;
+
+namespace {
+
+constexpr int NCLASS = 9;
+constexpr int64_t SCORE_CHUNK = 2048;  // rows per projection launch
+enum { K_GRAM = 0, K_REDUCE, K_EIG, K_COEFF, K_REBUILD, K_INSERT, K_PROJECT, K_FINALIZE, K_SELECT };
+
+}  // namespace
+
+struct sage_ctx {
+    Dims d{};
+    int dtype = SAGE_F32;
+    hipStream_t st = nullptr;
+    int num_cu = 256;
+
+    float* B = nullptr;
+    GramPlan gp{};
+    float* gram_partial = nullptr;
+    EigWork ew{};
+    float* Mt = nullptr;
+    double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps
+
+    int fill = 0;
+    int counted_base = 0;  // buffer rows [counted_base, fill) are not yet in frob2
+    int64_t rows_seen = 0, n_shrinks = 0;
+
+    bool has_basis = false;
+    int k = 0, KP = 0;
+    float* Vblk = nullptr;
+    int Vblk_KP = 0;
+    float* zhat = nullptr;
+    int64_t cap_rows = 0, n_scored = 0;
+    bool fixed_cap = false;
+    float* proj_partial = nullptr;
+    size_t proj_partial_floats = 0;
+    double* cons_partial = nullptr;
+    double* ssum = nullptr;
+    float* alpha = nullptr;
+    int64_t alpha_cap = 0, alpha_n = 0;
+    SelectWork sw{};
+
+    bool prof = false;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    double prof_ms[NCLASS] = {0};
+    int64_t prof_n[NCLASS] = {0};
+};
+
+namespace {
+
+#define HIPCHK(expr)                                 \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) return SAGE_ERR_HIP;   \
+    } while (0)
+
+#define ALLOC(ptr, bytes)                                                  \
+    do {                                                                   \
+        if (hipMalloc((void**)&(ptr), (bytes)) != hipSuccess) {            \
+            (void)hipGetLastError();                                       \
+            return SAGE_ERR_ALLOC;                                         \
+        }                                                                  \
+    } while (0)
+
+// run a launcher, optionally bracketed by events of kernel class `cls`
+template <typename F>
+int run(sage_ctx* c, int cls, F&& f) {
+    if (c->prof) HIPCHK(hipEventRecord(c->ev0, c->st));
+    HIPCHK(f());
+    if (c->prof) {
+        HIPCHK(hipEventRecord(c->ev1, c->st));
+        HIPCHK(hipEventSynchronize(c->ev1));
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, c->ev0, c->ev1));
+        c->prof_ms[cls] += ms;
+        c->prof_n[cls] += 1;
+    }
+    return SAGE_OK;
+}
+
+#define RUN(cls, call)                                         \
+    do {                                                       \
+        int rc_ = run(c, cls, [&]() -> hipError_t { return (call); }); \
+        if (rc_ != SAGE_OK) return rc_;                        \
+    } while (0)
+
+int pad_pow2_32(int v) {
+    int p = 32;
+    while (p < v) p *= 2;
+    return p;
+}
+
+int decompose(sage_ctx* c) {
+    RUN(K_GRAM, launch_gram(c->B, c->gram_partial, c->gp, c->d, c->st));
+    RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->ew.C, c->gp, c->d, c->st));
+    RUN(K_EIG, launch_eig(c->ew, c->d.NP, c->st));
+    return SAGE_OK;
+}
+
+int shrink(sage_ctx* c) {
+    int rc = decompose(c);
+    if (rc != SAGE_OK) return rc;
+    RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, c->d.LP, c->d.ell, c->counted_base, c->d.n, c->Mt, c->acc, c->st));
+    RUN(K_REBUILD, launch_rebuild(c->B, c->Mt, c->B, c->d.NP, c->d.LP, true, c->d, c->st));
+    c->fill = c->d.ell;
+    c->counted_base = c->d.ell;
+    c->n_shrinks += 1;
+    return SAGE_OK;
+}
+
+void reset_scoring(sage_ctx* c) {
+    c->n_scored = 0;
+    c->alpha_n = 0;
+}
+
+int ensure_score_buffers(sage_ctx* c) {
+    if (!c->ssum) ALLOC(c->ssum, 128 * sizeof(double));
+    if (!c->cons_partial) ALLOC(c->cons_partial, (size_t)(SCORE_CHUNK / 16) * 128 * sizeof(double));
+    if (!c->zhat) {
+        ALLOC(c->zhat, (size_t)c->cap_rows * 128 * sizeof(float));
+    }
+    HIPCHK(hipMemsetAsync(c->ssum, 0, 128 * sizeof(double), c->st));
+    return SAGE_OK;
+}
+
+int ensure_vblk(sage_ctx* c, int KP) {
+    if (c->Vblk && c->Vblk_KP == KP) return SAGE_OK;
+    if (c->Vblk) {
+        HIPCHK(hipStreamSynchronize(c->st));
+        HIPCHK(hipFree(c->Vblk));
+        c->Vblk = nullptr;
+    }
+    ALLOC(c->Vblk, (size_t)c->d.S * KP * DC * sizeof(float));
+    c->Vblk_KP = KP;
+    return SAGE_OK;
+}
+
+int64_t keep_count(double keep_rate, int64_t N) {
+    double x = floor(keep_rate * (double)N + 0.5);
+    int64_t m = (int64_t)x;
+    if (m < 0) m = 0;
+    if (m > N) m = N;
+    return m;
+}
+
+int alloc_select_work(SelectWork& w, int64_t N) {
+    int64_t nblk = (N + SELECT_BLOCK - 1) / SELECT_BLOCK;
+    if (nblk < 1) nblk = 1;
+    ALLOC(w.hist, 256 * sizeof(uint32_t));
+    ALLOC(w.state, 4 * sizeof(uint32_t));
+    ALLOC(w.blk_gt, (size_t)nblk * sizeof(uint32_t));
+    ALLOC(w.blk_eq, (size_t)nblk * sizeof(uint32_t));
+    w.nblk_cap = nblk;
+    return SAGE_OK;
+}
+
+void free_select_work(SelectWork& w) {
+    if (w.hist) (void)hipFree(w.hist);
+    if (w.state) (void)hipFree(w.state);
+    if (w.blk_gt) (void)hipFree(w.blk_gt);
+    if (w.blk_eq) (void)hipFree(w.blk_eq);
+    w = SelectWork{};
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sage_strerror(int code) {
+    switch (code) {
+        case SAGE_OK: return "ok";
+        case SAGE_ERR_ARG: return "bad argument";
+        case SAGE_ERR_STATE: return "call not allowed in this state";
+        case SAGE_ERR_ALLOC: return "allocation failed";
+        case SAGE_ERR_HIP: return "HIP runtime error";
+        case SAGE_ERR_CAPACITY: return "capacity exceeded";
+        default: return "unknown status";
+    }
+}
+
+int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, int64_t max_rows, void* hip_stream) {
+    if (!out) return SAGE_ERR_ARG;
+    *out = nullptr;
+    if (ell < 2 || ell > 256 || D < 1 || max_rows < 0) return SAGE_ERR_ARG;
+    if (in_dtype != SAGE_F32 && in_dtype != SAGE_BF16) return SAGE_ERR_ARG;
+    sage_ctx* c = new (std::nothrow) sage_ctx();
+    if (!c) return SAGE_ERR_ALLOC;
+    c->d.ell = ell;
+    c->d.n = 2 * ell;
+    c->d.LP = pad_pow2_32(ell);
+    c->d.NP = 2 * c->d.LP;
+    c->d.D = D;
+    c->d.S = (D + DC - 1) / DC;
+    c->d.Dp = c->d.S * DC;
+    c->dtype = in_dtype;
+    c->st = (hipStream_t)hip_stream;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        delete c;
+        return SAGE_ERR_HIP;
+    }
+    c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    c->gp = gram_plan(c->d, c->num_cu);
+    c->fixed_cap = max_rows > 0;
+    c->cap_rows = max_rows > 0 ? max_rows : 65536;
+
+    auto fail = [&](int rc) {
+        sage_destroy(c);
+        return rc;
+    };
+    const int NP = c->d.NP;
+    size_t bbytes = (size_t)c->d.S * NP * DC * sizeof(float);
+#define CALLOC(ptr, bytes)                                                        \
+    do {                                                                          \
+        if (hipMalloc((void**)&(ptr), (bytes)) != hipSuccess) {                   \
+            (void)hipGetLastError();                                              \
+            return fail(SAGE_ERR_ALLOC);                                          \
+        }                                                                         \
+    } while (0)
+    CALLOC(c->B, bbytes);
+    CALLOC(c->gram_partial, c->gp.partial_floats * sizeof(float));
+    CALLOC(c->ew.C, (size_t)NP * NP * sizeof(double));
+    CALLOC(c->ew.Y, (size_t)NP * NP * sizeof(double));
+    CALLOC(c->ew.Q, (size_t)(NP / 64) * 4096 * sizeof(double));
+    CALLOC(c->ew.diag0, (size_t)NP * sizeof(double));
+    CALLOC(c->ew.stat, 32 * sizeof(double));
+    CALLOC(c->ew.pos, (size_t)NP * sizeof(int));
+    CALLOC(c->ew.lam, (size_t)NP * sizeof(double));
+    CALLOC(c->Mt, (size_t)NP * c->d.LP * sizeof(float));
+    CALLOC(c->acc, 8 * sizeof(double));
+#undef CALLOC
+    if (hipMemsetAsync(c->B, 0, bbytes, c->st) != hipSuccess) return fail(SAGE_ERR_HIP);
+    if (hipMemsetAsync(c->acc, 0, 8 * sizeof(double), c->st) != hipSuccess) return fail(SAGE_ERR_HIP);
+    if (hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) return fail(SAGE_ERR_HIP);
+    *out = c;
+    return SAGE_OK;
+}
+
+int sage_fd_create(sage_ctx** out, int ell, int64_t D) { return sage_fd_create_ex(out, ell, D, SAGE_F32, 0, nullptr); }
+
+void sage_destroy(sage_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->st);
+    void* ptrs[] = {c->B,       c->gram_partial, c->ew.C, c->ew.Y,         c->ew.Q,         c->ew.diag0, c->ew.stat,
+                    c->ew.pos,  c->ew.lam,       c->Mt,   c->acc,          c->Vblk,         c->zhat,     c->proj_partial,
+                    c->cons_partial, c->ssum,    c->alpha};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    free_select_work(c->sw);
+    if (c->ev0) (void)hipEventDestroy(c->ev0);
+    if (c->ev1) (void)hipEventDestroy(c->ev1);
+    delete c;
+}
+
+int sage_sync(sage_ctx* c) {
+    if (!c) return SAGE_ERR_ARG;
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
+    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    if (rows == 0) return SAGE_OK;
+    c->has_basis = false;
+    const char* g = (const char*)G_batch;
+    const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
+    while (rows > 0) {
+        int take = (int)((int64_t)(c->d.n - c->fill) < rows ? (c->d.n - c->fill) : rows);
+        RUN(K_INSERT, launch_insert(g, c->dtype, take, c->fill, c->B, c->d, c->st));
+        c->fill += take;
+        c->rows_seen += take;
+        g += (size_t)take * c->d.D * esz;
+        rows -= take;
+        if (c->fill == c->d.n) {
+            int rc = shrink(c);
+            if (rc != SAGE_OK) return rc;
+        }
+    }
+    return SAGE_OK;
+}
+
+int sage_fd_basis(sage_ctx* c, int k) {
+    if (!c) return SAGE_ERR_ARG;
+    if (k < 1 || k > c->d.ell - 1 || k > 128) return SAGE_ERR_ARG;
+    const int KP = pad_pow2_32(k);
+    int rc = ensure_vblk(c, KP);
+    if (rc != SAGE_OK) return rc;
+    rc = decompose(c);
+    if (rc != SAGE_OK) return rc;
+    RUN(K_COEFF, launch_basis_coeffs(c->ew, c->d.NP, KP, k, c->d.n, c->counted_base, c->fill, c->Mt, c->acc, c->st));
+    c->counted_base = c->fill;
+    RUN(K_REBUILD, launch_rebuild(c->B, c->Mt, c->Vblk, KP, KP, false, c->d, c->st));
+    c->k = k;
+    c->KP = KP;
+    c->has_basis = true;
+    reset_scoring(c);
+    return ensure_score_buffers(c);
+}
+
+int sage_set_basis(sage_ctx* c, const float* Vt, int k) {
+    if (!c || !Vt || k < 1 || k > 128) return SAGE_ERR_ARG;
+    const int KP = pad_pow2_32(k);
+    int rc = ensure_vblk(c, KP);
+    if (rc != SAGE_OK) return rc;
+    HIPCHK(launch_import_rows(Vt, k, c->Vblk, KP, c->d, c->st));
+    c->k = k;
+    c->KP = KP;
+    c->has_basis = true;
+    reset_scoring(c);
+    return ensure_score_buffers(c);
+}
+
+int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) {
+    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    if (!c->has_basis) return SAGE_ERR_STATE;
+    if (rows == 0) return SAGE_OK;
+    if (c->n_scored + rows > c->cap_rows) {
+        if (c->fixed_cap) return SAGE_ERR_CAPACITY;
+        int64_t ncap = c->cap_rows;
+        while (ncap < c->n_scored + rows) ncap *= 2;
+        float* nz = nullptr;
+        ALLOC(nz, (size_t)ncap * 128 * sizeof(float));
+        if (hipMemcpyAsync(nz, c->zhat, (size_t)c->n_scored * c->k * sizeof(float), hipMemcpyDeviceToDevice, c->st) !=
+                hipSuccess ||
+            hipStreamSynchronize(c->st) != hipSuccess) {
+            (void)hipFree(nz);
+            return SAGE_ERR_HIP;
+        }
+        (void)hipFree(c->zhat);
+        c->zhat = nz;
+        c->cap_rows = ncap;
+    }
+    const char* g = (const char*)G_batch;
+    const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
+    while (rows > 0) {
+        int64_t R = rows < SCORE_CHUNK ? rows : SCORE_CHUNK;
+        ScorePlan p = score_plan(R, c->d, c->num_cu);
+        size_t need = (size_t)p.splits * R * c->KP;
+        if (need > c->proj_partial_floats) {
+            if (c->proj_partial) {
+                HIPCHK(hipStreamSynchronize(c->st));
+                (void)hipFree(c->proj_partial);
+                c->proj_partial = nullptr;
+                c->proj_partial_floats = 0;
+            }
+            size_t want = (size_t)512 * 128 * 128 > need ? (size_t)512 * 128 * 128 : need;
+            ALLOC(c->proj_partial, want * sizeof(float));
+            c->proj_partial_floats = want;
+        }
+        RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
+        RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, p.splits,
+                                             c->zhat + (size_t)c->n_scored * c->k, c->cons_partial, c->ssum, c->st));
+        c->n_scored += R;
+        g += (size_t)R * c->d.D * esz;
+        rows -= R;
+    }
+    c->alpha_n = 0;
+    return SAGE_OK;
+}
+
+int sage_select(sage_ctx* c, double keep_rate, int64_t* out_idx, int64_t cap, int64_t* out_m) {
+    if (!c || !out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0)) return SAGE_ERR_ARG;
+    if (!c->has_basis) return SAGE_ERR_STATE;
+    const int64_t N = c->n_scored;
+    const int64_t m = keep_count(keep_rate, N);
+    *out_m = m;
+    if (m > cap) return SAGE_ERR_CAPACITY;
+    if (m > 0 && !out_idx) return SAGE_ERR_ARG;
+    if (N > c->alpha_cap) {
+        if (c->alpha) {
+            HIPCHK(hipStreamSynchronize(c->st));
+            (void)hipFree(c->alpha);
+            c->alpha = nullptr;
+        }
+        free_select_work(c->sw);
+        int64_t ncap = N > c->cap_rows ? N : c->cap_rows;
+        ALLOC(c->alpha, (size_t)ncap * sizeof(float));
+        int rc = alloc_select_work(c->sw, ncap);
+        if (rc != SAGE_OK) return rc;
+        c->alpha_cap = ncap;
+    }
+    RUN(K_SELECT, launch_cosine(c->zhat, N, c->k, c->ssum, c->alpha, c->st));
+    c->alpha_n = N;
+    RUN(K_SELECT, launch_topm(c->alpha, N, m, out_idx, c->sw, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* hip_stream) {
+    if (N < 0 || m < 0 || m > N || (N > 0 && !alpha) || (m > 0 && !out_idx)) return SAGE_ERR_ARG;
+    if (m == 0) return SAGE_OK;
+    SelectWork w{};
+    int rc = alloc_select_work(w, N);
+    if (rc != SAGE_OK) {
+        free_select_work(w);
+        return rc;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = launch_topm(alpha, N, m, out_idx, w, st);
+    hipError_t e2 = hipStreamSynchronize(st);
+    free_select_work(w);
+    return (e == hipSuccess && e2 == hipSuccess) ? SAGE_OK : SAGE_ERR_HIP;
+}
+
+int sage_fd_sketch_export(sage_ctx* c, float* B_out) {
+    if (!c || !B_out) return SAGE_ERR_ARG;
+    HIPCHK(launch_export_rows(c->B, c->d.NP, c->d.n, B_out, c->d, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_basis_export(sage_ctx* c, float* Vt_out) {
+    if (!c || !Vt_out) return SAGE_ERR_ARG;
+    if (!c->has_basis) return SAGE_ERR_STATE;
+    HIPCHK(launch_export_rows(c->Vblk, c->KP, c->k, Vt_out, c->d, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_scores(sage_ctx* c, const float** alpha, int64_t* n) {
+    if (!c || !alpha || !n) return SAGE_ERR_ARG;
+    if (!c->has_basis || c->alpha_n != c->n_scored) return SAGE_ERR_STATE;
+    *alpha = c->alpha;
+    *n = c->alpha_n;
+    return SAGE_OK;
+}
+
+int sage_scores_export(sage_ctx* c, float* alpha_out) {
+    if (!c || (!alpha_out && c->n_scored > 0)) return SAGE_ERR_ARG;
+    if (!c->has_basis || c->alpha_n != c->n_scored) return SAGE_ERR_STATE;
+    if (c->alpha_n > 0)
+        HIPCHK(hipMemcpyAsync(alpha_out, c->alpha, (size_t)c->alpha_n * sizeof(float), hipMemcpyDeviceToDevice, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_zhat_export(sage_ctx* c, float* zhat_out) {
+    if (!c || (!zhat_out && c->n_scored > 0)) return SAGE_ERR_ARG;
+    if (!c->has_basis) return SAGE_ERR_STATE;
+    if (c->n_scored > 0)
+        HIPCHK(hipMemcpyAsync(zhat_out, c->zhat, (size_t)c->n_scored * c->k * sizeof(float), hipMemcpyDeviceToDevice,
+                              c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_stats(sage_ctx* c, sage_stats_t* out) {
+    if (!c || !out) return SAGE_ERR_ARG;
+    double acc[8];
+    HIPCHK(hipMemcpyAsync(acc, c->acc, sizeof(acc), hipMemcpyDeviceToHost, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    double pending = 0.0;
+    if (c->counted_base < c->fill) {
+        // rows inserted since the last decomposition: add their squared norms from a Gram of the buffer
+        int rc = SAGE_OK;
+        {
+            sage_ctx* cc = c;
+            (void)cc;
+            hipError_t e = launch_gram(c->B, c->gram_partial, c->gp, c->d, c->st);
+            if (e == hipSuccess) e = launch_gram_reduce(c->gram_partial, c->ew.C, c->gp, c->d, c->st);
+            if (e != hipSuccess) rc = SAGE_ERR_HIP;
+        }
+        if (rc != SAGE_OK) return rc;
+        const int NP = c->d.NP;
+        double* diag = (double*)malloc(sizeof(double) * NP);
+        if (!diag) return SAGE_ERR_ALLOC;
+        hipError_t e = hipMemcpy2DAsync(diag, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double),
+                                        NP, hipMemcpyDeviceToHost, c->st);
+        if (e == hipSuccess) e = hipStreamSynchronize(c->st);
+        if (e != hipSuccess) {
+            free(diag);
+            return SAGE_ERR_HIP;
+        }
+        for (int r = c->counted_base; r < c->fill; ++r) pending += diag[r];
+        free(diag);
+    }
+    out->rows_seen = c->rows_seen;
+    out->n_shrinks = c->n_shrinks;
+    out->n_scored = c->n_scored;
+    out->sum_delta = acc[0];
+    out->frob2 = acc[1] + pending;
+    out->last_delta = acc[2];
+    out->last_sweeps = (int)acc[3];
+    out->fill = c->fill;
+    return SAGE_OK;
+}
+
+int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, double* lam_out, int* n_pad) {
+    if (!c) return SAGE_ERR_ARG;
+    const int NP = c->d.NP;
+    if (n_pad) *n_pad = NP;
+    HIPCHK(launch_gram(c->B, c->gram_partial, c->gp, c->d, c->st));
+    HIPCHK(launch_gram_reduce(c->gram_partial, c->ew.C, c->gp, c->d, c->st));
+    if (C_out)
+        HIPCHK(hipMemcpyAsync(C_out, c->ew.C, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    if (eig) {
+        HIPCHK(launch_eig(c->ew, NP, c->st));
+        if (Y_out)
+            HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+        if (lam_out)
+            HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double),
+                                    NP, hipMemcpyDeviceToDevice, c->st));
+    }
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_profile_enable(sage_ctx* c, int on) {
+    if (!c) return SAGE_ERR_ARG;
+    c->prof = on != 0;
+    return SAGE_OK;
+}
+
+int sage_profile_read(sage_ctx* c, int which, double* ms, int64_t* launches) {
+    if (!c || which < 0 || which >= NCLASS || !ms || !launches) return SAGE_ERR_ARG;
+    HIPCHK(hipStreamSynchronize(c->st));
+    *ms = c->prof_ms[which];
+    *launches = c->prof_n[which];
+    c->prof_ms[which] = 0.0;
+    c->prof_n[which] = 0;
+    return SAGE_OK;
+}
+
+}  // extern "C"

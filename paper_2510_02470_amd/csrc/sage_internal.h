@@ -1,0 +1,110 @@
+// Internal declarations shared by the translation units of the SAGE HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sage.h"
+
+namespace sage {
+
+// ---- sketch / basis layout --------------------------------------------------------------------------------
+// The 2*ell x D buffer is kept as column slabs: element (row r, column d) lives at
+//     ((d / DC) * NP + r) * DC + d % DC
+// with DC = 16 floats (64 B) per row per slab and NP = padded row count. One slab (NP x 16 floats) is one
+// contiguous block, so the Gram kernel stages a slab with linear 1 KB wave loads, and the rebuild / basis
+// kernels read a 128 B line per buffer-row pair. Columns D..Dp-1 and rows beyond 2*ell are always zero.
+constexpr int DC = 16;
+
+struct Dims {
+    int ell;      // sketch size
+    int n;        // 2*ell buffer rows
+    int LP;       // ell padded to 32 * 2^j (32, 64, 128, 256)
+    int NP;       // 2*LP padded buffer rows (64 .. 512)
+    int64_t D;    // columns
+    int64_t S;    // slabs = ceil(D / DC)
+    int64_t Dp;   // S * DC
+};
+
+__host__ __device__ inline int64_t blk_off(int64_t d, int r, int NP) {
+    return ((d / DC) * NP + r) * (int64_t)DC + (d % DC);
+}
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));  // indexable 16-byte piece
+
+// fp32 matrix-core step: acc(32x32) += a(32x2) * b(2x32). Lane l supplies a[l%32][l/32] and b[l/32][l%32];
+// acc element i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 acc) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// ---- kernel launchers (each enqueues on `st` and returns hipGetLastError()) ---------------------------------
+// fd_insert.hip
+hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* B, const Dims& d, hipStream_t st);
+hipError_t launch_export_rows(const float* Bblk, int NPsrc, int nrows, float* out, const Dims& d, hipStream_t st);
+hipError_t launch_import_rows(const float* in, int nrows, float* Bblk, int NPdst, const Dims& d, hipStream_t st);
+hipError_t launch_zero_rows(float* Bblk, int NP, int r0, int r1, const Dims& d, hipStream_t st);
+
+// fd_gram.hip
+struct GramPlan {
+    int tiles;        // 64x64 lower-triangle tiles = P(P+1)/2, P = NP/64
+    int wg_per_group; // ceil(tiles / 12)
+    int groups;       // split-K groups (multiple of 8)
+    int64_t slabs_per_group;
+    size_t partial_floats; // groups * tiles * 4096
+};
+GramPlan gram_plan(const Dims& d, int num_cu);
+hipError_t launch_gram(const float* B, float* partial, const GramPlan& p, const Dims& d, hipStream_t st);
+hipError_t launch_gram_reduce(const float* partial, double* C, const GramPlan& p, const Dims& d, hipStream_t st);
+
+// fd_eig.hip
+struct EigWork {
+    double* C;      // NP x NP, destroyed (becomes near-diagonal)
+    double* Y;      // NP x NP eigenvectors in columns
+    double* Q;      // (NP/64) x 64 x 64 rotation blocks of the current step
+    double* diag0;  // NP: diagonal of C before the solve
+    double* stat;   // [0] trace, [1..MAXSWEEP] per-sweep max |off| / trace
+    int* pos;       // NP: pos[rank] = column of Y holding the rank-th largest eigenvalue
+    double* lam;    // NP: eigenvalues sorted descending
+};
+constexpr int MAX_SWEEPS = 16;
+hipError_t launch_eig(const EigWork& w, int NP, hipStream_t st);
+// scalars on device: acc[0] sum_delta, acc[1] frob2, acc[2] last_delta, acc[3] sweeps used (as double)
+hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int frob_r0, int frob_r1, float* Mt,
+                                double* acc, hipStream_t st);
+hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int frob_r0, int frob_r1, float* Mt,
+                               double* acc, hipStream_t st);
+
+// fd_rebuild.hip: out[0:MP] = M * B over every column; Mt is NP x MP (transposed coefficients).
+// zero_tail: also clear buffer rows MP..NP-1 (shrink). out may alias B (in place) when out_NP == NP.
+hipError_t launch_rebuild(const float* B, const float* Mt, float* out, int out_NP, int MP, bool zero_tail,
+                          const Dims& d, hipStream_t st);
+
+// score.hip
+struct ScorePlan {
+    int row_tiles;    // ceil(R / 128)
+    int splits;       // split-K over D
+    int64_t slabs_per_split;
+};
+ScorePlan score_plan(int64_t R, const Dims& d, int num_cu);
+hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk, int KP, float* partial,
+                          const ScorePlan& p, const Dims& d, hipStream_t st);
+hipError_t launch_score_finalize(const float* partial, int64_t R, int KP, int k, int splits, float* zhat_out,
+                                 double* cons_partial, double* ssum, hipStream_t st);
+
+// select.hip
+hipError_t launch_cosine(const float* zhat, int64_t N, int k, const double* ssum, float* alpha, hipStream_t st);
+struct SelectWork {
+    uint32_t* hist;      // 256 bins
+    uint32_t* state;     // [0] prefix key, [1] remaining m, [2] count greater, [3] ties to take
+    uint32_t* blk_gt;    // per block: count of keys > threshold
+    uint32_t* blk_eq;    // per block: count of keys == threshold
+    int64_t nblk_cap;
+};
+constexpr int SELECT_BLOCK = 2048;  // keys per block in the compaction passes
+hipError_t launch_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, const SelectWork& w,
+                       hipStream_t st);
+
+}  // namespace sage

@@ -1,0 +1,249 @@
+// Scoring pass, first half (Algorithm 1, Phase II, first line; Method, "Two-pass scoring"):
+//   z_i = V_k^T g_i  (fp32 matrix cores, split over D),  zhat_i = z_i / ||z_i||_2 (0 if z_i = 0),
+//   consensus sum  s += sum_i zhat_i  (fixed-order reductions, fp64).
+#include "sage_internal.h"
+
+namespace sage {
+
+// load one 16-byte-wide piece (4 columns) of a batch row, widened to fp32; columns >= D read as 0
+template <typename T, bool VEC>
+__device__ __forceinline__ f32x4 load_piece(const T* __restrict__ row, int64_t d0, int64_t D) {
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (VEC) {
+        if (d0 < D) {  // D % 4 == 0 on this path
+            if constexpr (sizeof(T) == 4) {
+                v = *reinterpret_cast<const f32x4*>(row + d0);
+            } else {
+                uint2 u = *reinterpret_cast<const uint2*>(row + d0);
+                v[0] = __uint_as_float(u.x << 16);
+                v[1] = __uint_as_float(u.x & 0xffff0000u);
+                v[2] = __uint_as_float(u.y << 16);
+                v[3] = __uint_as_float(u.y & 0xffff0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float x = 0.f;
+            if (d0 + c < D) {
+                if constexpr (sizeof(T) == 4) x = row[d0 + c];
+                else x = bf16_to_f32(row[d0 + c]);
+            }
+            v[c] = x;
+        }
+    }
+    return v;
+}
+
+// Work-group tile: 128 batch rows x KP basis columns, a wave owns 32 rows. Split-K over D: block id ->
+// (row tile, split) with the row tiles of one split adjacent on one XCD so that they share the basis slabs in L2.
+// partial[split][row][KP] receives the fp32 partial projections.
+template <int NT, typename T, bool VEC>  // NT = KP / 32
+__global__ __launch_bounds__(256) void project_kernel(const T* __restrict__ G, int64_t R, const float* __restrict__ Vblk,
+                                                      float* __restrict__ partial, int row_tiles, int64_t D,
+                                                      int64_t slabs_total, int64_t slabs_per_split) {
+    constexpr int KP = NT * 32;
+    constexpr int GP = 128 * 4;       // batch pieces per stage
+    constexpr int VP = KP * 4;        // basis pieces per stage
+    constexpr int STAGE = GP + VP;
+    constexpr int VPER = (VP + 255) / 256;
+    __shared__ f32x4 lds[2 * STAGE];
+
+    const int id = blockIdx.x;
+    const int xcd = id & 7, y = id >> 3;
+    const int rt = y % row_tiles;
+    const int split = (y / row_tiles) * 8 + xcd;
+    int64_t s0 = (int64_t)split * slabs_per_split;
+    int64_t s1 = s0 + slabs_per_split;
+    if (s1 > slabs_total) s1 = slabs_total;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int64_t row_base = (int64_t)rt * 128;
+
+    f32x16 acc[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+
+    // staging slots: batch piece slot ps -> (row ps/4, logical piece (ps%4)^((row/4)%4)); same for the basis
+    int grow[2], gp[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        int ps = it * 256 + tid;
+        grow[it] = ps >> 2;
+        gp[it] = (ps & 3) ^ ((grow[it] >> 2) & 3);
+    }
+    int vsrc[VPER];
+#pragma unroll
+    for (int it = 0; it < VPER; ++it) {
+        int ps = it * 256 + tid;
+        int row = ps >> 2;
+        vsrc[it] = row * 4 + ((ps & 3) ^ ((row >> 2) & 3));
+    }
+    const f32x4* Vv = reinterpret_cast<const f32x4*>(Vblk);
+    f32x4 gpre[2], vpre[VPER];
+
+    auto fetch = [&](int64_t s) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            int64_t r = row_base + grow[it];
+            gpre[it] = (r < R) ? load_piece<T, VEC>(G + r * D, s * DC + gp[it] * 4, D) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int it = 0; it < VPER; ++it)
+            if (it * 256 + tid < VP) vpre[it] = Vv[s * VP + vsrc[it]];
+    };
+    auto stash = [&](int buf) {
+        f32x4* dst = lds + buf * STAGE;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) dst[it * 256 + tid] = gpre[it];
+#pragma unroll
+        for (int it = 0; it < VPER; ++it)
+            if (it * 256 + tid < VP) dst[GP + it * 256 + tid] = vpre[it];
+    };
+
+    if (s0 < s1) {
+        fetch(s0);
+        stash(0);
+    }
+    __syncthreads();
+    for (int64_t s = s0; s < s1; ++s) {
+        const int cur = (int)((s - s0) & 1);
+        const bool more = s + 1 < s1;
+        if (more) fetch(s + 1);
+        const f32x4* gs = lds + cur * STAGE;
+        const f32x4* vs = gs + GP;
+        f32x4 a[2];
+        {
+            int r = wave * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) a[j] = gs[r * 4 + ((2 * j + h) ^ ((r >> 2) & 3))];
+        }
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            int r = n * 32 + l32;
+            f32x4 b[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = vs[r * 4 + ((2 * j + h) ^ ((r >> 2) & 3))];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    acc[n] = mfma32(a[j][c], b[j][c], acc[n]);
+        }
+        if (more) stash(cur ^ 1);
+        __syncthreads();
+    }
+
+    float* out = partial + (int64_t)split * R * KP;
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            int64_t r = row_base + wave * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+            if (r < R) out[r * KP + n * 32 + l32] = acc[n][i];
+        }
+}
+
+// 16 rows per work-group, one wave per row at a time; lane j holds coordinates j and j + 64.
+// Writes zhat (R x k, fp32) and cons_partial[block][128] (fp64 sums of the block's zhat).
+__global__ __launch_bounds__(256) void score_finalize_kernel(const float* __restrict__ partial, int64_t R, int KP, int k,
+                                                             int splits, float* __restrict__ zhat,
+                                                             double* __restrict__ cons_partial) {
+    __shared__ double red[4][128];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    double cons0 = 0.0, cons1 = 0.0;
+    for (int q = 0; q < 4; ++q) {
+        int64_t r = (int64_t)blockIdx.x * 16 + wave * 4 + q;
+        if (r >= R) break;
+        double z0 = 0.0, z1 = 0.0;
+        for (int s = 0; s < splits; ++s) {
+            const float* p = partial + ((int64_t)s * R + r) * KP;
+            if (lane < k) z0 += (double)p[lane];
+            if (lane + 64 < k) z1 += (double)p[lane + 64];
+        }
+        double q2 = z0 * z0 + z1 * z1;
+        for (int o = 32; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
+        double nrm = sqrt(q2);
+        float h0 = 0.f, h1 = 0.f;
+        if (nrm > 0.0) {
+            h0 = (float)(z0 / nrm);
+            h1 = (float)(z1 / nrm);
+        }
+        if (lane < k) zhat[r * k + lane] = h0;
+        if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
+        cons0 += (double)h0;
+        cons1 += (double)h1;
+    }
+    red[wave][lane] = cons0;
+    red[wave][lane + 64] = cons1;
+    __syncthreads();
+    if (tid < 128) {
+        double s = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+        cons_partial[(int64_t)blockIdx.x * 128 + tid] = s;
+    }
+}
+
+__global__ __launch_bounds__(128) void consensus_add_kernel(const double* __restrict__ cons_partial, int nblocks, int k,
+                                                            double* __restrict__ ssum) {
+    int j = threadIdx.x;
+    if (j >= k) return;
+    double s = 0.0;
+    for (int b = 0; b < nblocks; ++b) s += cons_partial[(int64_t)b * 128 + j];
+    ssum[j] += s;
+}
+
+ScorePlan score_plan(int64_t R, const Dims& d, int num_cu) {
+    ScorePlan p;
+    p.row_tiles = (int)((R + 127) / 128);
+    int64_t want = ((int64_t)num_cu * 2 + p.row_tiles - 1) / p.row_tiles;
+    int64_t s = (want + 7) / 8 * 8;
+    int64_t smax = ((d.S + 3) / 4 + 7) / 8 * 8;  // at least ~4 slabs per split
+    if (s > smax) s = smax;
+    if (s < 8) s = 8;
+    if (s > 512) s = 512;
+    p.splits = (int)s;
+    p.slabs_per_split = (d.S + s - 1) / s;
+    return p;
+}
+
+template <int NT>
+static hipError_t launch_project_nt(const void* G, int dtype, bool vec, int64_t R, const float* Vblk, float* partial,
+                                    const ScorePlan& p, const Dims& d, hipStream_t st) {
+    dim3 grid((unsigned)(p.row_tiles * p.splits));
+#define SAGE_PROJ(TT, VV)                                                                                          \
+    hipLaunchKernelGGL((project_kernel<NT, TT, VV>), grid, dim3(256), 0, st, (const TT*)G, R, Vblk, partial,       \
+                       p.row_tiles, d.D, d.S, p.slabs_per_split)
+    if (dtype == SAGE_BF16) {
+        if (vec) SAGE_PROJ(uint16_t, true); else SAGE_PROJ(uint16_t, false);
+    } else {
+        if (vec) SAGE_PROJ(float, true); else SAGE_PROJ(float, false);
+    }
+#undef SAGE_PROJ
+    return hipGetLastError();
+}
+
+hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk, int KP, float* partial,
+                          const ScorePlan& p, const Dims& d, hipStream_t st) {
+    size_t esz = dtype == SAGE_BF16 ? 2 : 4;
+    bool vec = (d.D % 4 == 0) && (((uintptr_t)G) % (4 * esz) == 0);
+    switch (KP / 32) {
+        case 1: return launch_project_nt<1>(G, dtype, vec, R, Vblk, partial, p, d, st);
+        case 2: return launch_project_nt<2>(G, dtype, vec, R, Vblk, partial, p, d, st);
+        case 4: return launch_project_nt<4>(G, dtype, vec, R, Vblk, partial, p, d, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_score_finalize(const float* partial, int64_t R, int KP, int k, int splits, float* zhat_out,
+                                 double* cons_partial, double* ssum, hipStream_t st) {
+    int nblocks = (int)((R + 15) / 16);
+    hipLaunchKernelGGL(score_finalize_kernel, dim3(nblocks), dim3(256), 0, st, partial, R, KP, k, splits, zhat_out,
+                       cons_partial);
+    hipLaunchKernelGGL(consensus_add_kernel, dim3(1), dim3(128), 0, st, cons_partial, nblocks, k, ssum);
+    return hipGetLastError();
+}
+
+}  // namespace sage
