@@ -166,6 +166,14 @@ int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* 
 int sage_probe_gram_eig(sage_ctx* ctx, double* C_out, int eig, double* Y_out, double* lam_out, int* n_pad);
 
 /*
+ * Stage probe: run the context's Jacobi eigensolve on a symmetric matrix given by the caller. C_in: DEVICE,
+ * n_pad*n_pad doubles (n_pad as reported by sage_probe_gram_eig), left untouched. Y_out, lam_out as above.
+ * sweep_stat_out: DEVICE, 18 doubles: [0] trace, [1+s] largest |off-diagonal| / trace met in sweep s (0 for
+ * sweeps that were skipped), [17] unused. Outputs may be NULL. The sketch is not modified. Waits.
+ */
+int sage_probe_eig_matrix(sage_ctx* ctx, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out);
+
+/*
  * Per-kernel timing for harnesses: when enabled, every kernel launch is bracketed by HIP events on the
  * context's stream (this serialises host and device, so whole-call timings taken while it is on are not
  * representative). sage_profile_read waits, then reports the accumulated milliseconds and launch count of

@@ -19,7 +19,8 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 EXPORTS = (
     "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_basis", "sage_score", "sage_select",
     "sage_destroy", "sage_sync", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
-    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_profile_enable",
+    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix",
+    "sage_profile_enable",
     "sage_profile_read", "sage_strerror",
 )
 
@@ -66,6 +67,7 @@ def lib():
     L.sage_stats.argtypes = [vp, C.POINTER(SageStats)]
     L.sage_topm.argtypes = [vp, i64, i64, vp, vp]
     L.sage_probe_gram_eig.argtypes = [vp, vp, i32, vp, vp, C.POINTER(i32)]
+    L.sage_probe_eig_matrix.argtypes = [vp, vp, vp, vp, vp]
     L.sage_profile_enable.argtypes = [vp, i32]
     L.sage_profile_read.argtypes = [vp, i32, C.POINTER(dbl), C.POINTER(i64)]
     L.sage_strerror.argtypes = [i32]
@@ -186,6 +188,15 @@ class Sage:
         _check(self.L.sage_probe_gram_eig(self.h, _ptr(Cm), 1 if eig else 0, _ptr(Y), _ptr(lam), C.byref(npad)),
                "sage_probe_gram_eig")
         return Cm, Y, lam
+
+    def probe_eig_matrix(self, Cm):
+        n = Cm.shape[0]
+        assert Cm.is_cuda and Cm.dtype == self.torch.float64 and Cm.is_contiguous()
+        Y = self.torch.empty((n, n), dtype=self.torch.float64, device="cuda")
+        lam = self.torch.empty((n,), dtype=self.torch.float64, device="cuda")
+        stat = self.torch.empty((18,), dtype=self.torch.float64, device="cuda")
+        _check(self.L.sage_probe_eig_matrix(self.h, _ptr(Cm), _ptr(Y), _ptr(lam), _ptr(stat)), "sage_probe_eig_matrix")
+        return Y, lam, stat
 
     def profile_enable(self, on=True):
         _check(self.L.sage_profile_enable(self.h, 1 if on else 0), "sage_profile_enable")

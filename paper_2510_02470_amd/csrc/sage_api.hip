@@ -514,6 +514,21 @@ int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, doub
     return SAGE_OK;
 }
 
+int sage_probe_eig_matrix(sage_ctx* c, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out) {
+    if (!c || !C_in) return SAGE_ERR_ARG;
+    const int NP = c->d.NP;
+    HIPCHK(hipMemcpyAsync(c->ew.C, C_in, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    HIPCHK(launch_eig(c->ew, NP, c->st));
+    if (Y_out) HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    if (lam_out)
+        HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double), NP,
+                                hipMemcpyDeviceToDevice, c->st));
+    if (sweep_stat_out)
+        HIPCHK(hipMemcpyAsync(sweep_stat_out, c->ew.stat, 18 * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
 int sage_profile_enable(sage_ctx* c, int on) {
     if (!c) return SAGE_ERR_ARG;
     c->prof = on != 0;

@@ -1,0 +1,320 @@
+"""GPU parity tests: the HIP library (through the C ABI binding) against the CPU oracle on the same seeded inputs.
+
+Bars (from the benchmark spec):
+  sketch      ||B^T B - B_o^T B_o||_2 / ||A||_F^2 <= 1e-4   (B is only defined up to a rotation of its rows)
+  scores      |alpha - alpha_o| <= 1e-4 with the oracle's basis injected (stage-isolated), and end to end where
+              the basis is well conditioned (config 1)
+  selection   bit-exact on identical score vectors; end to end identical outside a 1e-4 band round the threshold
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from helpers import cov_diff_spec_norm, run_gpu, run_oracle, to_dev  # noqa: E402
+import oracle  # noqa: E402
+from oracle import Oracle  # noqa: E402
+from paper_2510_02470_amd import inputs  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+COV_TOL = 1e-4
+SCORE_TOL = 1e-4
+
+
+def _binding():
+    from paper_2510_02470_amd import binding
+
+    return binding
+
+
+def _check_selection(gidx, oidx, alpha_o, band=SCORE_TOL):
+    """Sets must agree except for examples whose oracle score lies within `band` of the oracle threshold."""
+    gi, oi = set(gidx.tolist()), set(oidx.tolist())
+    assert len(gi) == len(oi)
+    if not oi:
+        return
+    tau = float(np.min(alpha_o[list(oi)]))
+    for i in gi ^ oi:
+        assert abs(float(alpha_o[i]) - tau) <= band, (i, alpha_o[i], tau)
+
+
+# ------------------------------------------------------------------------------------------ stage: Gram + Jacobi
+@pytest.mark.parametrize("ell,D,rows", [(32, 512, 63), (16, 100, 20), (64, 5130, 127), (128, 1300, 255),
+                                        (256, 4099, 511), (37, 333, 70)])
+def test_gram_and_eigensolve(ell, D, rows):
+    B = _binding()
+    rng = np.random.default_rng(ell * 7 + D)
+    A = (rng.standard_normal((rows, D)) * np.exp(rng.standard_normal((rows, 1)))).astype(np.float32)
+    s = B.Sage(ell, D)
+    s.fd_update(torch.from_numpy(A).cuda())
+    back = s.sketch().cpu().numpy()
+    assert np.array_equal(back[:rows], A) and not back[rows:].any()
+    Cm, Y, lam = s.probe_gram_eig(True)
+    Cm, Y, lam = Cm.cpu().numpy(), Y.cpu().numpy(), lam.cpu().numpy()
+    npad = Cm.shape[0]
+    ref = np.zeros((npad, npad))
+    A64 = A.astype(np.float64)
+    ref[:rows, :rows] = A64 @ A64.T
+    scale = np.abs(ref).max()
+    assert np.abs(Cm - ref).max() <= 2e-6 * scale          # fp32 products, fp32 accumulation inside a split
+    assert np.array_equal(Cm, Cm.T)
+    assert np.abs(Y.T @ Y - np.eye(npad)).max() <= 1e-12
+    assert np.abs(Y @ np.diag(lam) @ Y.T - Cm).max() <= 1e-8 * np.trace(Cm)
+    ev = np.linalg.eigvalsh(Cm)[::-1]
+    assert np.abs(np.sort(lam)[::-1] - ev).max() <= 1e-8 * np.trace(Cm)
+    st = s.stats()
+    assert st.rows_seen == rows and st.fill == rows and st.n_shrinks == 0
+    assert abs(st.frob2 - (A64 ** 2).sum()) <= 1e-5 * (A64 ** 2).sum()
+
+
+def test_eigensolve_on_given_matrices():
+    """Jacobi on matrices that are hard for it: clustered and repeated eigenvalues, rank deficiency, zero."""
+    B = _binding()
+    s = B.Sage(64, 64)  # n_pad = 128
+    n = 128
+    rng = np.random.default_rng(5)
+    Qm, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    cases = {
+        "clustered": np.concatenate([np.full(40, 1.0), 1.0 + 1e-9 * np.arange(40), np.linspace(0.5, 1e-8, 48)]),
+        "rank8": np.concatenate([np.linspace(3, 1, 8), np.zeros(n - 8)]),
+        "graded": 10.0 ** (-np.arange(n) / 8.0),
+    }
+    for name, ev in cases.items():
+        Cm = (Qm * ev[None, :]) @ Qm.T
+        Cm = (Cm + Cm.T) / 2
+        Y, lam, stat = s.probe_eig_matrix(torch.from_numpy(Cm).cuda())
+        Y, lam = Y.cpu().numpy(), lam.cpu().numpy()
+        tr = np.trace(Cm)
+        assert np.abs(Y.T @ Y - np.eye(n)).max() <= 1e-12, name
+        # the solve stops once every off-diagonal element is below ~1e-9 of the trace: that is the residual
+        assert np.abs(Y @ np.diag(lam) @ Y.T - Cm).max() <= 1e-8 * tr, name
+        assert np.abs(np.sort(lam)[::-1] - np.sort(ev)[::-1]).max() <= 1e-8 * tr, name
+    Z = torch.zeros((n, n), dtype=torch.float64, device="cuda")
+    Y, lam, stat = s.probe_eig_matrix(Z)
+    assert torch.equal(Y, torch.eye(n, dtype=torch.float64, device="cuda")) and not lam.any()
+
+
+# ------------------------------------------------------------------------------------------ sketch parity
+def _small_workloads():
+    W = inputs.WORKLOADS
+    return {
+        "cfg1": W[1],
+        "cfg1_ragged": W[1].scaled(N=1000, batch=77),
+        "cfg2_small": W[2].scaled(N=1500, batch=400),
+        "cfg3_small": W[3].scaled(N=900, D=5130, batch=300),
+        "cfg4_small": W[4].scaled(N=1100, D=4096, batch=512),
+        "cfg5_small_bf16": W[5].scaled(N=1300, D=3000, batch=1024),
+        "odd_ell": W[1].scaled(N=400, D=333, ell=23, k=7, batch=50),
+    }
+
+
+_ORACLE_RUNS = {}
+
+
+def _oracle_run(name):
+    """The oracle's full run of a small workload (Gram route), computed once per session."""
+    if name not in _ORACLE_RUNS:
+        w = _small_workloads()[name]
+        G = inputs.generate_numpy(w)
+        o, oidx = run_oracle(w, G, mode=1)
+        _ORACLE_RUNS[name] = (w, G, o, oidx)
+    return _ORACLE_RUNS[name]
+
+
+@pytest.mark.parametrize("name", list(_small_workloads().keys()))
+def test_sketch_covariance_matches_oracle(name):
+    w, G, o, _ = _oracle_run(name)
+    s, _ = run_gpu(w, G, score=False)
+    Bg = s.sketch().cpu().numpy()
+    A64 = (inputs.bf16_bits_to_f32(G) if G.dtype == np.uint16 else G).astype(np.float64)
+    fro = (A64 ** 2).sum()
+    st = s.stats()
+    assert st.n_shrinks == o.n_shrinks and st.fill == o.fill and st.rows_seen == o.rows_seen
+    assert not Bg[st.fill:].any()
+    err = cov_diff_spec_norm(Bg, o.B) / fro
+    assert err <= COV_TOL, err
+    assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro
+    assert abs(st.frob2 - fro) <= 1e-5 * fro
+    # FD guarantee on the GPU sketch itself: 0 <= A^T A - B^T B <= sum(delta)   (D x D is small here)
+    if w.D <= 5200:
+        diff = A64.T @ A64 - Bg.astype(np.float64).T @ Bg.astype(np.float64)
+        ev = np.linalg.eigvalsh(diff)
+        assert ev.min() >= -1e-5 * fro and ev.max() <= st.sum_delta + 1e-5 * fro
+
+
+def test_sketch_is_deterministic():
+    w = inputs.WORKLOADS[1].scaled(N=700)
+    G = inputs.generate_numpy(w)
+    s1, i1 = run_gpu(w, G)
+    s2, i2 = run_gpu(w, G)
+    assert torch.equal(s1.sketch(), s2.sketch())
+    assert torch.equal(s1.scores(), s2.scores()) and torch.equal(i1, i2)
+
+
+# ------------------------------------------------------------------------------------------ scoring parity
+@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg3_small", "cfg4_small", "cfg5_small_bf16", "odd_ell"])
+def test_scores_with_oracle_basis(name):
+    """Stage-isolated: both sides project on the oracle's basis, so only the scoring arithmetic is compared."""
+    B = _binding()
+    w, G, o, oidx = _oracle_run(name)
+    V = o.V
+    s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    s.set_basis(torch.from_numpy(V.astype(np.float32)).cuda())
+    o2 = Oracle(w.ell, w.D, 1)
+    o2.set_basis(V.astype(np.float32).astype(np.float64))  # the very same (fp32-rounded) basis on both sides
+    Gd = to_dev(G, torch)
+    for lo in range(0, w.N, w.batch):
+        s.score(Gd[lo:lo + w.batch])
+        o2.score(G[lo:lo + w.batch])
+    gidx = s.select(w.keep).cpu().numpy()
+    oidx2 = o2.select(w.keep)
+    al = s.scores().cpu().numpy()
+    assert np.abs(al - o2.alpha).max() <= SCORE_TOL
+    assert al.max() <= 1.0 and al.min() >= -1.0
+    zh = s.zhat().cpu().numpy()
+    assert np.abs(zh - o2.zhat).max() <= 1e-5
+    _check_selection(gidx, oidx2, o2.alpha)
+    # the selection is exactly the top-m of the GPU's own score vector
+    assert gidx.tolist() == oracle.topm_f32(al, len(gidx)).tolist()
+
+
+def test_end_to_end_config1():
+    """Config 1 has a wide spectral gap after k = 16, so sketch -> basis -> scores -> selection must match."""
+    w = inputs.WORKLOADS[1]
+    G = inputs.generate_numpy(w)
+    o, oidx = run_oracle(w, G, mode=0)
+    s, gidx = run_gpu(w, G)
+    al = s.scores().cpu().numpy()
+    assert np.abs(al - o.alpha).max() <= SCORE_TOL
+    _check_selection(gidx.cpu().numpy(), oidx, o.alpha)
+    Vg = s.basis().cpu().numpy().astype(np.float64)
+    assert np.abs(Vg @ Vg.T - np.eye(w.k)).max() <= 1e-5
+    assert np.abs(Vg.T @ Vg - o.V.T @ o.V).max() <= 1e-4  # same span
+
+
+def test_end_to_end_reports_conditioning():
+    """Slow power-law spectra make span(V_k) ill-conditioned; scores then agree only as far as the two sketches'
+    top-k subspaces do. The check: the score gap is explained by the principal angle between the two bases."""
+    w = inputs.WORKLOADS[2].scaled(N=1500, batch=400)
+    G = inputs.generate_numpy(w)
+    o, oidx = run_oracle(w, G, mode=1)
+    s, gidx = run_gpu(w, G)
+    Vg = s.basis().cpu().numpy().astype(np.float64)
+    sv = np.linalg.svd(Vg @ o.V.T, compute_uv=False)
+    sin_max = float(np.sqrt(max(0.0, 1.0 - sv.min() ** 2)))
+    err = float(np.abs(s.scores().cpu().numpy() - o.alpha).max())
+    assert err <= max(SCORE_TOL, 20.0 * sin_max), (err, sin_max)
+
+
+# ------------------------------------------------------------------------------------------ selection
+@pytest.mark.parametrize("N,m", [(1, 1), (5, 0), (5, 5), (2048, 205), (2049, 1), (100_000, 10_000), (1_000_003, 9_999),
+                                 (300_000, 299_999)])
+def test_topm_bit_exact(N, m):
+    B = _binding()
+    rng = np.random.default_rng(N + m)
+    a = rng.standard_normal(N).astype(np.float32).clip(-1, 1)
+    a[rng.integers(0, N, size=N // 3)] = np.float32(0.25)      # many ties
+    a[rng.integers(0, N, size=max(1, N // 50))] = np.float32(-0.0)
+    a[rng.integers(0, N, size=max(1, N // 50))] = np.float32(0.0)
+    got = B.topm(torch.from_numpy(a).cuda(), m).cpu().numpy()
+    want = oracle.topm_f32(a, m)
+    assert got.tolist() == want.tolist()
+
+
+def test_topm_all_equal_and_extremes():
+    B = _binding()
+    a = np.full(5000, 0.5, dtype=np.float32)
+    assert B.topm(torch.from_numpy(a).cuda(), 17).cpu().tolist() == list(range(17))
+    a = np.array([1.0, -1.0, 1.0, -1.0, 0.0, -0.0], dtype=np.float32)
+    assert B.topm(torch.from_numpy(a).cuda(), 3).cpu().tolist() == [0, 2, 4]
+    assert B.topm(torch.from_numpy(a).cuda(), 4).cpu().tolist() == [0, 2, 4, 5]
+
+
+# ------------------------------------------------------------------------------------------ degenerate inputs
+def test_zero_rows_zero_consensus_and_empty_calls():
+    B = _binding()
+    D, ell = 96, 8
+    s = B.Sage(ell, D)
+    empty = torch.empty((0, D), dtype=torch.float32, device="cuda")
+    s.fd_update(empty)
+    V = np.zeros((2, D), dtype=np.float32)
+    V[0, 0] = 1.0
+    V[1, 1] = 1.0
+    s.set_basis(torch.from_numpy(V).cuda())
+    s.score(empty)
+    assert s.select(0.5).numel() == 0
+    rows = np.zeros((4, D), dtype=np.float32)
+    rows[0, 0] = 2.0
+    rows[1, 0] = -2.0
+    rows[2, 5] = 1.0
+    s.score(torch.from_numpy(rows).cuda())
+    idx = s.select(0.5)
+    al = s.scores().cpu().numpy()
+    assert idx.cpu().tolist() == [0, 1]
+    assert not al.any() and not np.signbit(al).any()
+    zh = s.zhat().cpu().numpy()
+    assert zh[0, 0] == 1.0 and zh[1, 0] == -1.0 and not zh[2:].any()
+
+
+def test_low_rank_stream_is_recovered():
+    """rank(A) < ell: every delta is ~0 and the sketch reproduces A^T A (exact-recovery case of FD)."""
+    B = _binding()
+    rng = np.random.default_rng(3)
+    ell, D, N, r = 32, 700, 400, 9
+    A = (rng.standard_normal((N, r)) @ rng.standard_normal((r, D))).astype(np.float32)
+    s = B.Sage(ell, D)
+    s.fd_update(torch.from_numpy(A).cuda())
+    Bg = s.sketch().cpu().numpy().astype(np.float64)
+    A64 = A.astype(np.float64)
+    fro = (A64 ** 2).sum()
+    st = s.stats()
+    assert st.sum_delta <= 1e-6 * fro
+    assert cov_diff_spec_norm(Bg, A64) <= 1e-5 * fro
+
+
+def test_argument_and_state_errors():
+    B = _binding()
+    import ctypes as C
+
+    L = B.lib()
+    h = C.c_void_p(0)
+    assert L.sage_fd_create(C.byref(h), 1, 10) == B.SAGE_ERR_ARG
+    assert L.sage_fd_create(C.byref(h), 257, 10) == B.SAGE_ERR_ARG
+    assert L.sage_fd_create(C.byref(h), 8, 0) == B.SAGE_ERR_ARG
+    assert L.sage_fd_create(None, 8, 10) == B.SAGE_ERR_ARG
+    s = B.Sage(8, 40, max_rows=10)
+    g = torch.ones((6, 40), dtype=torch.float32, device="cuda")
+    assert L.sage_score(s.h, C.c_void_p(g.data_ptr()), 6) == B.SAGE_ERR_STATE
+    m = C.c_int64(0)
+    assert L.sage_select(s.h, 0.5, None, 0, C.byref(m)) == B.SAGE_ERR_STATE
+    assert L.sage_fd_update(s.h, None, 3) == B.SAGE_ERR_ARG
+    assert L.sage_fd_update(s.h, C.c_void_p(g.data_ptr()), -1) == B.SAGE_ERR_ARG
+    s.fd_update(g)
+    assert L.sage_fd_basis(s.h, 0) == B.SAGE_ERR_ARG
+    assert L.sage_fd_basis(s.h, 8) == B.SAGE_ERR_ARG
+    s.fd_basis(3)
+    s.score(g)
+    assert L.sage_score(s.h, C.c_void_p(g.data_ptr()), 6) == B.SAGE_ERR_CAPACITY
+    assert L.sage_select(s.h, 1.5, None, 0, C.byref(m)) == B.SAGE_ERR_ARG
+    out = torch.empty(2, dtype=torch.int64, device="cuda")
+    assert L.sage_select(s.h, 1.0, C.c_void_p(out.data_ptr()), 2, C.byref(m)) == B.SAGE_ERR_CAPACITY and m.value == 6
+    s.fd_update(g)  # invalidates the basis
+    assert L.sage_score(s.h, C.c_void_p(g.data_ptr()), 1) == B.SAGE_ERR_STATE
+    assert B.lib().sage_strerror(B.SAGE_ERR_STATE) == b"call not allowed in this state"
+
+
+def test_score_store_grows():
+    B = _binding()
+    D = 64
+    s = B.Sage(8, D)  # growable store, first capacity 65536 rows
+    V = np.zeros((2, D), dtype=np.float32)
+    V[0, 0] = V[1, 1] = 1.0
+    s.set_basis(torch.from_numpy(V).cuda())
+    g = torch.randn((40_000, D), device="cuda")
+    s.score(g)
+    s.score(g)
+    idx = s.select(0.01)
+    assert s.stats().n_scored == 80_000 and idx.numel() == 800
+    al = s.scores()
+    assert torch.equal(al[:40_000], al[40_000:])
