@@ -5,15 +5,14 @@
 // vectors y_j of the buffer:  sigma_j v_j^T = y_j^T B.  The matrix is cut into 32x32 blocks. One sweep is:
 //   step 0        every work-group takes two diagonal blocks and annihilates all pairs inside each block,
 //   step 1..nb-1  round-robin over block pairs (I, J): annihilate every pair (p in I, q in J),
-// so each off-diagonal element is rotated exactly once per sweep. A step is two kernels: `solve` runs the
+// so each off-diagonal element is rotated exactly once per sweep. A step is two kernels: a solve kernel runs the
 // rotations of each 64x64 pivot sub-matrix in LDS and emits its accumulated 64x64 rotation Q_w; `apply`
-// updates C <- Q^T C Q and Y <- Y Q with Q = blockdiag(Q_w) as small LDS-tiled products.
+// updates C <- Q^T C Q and Y <- Y Q with Q = blockdiag(Q_w) as 64x64x64 products on the fp64 matrix cores.
 #include "sage_internal.h"
 
 namespace sage {
 
-constexpr double JACOBI_TOL = 1e-11;  // sweep converged when every |c_pq| it met was <= TOL * trace(C)
-constexpr int LDA = 65;               // padded leading dimension of the 64x64 LDS matrices (doubles)
+constexpr int LDA = 65;  // padded leading dimension of the 64x64 LDS matrix of the solve kernels (doubles)
 
 // round-robin pairing of n (even) players, step t in [0, n-1), slot i in [0, n/2): player n-1 stays put
 __device__ __forceinline__ void rr_pair(int n, int t, int i, int& p, int& q) {
@@ -34,13 +33,56 @@ __device__ __forceinline__ void block_pair(int nb, int st, int w, int& I, int& J
     }
 }
 
-__device__ __forceinline__ bool sweep_done(const double* stat, int sweep) {
-    return sweep > 0 && stat[1 + sweep - 1] <= JACOBI_TOL;
+// stat[1 + s] = largest off-diagonal |c_pq| / trace(C) measured (jac_measure_kernel) just before sweep s. The solve
+// is finished, and sweep s and all later ones do nothing, once that is <= tol.
+__device__ __forceinline__ bool sweep_done(const double* stat, int sweep, double tol) {
+    return stat[1 + sweep] <= tol;
 }
 
 __device__ __forceinline__ void atomic_max_pos_double(double* addr, double v) {
     // non-negative doubles order like their bit patterns
     atomicMax(reinterpret_cast<unsigned long long*>(addr), (unsigned long long)__double_as_longlong(v));
+}
+
+// Rotation [[c, s], [-s, c]] that annihilates a_pq of the symmetric 2x2 [[app, apq], [apq, aqq]] (the one of
+// smaller angle): t = sign(a) apq / (|a| + sqrt(a^2 + apq^2)), a = (aqq - app)/2, c = 1/sqrt(1 + t^2), s = c t.
+__device__ __forceinline__ void rot_params(double app, double aqq, double apq, double& c, double& s) {
+    c = 1.0;
+    s = 0.0;
+    if (apq == 0.0) return;
+    double a = 0.5 * (aqq - app);
+    double den = fabs(a) + sqrt(a * a + apq * apq);
+    if (!(den > 0.0)) return;
+    double t = apq / den;
+    if (a < 0.0) t = -t;
+    c = 1.0 / sqrt(1.0 + t * t);
+    s = c * t;
+}
+
+// Same rotation from the hardware reciprocal / reciprocal-square-root approximations, each polished by two Newton
+// steps (the serial chain of a round starts here, so the IEEE division and square root are avoided). Also returns
+// t = s/c, which gives the rotated diagonal in closed form: a_pp - t a_pq and a_qq + t a_pq.
+__device__ __forceinline__ double rsqrt_newton(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+    y = y * (1.5 - 0.5 * x * y * y);
+    y = y * (1.5 - 0.5 * x * y * y);
+    return y;
+}
+__device__ __forceinline__ void rot_params_fast(double app, double aqq, double apq, double& c, double& s, double& t) {
+    c = 1.0;
+    s = 0.0;
+    t = 0.0;
+    double a = 0.5 * (aqq - app);
+    double h = a * a + apq * apq;
+    if (apq == 0.0 || !(h > 1e-280) || !(h < 1e280)) return;  // nothing to rotate, or outside the safe range
+    double den = fabs(a) + h * rsqrt_newton(h);
+    double inv = __builtin_amdgcn_rcp(den);
+    inv = inv * (2.0 - den * inv);
+    inv = inv * (2.0 - den * inv);
+    t = apq * inv;
+    if (a < 0.0) t = -t;
+    c = rsqrt_newton(1.0 + t * t);
+    s = c * t;
 }
 
 // Y = I, diag0 = diag(C), stat[0] = trace(C), stat[1..] = 0. grid = NP blocks of 256.
@@ -68,64 +110,68 @@ __global__ __launch_bounds__(256) void jac_init_kernel(const double* __restrict_
     }
 }
 
-// One work-group per block pair: rotations of the 64x64 pivot sub-matrix, Q_w written to Qout[w].
-__global__ __launch_bounds__(256) void jac_solve_kernel(const double* __restrict__ C, double* __restrict__ Qout,
-                                                        double* __restrict__ stat, int NP, int sweep, int st) {
-    if (sweep_done(stat, sweep)) return;
-    extern __shared__ double sm[];
-    double* A = sm;             // 64 x LDA
-    double* Qm = sm + 64 * LDA; // 64 x LDA
-    double* cs = Qm + 64 * LDA; // 32 x 2
-    const int tid = threadIdx.x;
-    const int nb = NP / 32;
-    int I, J;
-    block_pair(nb, st, blockIdx.x, I, J);
-    const bool diag_mode = (st == 0);
-
-    for (int e = tid; e < 64 * 64; e += 256) {
+// all 16 global loads of a thread are issued before the first LDS store, so their latencies overlap
+__device__ __forceinline__ void load_pivot(const double* __restrict__ C, int NP, int I, int J, double* A, int tid) {
+    double v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        int e = u * 256 + tid;
         int r = e >> 6, c = e & 63;
         int gr = (r < 32 ? I * 32 + r : J * 32 + r - 32);
         int gc = (c < 32 ? I * 32 + c : J * 32 + c - 32);
-        A[r * LDA + c] = C[(int64_t)gr * NP + gc];
-        Qm[r * LDA + c] = (r == c) ? 1.0 : 0.0;
+        v[u] = C[(int64_t)gr * NP + gc];
     }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        int e = u * 256 + tid;
+        A[(e >> 6) * LDA + (e & 63)] = v[u];
+    }
+}
+
+// Before sweep `sweep`: stat[1 + sweep] = max off-diagonal |c_pq| / trace. One block per 16 matrix rows.
+// Once a measurement is <= tol the later ones simply repeat it (the matrix no longer changes).
+__global__ __launch_bounds__(256) void jac_measure_kernel(const double* __restrict__ C, double* __restrict__ stat, int NP,
+                                                          int sweep, double tol) {
+    if (sweep > 0 && stat[sweep] <= tol) return;  // stat[1 + sweep] stays 0 <= tol
+    __shared__ double red[4];
+    double mx = 0.0;
+    for (int rr = 0; rr < 16; ++rr) {
+        const int row = blockIdx.x * 16 + rr;
+        for (int c = threadIdx.x; c < NP; c += 256)
+            if (c != row) mx = fmax(mx, fabs(C[(int64_t)row * NP + c]));
+    }
+    for (int o = 32; o >= 1; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    double tr = stat[0];
+    if (threadIdx.x == 0 && tr > 0.0) {
+        mx = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+        if (mx > 0.0) atomic_max_pos_double(&stat[1 + sweep], mx / tr);
+    }
+}
+
+// Step 0 of a sweep: work-group w holds diagonal blocks 2w and 2w+1 as one 64x64 matrix and annihilates every pair
+// inside each block (31 rounds of 16 + 16 disjoint rotations, round-robin inside a block). Q accumulates in LDS.
+__global__ __launch_bounds__(256) void jac_diag_kernel(const double* __restrict__ C, double* __restrict__ Qout,
+                                                       double* __restrict__ stat, int NP, int sweep, double tol) {
+    if (sweep_done(stat, sweep, tol)) return;
+    extern __shared__ double sm[];
+    double* A = sm;              // 64 x LDA
+    double* Qm = sm + 64 * LDA;  // 64 x LDA
+    double* cs = Qm + 64 * LDA;  // 32 x 2
+    const int tid = threadIdx.x;
+    const int I = 2 * blockIdx.x, J = 2 * blockIdx.x + 1;
+    load_pivot(C, NP, I, J, A, tid);
+    for (int e = tid; e < 64 * 64; e += 256) Qm[(e >> 6) * LDA + (e & 63)] = ((e >> 6) == (e & 63)) ? 1.0 : 0.0;
     __syncthreads();
 
-    // largest element this step is about to annihilate, relative to the trace
-    {
-        double mx = 0.0;
-        for (int e = tid; e < 64 * 64; e += 256) {
-            int r = e >> 6, c = e & 63;
-            bool mine = diag_mode ? ((r < 32) == (c < 32) && r != c) : ((r < 32) != (c < 32));
-            if (mine) mx = fmax(mx, fabs(A[r * LDA + c]));
-        }
-        for (int o = 32; o >= 1; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
-        double tr = stat[0];
-        if ((tid & 63) == 0 && tr > 0.0) atomic_max_pos_double(&stat[1 + sweep], mx / tr);
-    }
-
-    const int nsteps = diag_mode ? 31 : 32;
-    for (int t = 0; t < nsteps; ++t) {
+    for (int t = 0; t < 31; ++t) {
         if (tid < 32) {
             int p, q;
-            if (diag_mode) {
-                rr_pair(32, t, tid & 15, p, q);
-                if (tid >= 16) { p += 32; q += 32; }
-            } else {
-                p = tid;
-                q = 32 + ((tid + t) & 31);
-            }
-            double apq = A[p * LDA + q];
-            double c = 1.0, s = 0.0;
-            if (apq != 0.0) {
-                double app = A[p * LDA + p], aqq = A[q * LDA + q];
-                double zeta = (aqq - app) / (2.0 * apq);
-                double az = fabs(zeta);
-                double tt = 1.0 / (az + sqrt(1.0 + az * az));
-                if (zeta < 0.0) tt = -tt;
-                c = 1.0 / sqrt(1.0 + tt * tt);
-                s = c * tt;
-            }
+            rr_pair(32, t, tid & 15, p, q);
+            if (tid >= 16) { p += 32; q += 32; }
+            double c, s;
+            rot_params(A[p * LDA + p], A[q * LDA + q], A[p * LDA + q], c, s);
             cs[2 * tid] = c;
             cs[2 * tid + 1] = s;
         }
@@ -136,15 +182,10 @@ __global__ __launch_bounds__(256) void jac_solve_kernel(const double* __restrict
             int b = it * 256 + tid;
             int i = b >> 5, j = b & 31;
             int pi, qi, pj, qj;
-            if (diag_mode) {
-                rr_pair(32, t, i & 15, pi, qi);
-                if (i >= 16) { pi += 32; qi += 32; }
-                rr_pair(32, t, j & 15, pj, qj);
-                if (j >= 16) { pj += 32; qj += 32; }
-            } else {
-                pi = i; qi = 32 + ((i + t) & 31);
-                pj = j; qj = 32 + ((j + t) & 31);
-            }
+            rr_pair(32, t, i & 15, pi, qi);
+            if (i >= 16) { pi += 32; qi += 32; }
+            rr_pair(32, t, j & 15, pj, qj);
+            if (j >= 16) { pj += 32; qj += 32; }
             double ci = cs[2 * i], si = cs[2 * i + 1], cj = cs[2 * j], sj = cs[2 * j + 1];
             double x00 = A[pi * LDA + pj], x01 = A[pi * LDA + qj], x10 = A[qi * LDA + pj], x11 = A[qi * LDA + qj];
             double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
@@ -161,12 +202,8 @@ __global__ __launch_bounds__(256) void jac_solve_kernel(const double* __restrict
             int b = it * 256 + tid;
             int r = b >> 5, j = b & 31;
             int pj, qj;
-            if (diag_mode) {
-                rr_pair(32, t, j & 15, pj, qj);
-                if (j >= 16) { pj += 32; qj += 32; }
-            } else {
-                pj = j; qj = 32 + ((j + t) & 31);
-            }
+            rr_pair(32, t, j & 15, pj, qj);
+            if (j >= 16) { pj += 32; qj += 32; }
             double cj = cs[2 * j], sj = cs[2 * j + 1];
             double a = Qm[r * LDA + pj], bq = Qm[r * LDA + qj];
             Qm[r * LDA + pj] = cj * a - sj * bq;
@@ -178,79 +215,205 @@ __global__ __launch_bounds__(256) void jac_solve_kernel(const double* __restrict
     for (int e = tid; e < 4096; e += 256) Qo[e] = Qm[(e >> 6) * LDA + (e & 63)];
 }
 
-// 64x64x64 product in LDS by 256 threads, 4x4 micro-tile each: out(r0.., c0..) = sum_e L(e, r or r, e) * R(e, c).
-// TRANS_L: left operand is read transposed (L^T R), else (L R).
-template <bool TRANS_L>
-__device__ __forceinline__ void mm64(const double* L, const double* R, double (&o)[4][4], int r0, int c0) {
+// Steps 1..nb-1: work-group w holds blocks (I, J) as one 64x64 matrix and annihilates every pair (p in I, q in J) in
+// 32 rounds of 32 disjoint rotations. Index i = 4a + l of the first half (a < 8, l < 4) meets, in round
+// (sigma, tau), index 4((a + tau) % 8) + (l + sigma) % 4 of the second half: a Latin square, so every pair is met
+// once. A lives in LDS. Q lives in registers: a quad of lanes owns one row of Q, lane l of the quad holding the
+// first-half columns {4a + l} and the second-half columns {32 + 4a' + (l + sigma) % 4}; with this schedule a round
+// only rotates register pairs of one lane (static indices), and a change of sigma is a one-lane shift in the quad.
+__global__ __launch_bounds__(256) void jac_cross_kernel(const double* __restrict__ C, double* __restrict__ Qout,
+                                                        double* __restrict__ stat, int NP, int sweep, int st,
+                                                        double tol) {
+    if (sweep_done(stat, sweep, tol)) return;
+    __shared__ double A[64 * LDA];
+    __shared__ double cs[2][64];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int nb = NP / 32;
+    int I, J;
+    block_pair(nb, st, blockIdx.x, I, J);
+    load_pivot(C, NP, I, J, A, tid);
+
+    const int qrow = wave * 16 + (lane >> 2), lq = lane & 3;
+    double qa[8], qb[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int a = 0; a < 8; ++a) {
+        qa[a] = (qrow == 4 * a + lq) ? 1.0 : 0.0;
+        qb[a] = (qrow == 32 + 4 * a + lq) ? 1.0 : 0.0;
+    }
+    __syncthreads();
+
+    // the 496 pair-of-pairs (i < j) a round has to update are split statically: thread -> e = tid and e = 256 + tid
+    int bi[2], bj[2];
+    const bool second = (256 + tid) < 496;  // 16 threads have no second block
 #pragma unroll
-        for (int v = 0; v < 4; ++v) o[u][v] = 0.0;
-    for (int e = 0; e < 64; ++e) {
-        double a[4], b[4];
+    for (int u = 0; u < 2; ++u) {
+        int e = u * 256 + tid, i = 0;
+        if (e >= 496) e = 0;
+        while (e >= 31 - i) { e -= 31 - i; ++i; }
+        bi[u] = i;
+        bj[u] = i + 1 + e;
+    }
+
+    for (int sigma = 0; sigma < 4; ++sigma) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a[u] = TRANS_L ? L[e * LDA + r0 + u] : L[(r0 + u) * LDA + e];
+        for (int tau = 0; tau < 8; ++tau) {
+            const int par = tau & 1;
+            if (tid < 32) {
+                // rotation of pair `tid`; its own 2x2 block has a closed form and nobody else touches it
+                int p = tid;
+                int q = 32 + ((((tid >> 2) + tau) & 7) << 2) + (((tid & 3) + sigma) & 3);
+                double app = A[p * LDA + p], aqq = A[q * LDA + q], apq = A[p * LDA + q];
+                double c, s, t;
+                rot_params_fast(app, aqq, apq, c, s, t);
+                cs[par][2 * tid] = c;
+                cs[par][2 * tid + 1] = s;
+                if (s != 0.0) {
+                    A[p * LDA + p] = app - t * apq;
+                    A[q * LDA + q] = aqq + t * apq;
+                    A[p * LDA + q] = 0.0;
+                    A[q * LDA + p] = 0.0;
+                }
+            }
+            __syncthreads();
+            // 2x2 blocks of A for pairs i < j: X <- R_i^T X R_j, written to (i, j) and mirrored to (j, i)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) b[v] = R[e * LDA + c0 + v];
+            for (int u = 0; u < 2; ++u) {
+                if (u == 1 && !second) continue;
+                const int i = bi[u], j = bj[u];
+                int pi = i, qi = 32 + ((((i >> 2) + tau) & 7) << 2) + (((i & 3) + sigma) & 3);
+                int pj = j, qj = 32 + ((((j >> 2) + tau) & 7) << 2) + (((j & 3) + sigma) & 3);
+                double ci = cs[par][2 * i], si = cs[par][2 * i + 1], cj = cs[par][2 * j], sj = cs[par][2 * j + 1];
+                // only the upper triangle is kept current: (qi, pj) lives at (pj, qi), (qi, qj) at (min, max)
+                const int o00 = pi * LDA + pj, o01 = pi * LDA + qj, o10 = pj * LDA + qi;
+                const int o11 = qi < qj ? qi * LDA + qj : qj * LDA + qi;
+                double x00 = A[o00], x01 = A[o01], x10 = A[o10], x11 = A[o11];
+                double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
+                double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
+                A[o00] = cj * y00 - sj * y01;
+                A[o01] = sj * y00 + cj * y01;
+                A[o10] = cj * y10 - sj * y11;
+                A[o11] = sj * y10 + cj * y11;
+            }
+            // Q <- Q R: register pairs (qa[a], qb[(a + tau) % 8]) of pair index i = 4a + lq
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+            for (int a = 0; a < 8; ++a) {
+                const int i = 4 * a + lq;
+                double c = cs[par][2 * i], s = cs[par][2 * i + 1];
+                double x = qa[a], y = qb[(a + tau) & 7];
+                qa[a] = c * x - s * y;
+                qb[(a + tau) & 7] = s * x + c * y;
+            }
+            __syncthreads();
+        }
+        if (sigma < 3) {
+            const int src = (lane & ~3) | ((lane + 1) & 3);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) o[u][v] = fma(a[u], b[v], o[u][v]);
+            for (int a = 0; a < 8; ++a) qb[a] = __shfl(qb[a], src);
+        }
+    }
+    double* Qo = Qout + (int64_t)blockIdx.x * 4096 + qrow * 64;
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+        Qo[4 * a + lq] = qa[a];
+        Qo[32 + 4 * a + ((lq + 3) & 3)] = qb[a];
     }
 }
 
-// grid = 2 * np^2 (np = NP/64 pairs): blocks [0, np^2) update C tile (a, b) <- Q_a^T C Q_b, the rest update
-// Y tile (row chunk rc, b) <- Y Q_b. Every tile is read and written by exactly one work-group (in place).
-__global__ __launch_bounds__(256) void jac_apply_kernel(double* __restrict__ C, double* __restrict__ Y,
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+constexpr int LDX = 68;  // leading dimension of an LDS matrix read as the row operand   (lane -> row l%16, k l/16)
+constexpr int LDQ = 72;  // leading dimension of an LDS matrix read as the column operand (lane -> k l/16, col l%16)
+
+// fp64 matrix-core step acc(16x16) += a(16x4) b(4x16): lane l supplies a[l%16][l/16] and b[l/16][l%16];
+// acc element v of lane l is row 4v + l/16, column l%16.
+__device__ __forceinline__ f64x4 mfma64(double a, double b, f64x4 acc) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+}
+
+// grid = 4 * np^2 (np = NP/64 pairs): block -> (kind, tile (a, b), column half h). C tiles: out(a, b)[:, h] =
+// Q_a^T (C(a, b) Q_b[:, h]); Y tiles: out(a, b)[:, h] = Y(a, b) Q_b[:, h]. Reads `in`, writes `out` (ping-pong), so
+// the two halves of a tile never race. A wave owns 16 rows of the 64x32 result (2 accumulator tiles).
+__global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict__ Cin, double* __restrict__ Cout,
+                                                        const double* __restrict__ Yin, double* __restrict__ Yout,
                                                         const double* __restrict__ Q, const double* __restrict__ stat,
-                                                        int NP, int sweep, int st) {
-    if (sweep_done(stat, sweep)) return;
+                                                        int NP, int sweep, int st, double tol) {
+    if (sweep_done(stat, sweep, tol)) return;
     extern __shared__ double sm[];
-    double* X = sm;               // 64 x LDA
-    double* Qb = sm + 64 * LDA;   // 64 x LDA
-    double* Qa = Qb + 64 * LDA;   // 64 x LDA
-    const int tid = threadIdx.x;
+    double* X = sm;                // 64 x LDX
+    double* Qb = sm + 64 * LDX;    // 64 x LDQ (32 columns used), later T = X Q_b[:, h]
+    double* Qa = Qb + 64 * LDQ;    // 64 x LDQ
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int np = NP / 64, nb = NP / 32;
-    int bid = blockIdx.x;
+    const int half = blockIdx.x & 1;
+    int bid = blockIdx.x >> 1;
     const bool isY = bid >= np * np;
     if (isY) bid -= np * np;
     const int a = bid / np, b = bid % np;
     int Ia, Ja, Ib, Jb;
     block_pair(nb, st, a, Ia, Ja);
     block_pair(nb, st, b, Ib, Jb);
-    double* M = isY ? Y : C;
+    const double* Min = isY ? Yin : Cin;
+    double* Mout = isY ? Yout : Cout;
 
-    for (int e = tid; e < 4096; e += 256) {
-        int r = e >> 6, c = e & 63;
-        int gr = isY ? (a * 64 + r) : (r < 32 ? Ia * 32 + r : Ja * 32 + r - 32);
-        int gc = (c < 32 ? Ib * 32 + c : Jb * 32 + c - 32);
-        X[r * LDA + c] = M[(int64_t)gr * NP + gc];
-        Qb[r * LDA + c] = Q[(int64_t)b * 4096 + e];
-        if (!isY) Qa[r * LDA + c] = Q[(int64_t)a * 4096 + e];
+    {   // issue every global load before the first LDS store
+        double vx[16], va[16], vb[8];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            int e = u * 256 + tid;
+            int r = e >> 6, c = e & 63;
+            int gr = isY ? (a * 64 + r) : (r < 32 ? Ia * 32 + r : Ja * 32 + r - 32);
+            int gc = (c < 32 ? Ib * 32 + c : Jb * 32 + c - 32);
+            vx[u] = Min[(int64_t)gr * NP + gc];
+            va[u] = isY ? 0.0 : Q[(int64_t)a * 4096 + e];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int e = u * 256 + tid;
+            vb[u] = Q[(int64_t)b * 4096 + (e >> 5) * 64 + half * 32 + (e & 31)];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            int e = u * 256 + tid;
+            X[(e >> 6) * LDX + (e & 63)] = vx[u];
+            if (!isY) Qa[(e >> 6) * LDQ + (e & 63)] = va[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int e = u * 256 + tid;
+            Qb[(e >> 5) * LDQ + (e & 31)] = vb[u];
+        }
     }
     __syncthreads();
-    const int r0 = (tid >> 4) * 4, c0 = (tid & 15) * 4;
-    double o[4][4];
-    mm64<false>(X, Qb, o, r0, c0);  // T = X Q_b
-    if (!isY) {
-        __syncthreads();
+    const int l16 = lane & 15, lk = lane >> 4, i0 = wave * 16;
+    f64x4 acc[2];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+    for (int jt = 0; jt < 2; ++jt) acc[jt] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int k0 = 0; k0 < 64; k0 += 4) {  // T = X Q_b[:, h]
+        double av = X[(i0 + l16) * LDX + k0 + lk];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) X[(r0 + u) * LDA + c0 + v] = o[u][v];
-        __syncthreads();
-        mm64<true>(Qa, X, o, r0, c0);  // Q_a^T T
+        for (int jt = 0; jt < 2; ++jt) acc[jt] = mfma64(av, Qb[(k0 + lk) * LDQ + jt * 16 + l16], acc[jt]);
     }
+    if (!isY) {
+        __syncthreads();  // everyone is done reading Q_b
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        int r = r0 + u;
+        for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Qb[(i0 + 4 * v + lk) * LDQ + jt * 16 + l16] = acc[jt][v];
+        __syncthreads();
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) acc[jt] = f64x4{0.0, 0.0, 0.0, 0.0};
+        for (int k0 = 0; k0 < 64; k0 += 4) {  // Q_a^T T
+            double av = Qa[(k0 + lk) * LDQ + i0 + l16];
+#pragma unroll
+            for (int jt = 0; jt < 2; ++jt) acc[jt] = mfma64(av, Qb[(k0 + lk) * LDQ + jt * 16 + l16], acc[jt]);
+        }
+    }
+    const int gcb = (half == 0 ? Ib : Jb) * 32;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        int r = i0 + 4 * v + lk;
         int gr = isY ? (a * 64 + r) : (r < 32 ? Ia * 32 + r : Ja * 32 + r - 32);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            int c = c0 + v;
-            int gc = (c < 32 ? Ib * 32 + c : Jb * 32 + c - 32);
-            M[(int64_t)gr * NP + gc] = o[u][v];
-        }
+        for (int jt = 0; jt < 2; ++jt) Mout[(int64_t)gr * NP + gcb + jt * 16 + l16] = acc[jt][v];
     }
 }
 
@@ -258,7 +421,7 @@ __global__ __launch_bounds__(256) void jac_apply_kernel(double* __restrict__ C, 
 // One work-group of 512 threads. Also records the sweeps that were needed in acc[3].
 __global__ __launch_bounds__(512) void eig_sort_kernel(const double* __restrict__ C, const double* __restrict__ stat,
                                                        int* __restrict__ pos, double* __restrict__ lam, int NP,
-                                                       double* __restrict__ acc) {
+                                                       double* __restrict__ acc, double tol) {
     __shared__ double l[512];
     int j = threadIdx.x;
     double v = 0.0;
@@ -280,7 +443,7 @@ __global__ __launch_bounds__(512) void eig_sort_kernel(const double* __restrict_
     if (j == 0) {
         int used = MAX_SWEEPS;
         for (int s = 0; s < MAX_SWEEPS; ++s)
-            if (stat[1 + s] <= JACOBI_TOL) { used = s + 1; break; }
+            if (stat[1 + s] <= tol) { used = s; break; }
         acc[3] = (double)used;
     }
 }
@@ -334,39 +497,47 @@ __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restr
     }
 }
 
-static const size_t SOLVE_LDS = (size_t)(2 * 64 * LDA + 64) * sizeof(double);
-static const size_t APPLY_LDS = (size_t)(3 * 64 * LDA) * sizeof(double);
+static const size_t DIAG_LDS = (size_t)(2 * 64 * LDA + 64) * sizeof(double);
+static const size_t APPLY_LDS = (size_t)(64 * LDX + 2 * 64 * LDQ) * sizeof(double);
 
-hipError_t launch_eig(const EigWork& w, int NP, hipStream_t st) {
+hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st) {
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute((const void*)jac_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SOLVE_LDS);
+        (void)hipFuncSetAttribute((const void*)jac_diag_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)DIAG_LDS);
         (void)hipFuncSetAttribute((const void*)jac_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)APPLY_LDS);
         attr = true;
     }
     hipLaunchKernelGGL(jac_init_kernel, dim3(NP), dim3(256), 0, st, w.C, w.Y, w.diag0, w.stat, NP);
     const int np = NP / 64, nb = NP / 32;
+    // nb is even, so every sweep starts and ends on buffer 0: that is where the result is, whenever it converged
+    double* Cb[2] = {w.C, w.C2};
+    double* Yb[2] = {w.Y, w.Y2};
     for (int sweep = 0; sweep < MAX_SWEEPS; ++sweep) {
+        hipLaunchKernelGGL(jac_measure_kernel, dim3(NP / 16), dim3(256), 0, st, w.C, w.stat, NP, sweep, tol);
         for (int s = 0; s < nb; ++s) {
-            hipLaunchKernelGGL(jac_solve_kernel, dim3(np), dim3(256), SOLVE_LDS, st, w.C, w.Q, w.stat, NP, sweep, s);
-            hipLaunchKernelGGL(jac_apply_kernel, dim3(2 * np * np), dim3(256), APPLY_LDS, st, w.C, w.Y, w.Q, w.stat, NP,
-                               sweep, s);
+            const int cur = s & 1;
+            if (s == 0)
+                hipLaunchKernelGGL(jac_diag_kernel, dim3(np), dim3(256), DIAG_LDS, st, Cb[cur], w.Q, w.stat, NP, sweep, tol);
+            else
+                hipLaunchKernelGGL(jac_cross_kernel, dim3(np), dim3(256), 0, st, Cb[cur], w.Q, w.stat, NP, sweep, s, tol);
+            hipLaunchKernelGGL(jac_apply_kernel, dim3(4 * np * np), dim3(256), APPLY_LDS, st, Cb[cur], Cb[cur ^ 1], Yb[cur],
+                               Yb[cur ^ 1], w.Q, w.stat, NP, sweep, s, tol);
         }
     }
     return hipGetLastError();
 }
 
 hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int frob_r0, int frob_r1, float* Mt,
-                                double* acc, hipStream_t st) {
-    hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc);
+                                double* acc, double tol, hipStream_t st) {
+    hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc, tol);
     hipLaunchKernelGGL(shrink_coeffs_kernel, dim3((NP * LP + 255) / 256), dim3(256), 0, st, w.Y, w.pos, w.lam, w.diag0,
                        NP, LP, ell, frob_r0, frob_r1, Mt, acc);
     return hipGetLastError();
 }
 
 hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int frob_r0, int frob_r1, float* Mt,
-                               double* acc, hipStream_t st) {
-    hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc);
+                               double* acc, double tol, hipStream_t st) {
+    hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc, tol);
     hipLaunchKernelGGL(basis_coeffs_kernel, dim3((NP * KP + 255) / 256), dim3(256), 0, st, w.Y, w.pos, w.lam, w.diag0,
                        NP, KP, k, n, frob_r0, frob_r1, Mt, acc);
     return hipGetLastError();

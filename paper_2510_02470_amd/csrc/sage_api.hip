@@ -98,17 +98,18 @@ int pad_pow2_32(int v) {
     return p;
 }
 
-int decompose(sage_ctx* c) {
+int decompose(sage_ctx* c, double tol) {
     RUN(K_GRAM, launch_gram(c->B, c->gram_partial, c->gp, c->d, c->st));
     RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->ew.C, c->gp, c->d, c->st));
-    RUN(K_EIG, launch_eig(c->ew, c->d.NP, c->st));
+    RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, c->st));
     return SAGE_OK;
 }
 
 int shrink(sage_ctx* c) {
-    int rc = decompose(c);
+    int rc = decompose(c, JACOBI_TOL_SHRINK);
     if (rc != SAGE_OK) return rc;
-    RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, c->d.LP, c->d.ell, c->counted_base, c->d.n, c->Mt, c->acc, c->st));
+    RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, c->d.LP, c->d.ell, c->counted_base, c->d.n, c->Mt, c->acc,
+                                      JACOBI_TOL_SHRINK, c->st));
     RUN(K_REBUILD, launch_rebuild(c->B, c->Mt, c->B, c->d.NP, c->d.LP, true, c->d, c->st));
     c->fill = c->d.ell;
     c->counted_base = c->d.ell;
@@ -230,6 +231,8 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     CALLOC(c->gram_partial, c->gp.partial_floats * sizeof(float));
     CALLOC(c->ew.C, (size_t)NP * NP * sizeof(double));
     CALLOC(c->ew.Y, (size_t)NP * NP * sizeof(double));
+    CALLOC(c->ew.C2, (size_t)NP * NP * sizeof(double));
+    CALLOC(c->ew.Y2, (size_t)NP * NP * sizeof(double));
     CALLOC(c->ew.Q, (size_t)(NP / 64) * 4096 * sizeof(double));
     CALLOC(c->ew.diag0, (size_t)NP * sizeof(double));
     CALLOC(c->ew.stat, 32 * sizeof(double));
@@ -250,7 +253,7 @@ int sage_fd_create(sage_ctx** out, int ell, int64_t D) { return sage_fd_create_e
 void sage_destroy(sage_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->st);
-    void* ptrs[] = {c->B,       c->gram_partial, c->ew.C, c->ew.Y,         c->ew.Q,         c->ew.diag0, c->ew.stat,
+    void* ptrs[] = {c->B,       c->gram_partial, c->ew.C, c->ew.Y, c->ew.C2, c->ew.Y2, c->ew.Q,         c->ew.diag0, c->ew.stat,
                     c->ew.pos,  c->ew.lam,       c->Mt,   c->acc,          c->Vblk,         c->zhat,     c->proj_partial,
                     c->cons_partial, c->ssum,    c->alpha};
     for (void* p : ptrs)
@@ -294,9 +297,10 @@ int sage_fd_basis(sage_ctx* c, int k) {
     const int KP = pad_pow2_32(k);
     int rc = ensure_vblk(c, KP);
     if (rc != SAGE_OK) return rc;
-    rc = decompose(c);
+    rc = decompose(c, JACOBI_TOL_BASIS);
     if (rc != SAGE_OK) return rc;
-    RUN(K_COEFF, launch_basis_coeffs(c->ew, c->d.NP, KP, k, c->d.n, c->counted_base, c->fill, c->Mt, c->acc, c->st));
+    RUN(K_COEFF, launch_basis_coeffs(c->ew, c->d.NP, KP, k, c->d.n, c->counted_base, c->fill, c->Mt, c->acc,
+                                     JACOBI_TOL_BASIS, c->st));
     c->counted_base = c->fill;
     RUN(K_REBUILD, launch_rebuild(c->B, c->Mt, c->Vblk, KP, KP, false, c->d, c->st));
     c->k = k;
@@ -503,7 +507,7 @@ int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, doub
     if (C_out)
         HIPCHK(hipMemcpyAsync(C_out, c->ew.C, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
     if (eig) {
-        HIPCHK(launch_eig(c->ew, NP, c->st));
+        HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, c->st));
         if (Y_out)
             HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
         if (lam_out)
@@ -518,7 +522,7 @@ int sage_probe_eig_matrix(sage_ctx* c, const double* C_in, double* Y_out, double
     if (!c || !C_in) return SAGE_ERR_ARG;
     const int NP = c->d.NP;
     HIPCHK(hipMemcpyAsync(c->ew.C, C_in, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
-    HIPCHK(launch_eig(c->ew, NP, c->st));
+    HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, c->st));
     if (Y_out) HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
     if (lam_out)
         HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double), NP,

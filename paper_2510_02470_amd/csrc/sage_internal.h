@@ -63,19 +63,26 @@ hipError_t launch_gram_reduce(const float* partial, double* C, const GramPlan& p
 struct EigWork {
     double* C;      // NP x NP, destroyed (becomes near-diagonal)
     double* Y;      // NP x NP eigenvectors in columns
+    double* C2;     // ping-pong partners of C and Y for the out-of-place rotation updates
+    double* Y2;
     double* Q;      // (NP/64) x 64 x 64 rotation blocks of the current step
     double* diag0;  // NP: diagonal of C before the solve
     double* stat;   // [0] trace, [1..MAXSWEEP] per-sweep max |off| / trace
     int* pos;       // NP: pos[rank] = column of Y holding the rank-th largest eigenvalue
     double* lam;    // NP: eigenvalues sorted descending
 };
-constexpr int MAX_SWEEPS = 16;
-hipError_t launch_eig(const EigWork& w, int NP, hipStream_t st);
+constexpr int MAX_SWEEPS = 14;
+// Stopping rule: a sweep records the largest |c_pq| / trace(C) it met before rotating; the solve ends after the
+// first sweep whose record is <= tol. The shrink only needs the residual to be below the fp32 error of the Gram
+// matrix (~1e-7 trace); the scoring basis is taken once per pass and is solved tighter.
+constexpr double JACOBI_TOL_SHRINK = 1e-7;
+constexpr double JACOBI_TOL_BASIS = 1e-9;
+hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st);
 // scalars on device: acc[0] sum_delta, acc[1] frob2, acc[2] last_delta, acc[3] sweeps used (as double)
 hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int frob_r0, int frob_r1, float* Mt,
-                                double* acc, hipStream_t st);
+                                double* acc, double tol, hipStream_t st);
 hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int frob_r0, int frob_r1, float* Mt,
-                               double* acc, hipStream_t st);
+                               double* acc, double tol, hipStream_t st);
 
 // fd_rebuild.hip: out[0:MP] = M * B over every column; Mt is NP x MP (transposed coefficients).
 // zero_tail: also clear buffer rows MP..NP-1 (shrink). out may alias B (in place) when out_NP == NP.
