@@ -449,7 +449,7 @@ __global__ __launch_bounds__(512) void eig_sort_kernel(const double* __restrict_
 }
 
 // Shrink coefficients (Method, FD paragraph: delta = sigma_ell^2, Sigma'_jj = sqrt(max(sigma_j^2 - delta, 0))):
-// new row m = w_m * y_m^T B with w_m = sqrt(max(lambda_m - delta, 0) / lambda_m); stored transposed, Mt[i][m].
+// new row m = w_m * y_m^T B with w_m = sqrt(max(lambda_m - delta, 0) / lambda_m); stored in coeff_offset order.
 __global__ __launch_bounds__(256) void shrink_coeffs_kernel(const double* __restrict__ Y, const int* __restrict__ pos,
                                                             const double* __restrict__ lam,
                                                             const double* __restrict__ diag0, int NP, int LP, int ell,
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(256) void shrink_coeffs_kernel(const double* __rest
         double lm = lam[m];
         double keep = lm - delta;
         double w = (keep > 0.0 && lm > 0.0) ? sqrt(keep / lm) : 0.0;
-        Mt[e] = (w > 0.0) ? (float)(w * Y[(int64_t)i * NP + pos[m]]) : 0.f;
+        Mt[coeff_offset(i, m, LP)] = (w > 0.0) ? (float)(w * Y[(int64_t)i * NP + pos[m]]) : 0.f;
     }
     if (e == 0) {
         acc[0] += delta;
@@ -488,7 +488,7 @@ __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restr
             double lm = lam[m];
             if (lm > thr && lm > 0.0) out = (float)(Y[(int64_t)i * NP + pos[m]] / sqrt(lm));
         }
-        Mt[e] = out;
+        Mt[coeff_offset(i, m, KP)] = out;
     }
     if (e == 0) {
         double f = 0.0;

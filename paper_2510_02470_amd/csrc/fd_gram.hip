@@ -16,14 +16,16 @@ __device__ __forceinline__ void tile_coords(int t, int& ti, int& tj) {
     tj = t - i * (i + 1) / 2;
 }
 
-// P = NP / 64 row panels. 256 threads = 4 waves; a wave owns up to 3 tiles (12 accumulators of 32x32).
+// P = NP / 64 row panels. 256 threads = 4 waves; the unit of work is half a tile (32 rows x 64 columns, two
+// 32x32 accumulators); a wave owns up to 3 units, a work-group 12 (6 tiles), and two work-groups share a CU so
+// that one's LDS reads and barrier waits hide under the other's matrix-core work.
 // Dynamic LDS: 2 stages x NP rows x 64 B, 16-byte pieces XOR-swizzled by (row/4)%4 so that the 16 rows read
 // by a quarter wave fall in distinct banks.
 template <int P>
-__global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ B, float* __restrict__ partial, int tiles,
-                                                   int wg_per_group, int64_t slabs_total, int64_t slabs_per_group) {
+__global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ B, float* __restrict__ partial, int tiles,
+                                                      int wg_per_group, int64_t slabs_total, int64_t slabs_per_group) {
     constexpr int NP = P * 64;
-    constexpr int STAGE = NP * 4;  // float4 pieces per stage
+    constexpr int STAGE = NP * 4;  // 16-byte pieces per stage
     extern __shared__ f32x4 lds[];
 
     const int id = blockIdx.x;
@@ -39,27 +41,27 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ B, 
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, h = lane >> 5;
 
-    int ti[3], tj[3];
+    // unit u = 2 * tile + row half
+    int arow[3], brow[3];
     bool on[3];
-    const int tbase = (w * 4 + wave) * 3;
+    const int ubase = (w * 4 + wave) * 3;
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
-        int t = tbase + q;
-        on[q] = t < tiles;
-        ti[q] = 0;
-        tj[q] = 0;
-        if (on[q]) tile_coords(t, ti[q], tj[q]);
+        int u = ubase + q;
+        on[q] = u < 2 * tiles;
+        int ti = 0, tj = 0;
+        if (on[q]) tile_coords(u >> 1, ti, tj);
+        arow[q] = ti * 64 + (u & 1) * 32 + l32;
+        brow[q] = tj * 64 + l32;
     }
 
-    f32x16 acc[3][2][2];
+    f32x16 acc[3][2];
 #pragma unroll
     for (int q = 0; q < 3; ++q)
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[q][a][b][i] = 0.f;
+            for (int i = 0; i < 16; ++i) acc[q][b][i] = 0.f;
 
     // staging map: slot ps = it*256 + tid holds (row = ps/4, logical piece = (ps%4) ^ ((row/4)%4))
     int src[P];
@@ -91,38 +93,34 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ B, 
             for (int it = 0; it < P; ++it) pre[it] = slab[src[it]];
         }
         const f32x4* st = lds + cur * STAGE;
+        // operands of the whole stage are fetched up front, first the pieces of k-half 0 for every unit, then those of
+        // k-half 1, which land while the matrix cores work on half 0 (units that are switched off read rows that
+        // exist and are simply not written back, so the stage is one straight-line block)
+        f32x4 a[2][3], b[2][3][2];
 #pragma unroll
-        for (int q = 0; q < 3; ++q) {
-            if (on[q]) {
-                f32x4 a[2][2], b[2][2];
+        for (int j = 0; j < 2; ++j) {
+            const int p = 2 * j + h;
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) {
-                    int ra = ti[q] * 64 + rb * 32 + l32;
-                    int rbw = tj[q] * 64 + rb * 32 + l32;
+            for (int q = 0; q < 3; ++q) {
+                const int ra = arow[q];
+                a[j][q] = st[ra * 4 + (p ^ ((ra >> 2) & 3))];
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        int p = 2 * j + h;
-                        a[rb][j] = st[ra * 4 + (p ^ ((ra >> 2) & 3))];
-                        b[rb][j] = st[rbw * 4 + (p ^ ((rbw >> 2) & 3))];
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-#pragma unroll
-                        for (int rb = 0; rb < 2; ++rb) {
-                            float av = a[rb][j][c];
-#pragma unroll
-                            for (int cb = 0; cb < 2; ++cb) {
-                                float bv = b[cb][j][c];
-                                acc[q][rb][cb] = mfma32(av, bv, acc[q][rb][cb]);
-                            }
-                        }
-                    }
+                for (int cb = 0; cb < 2; ++cb) {
+                    const int rb = brow[q] + cb * 32;
+                    b[j][q][cb] = st[rb * 4 + (p ^ ((rb >> 2) & 3))];
                 }
             }
         }
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above: the scheduler would sink each next to its use
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int q = 0; q < 3; ++q)
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb) acc[q][cb] = mfma32(a[j][q][c], b[j][q][cb][c], acc[q][cb]);
+        __builtin_amdgcn_sched_barrier(0);
         if (more) {
             f32x4* nx = lds + (cur ^ 1) * STAGE;
 #pragma unroll
@@ -131,21 +129,20 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ B, 
         __syncthreads();
     }
 
-    // partial[group][tile][64 x 64]
+    // partial[group][tile][64 x 64]; unit u covers rows (u & 1) * 32 .. + 32 of tile u / 2
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
         if (!on[q]) continue;
-        float* out = partial + ((int64_t)group * tiles + (tbase + q)) * 4096;
+        const int u = ubase + q;
+        float* out = partial + ((int64_t)group * tiles + (u >> 1)) * 4096 + (u & 1) * 2048;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    int r = rb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-                    int c = cb * 32 + l32;
-                    out[r * 64 + c] = acc[q][rb][cb][i];
-                }
+            for (int i = 0; i < 16; ++i) {
+                int r = 8 * (i >> 2) + 4 * h + (i & 3);
+                int c = cb * 32 + l32;
+                out[r * 64 + c] = acc[q][cb][i];
+            }
     }
 }
 
@@ -169,8 +166,8 @@ GramPlan gram_plan(const Dims& d, int num_cu) {
     GramPlan p;
     int P = d.NP / 64;
     p.tiles = P * (P + 1) / 2;
-    p.wg_per_group = (p.tiles + 11) / 12;
-    int g = (num_cu / p.wg_per_group) / 8 * 8;
+    p.wg_per_group = (p.tiles + 5) / 6;
+    int g = (2 * num_cu / p.wg_per_group) / 8 * 8;  // two work-groups per CU
     if (g < 8) g = 8;
     // keep at least 4 slabs per group so that tiny problems do not drown in partial tiles
     int64_t gmax = ((d.S + 3) / 4 + 7) / 8 * 8;

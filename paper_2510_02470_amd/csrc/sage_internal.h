@@ -50,7 +50,7 @@ hipError_t launch_zero_rows(float* Bblk, int NP, int r0, int r1, const Dims& d, 
 // fd_gram.hip
 struct GramPlan {
     int tiles;        // 64x64 lower-triangle tiles = P(P+1)/2, P = NP/64
-    int wg_per_group; // ceil(tiles / 12)
+    int wg_per_group; // ceil(tiles / 6): a work-group computes 12 half-tiles
     int groups;       // split-K groups (multiple of 8)
     int64_t slabs_per_group;
     size_t partial_floats; // groups * tiles * 4096
@@ -84,9 +84,19 @@ hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int f
 hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int frob_r0, int frob_r1, float* Mt,
                                double* acc, double tol, hipStream_t st);
 
-// fd_rebuild.hip: out[0:MP] = M * B over every column; Mt is NP x MP (transposed coefficients).
+// Where the coefficient M[m][i] (output row m < MP, buffer row i < NP) is stored for the rebuild kernel: chunks of
+// 16 buffer rows; inside a chunk [i & 1][m][(i & 15) >> 1], i.e. the 8 values a matrix-core lane needs are
+// contiguous, and the two 16-byte halves of those 32 bytes are swapped when (m >> 3) is odd so that a quarter wave
+// reading one half touches every LDS bank once.
+__host__ __device__ inline int64_t coeff_offset(int i, int m, int MP) {
+    const int s = (i & 15) >> 1, h = i & 1;
+    const int piece = (s >> 2) ^ ((m >> 3) & 1);
+    return (int64_t)(i >> 4) * 16 * MP + ((h * MP + m) * 2 + piece) * 4 + (s & 3);
+}
+
+// fd_rebuild.hip: out[0:MP] = M * B over every column; Mc holds the NP x MP coefficients in coeff_offset order.
 // zero_tail: also clear buffer rows MP..NP-1 (shrink). out may alias B (in place) when out_NP == NP.
-hipError_t launch_rebuild(const float* B, const float* Mt, float* out, int out_NP, int MP, bool zero_tail,
+hipError_t launch_rebuild(const float* B, const float* Mc, float* out, int out_NP, int MP, bool zero_tail,
                           const Dims& d, hipStream_t st);
 
 // score.hip
