@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Throughput of the SAGE hot path on one MI355X.
 
-Workload: BASELINE.json's ell = 256 configuration that is quoted in the metric (config 4, "wide streamed
-gradients": D = 1,048,576 fp32 rows, ell = 256, k = 128, batches of 512 rows; --workload 5 gives the bf16
-large-head configuration). Rows are synthetic, generated on the device before the timed region.
+Workload: the largest single-GPU configuration of BASELINE.json at the metric's ell = 256 (config 5, "large-head
+stress": D = 2,049,000 bf16 rows, fp32 sketch and accumulation, ell = 256, k = 128, batches of 1024 rows;
+--workload 4 gives the fp32 D = 1,048,576 configuration). Rows are synthetic, generated on the device before the
+timed region.
 
 A step = one batch through the whole path: sage_fd_update(batch) in pass 1 and sage_score(batch) in pass 2.
 The timed region runs pass 1 over the K batches, forms the basis once (sage_fd_basis), runs pass 2 over the same
@@ -63,9 +64,9 @@ def cpu_baseline(w, seconds_hint=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", type=int, default=4, choices=[3, 4, 5])
+    ap.add_argument("--workload", type=int, default=5, choices=[3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -87,10 +88,11 @@ def main():
     esz = 2 if w.dtype == "bf16" else 4
 
     ds = inputs.DeviceStream(w, w_dtype=torch.bfloat16)
-    batches = [ds.batch(b) for b in range(W + K)]
+    # W warm-up batches, K timed batches, K fresh batches for the per-kernel timing pass
+    batches = [ds.batch(b) for b in range(W + 2 * K)]
     torch.cuda.synchronize()
 
-    s = Sage(w.ell, w.D, dtype=w.dtype, max_rows=(W + K) * w.batch)
+    s = Sage(w.ell, w.D, dtype=w.dtype, max_rows=(W + 2 * K) * w.batch)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
 
     # ---- warm-up: W batches through both passes (fills the buffer, first-use allocations, code load)
@@ -132,10 +134,10 @@ def main():
     if not args.no_kernel_timing:
         s.profile_enable(True)
         s.profile_read()
-        for b in range(W, W + K):
+        for b in range(W + K, W + 2 * K):
             s.fd_update(batches[b])
         s.fd_basis(w.k)
-        for b in range(W, W + K):
+        for b in range(W + K, W + 2 * K):
             s.score(batches[b])
         s.select(w.keep)
         pr = s.profile_read()
