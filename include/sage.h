@@ -135,6 +135,17 @@ int sage_basis_export(sage_ctx* ctx, float* Vt_out);
  */
 int sage_set_basis(sage_ctx* ctx, const float* Vt, int k);
 
+/*
+ * Arithmetic of the projection z = V_k^T g (Algorithm 1, Phase II, first line). SAGE_PROJ_AUTO (default): when
+ * every row of a batch starts on a 16-byte boundary (D * element size a multiple of 16, batch pointer 16-byte
+ * aligned, D >= 64 for bf16 / 32 for fp32 rows, D * element size < 16 MiB) the products run on the bf16 matrix cores
+ * with every fp32 basis entry split as hi + lo (two bf16, relative error <= 2^-17) and fp32 rows split the same
+ * way, accumulated in fp32; otherwise, and always under SAGE_PROJ_F32, on the fp32 matrix cores. Drops the current
+ * basis: call before sage_fd_basis / sage_set_basis.
+ */
+typedef enum { SAGE_PROJ_AUTO = 0, SAGE_PROJ_F32 = 1 } sage_proj_mode;
+int sage_set_projection_mode(sage_ctx* ctx, int mode);
+
 /* View of the scores of the last sage_select: *alpha receives a DEVICE pointer to N fp32 owned by the library,
  * valid until the next scoring call; *n receives N. HOST pointers. */
 int sage_scores(sage_ctx* ctx, const float** alpha, int64_t* n);

@@ -18,7 +18,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 # every symbol include/sage.h declares
 EXPORTS = (
     "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_basis", "sage_score", "sage_select",
-    "sage_destroy", "sage_sync", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
+    "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix",
     "sage_profile_enable",
     "sage_profile_read", "sage_strerror",
@@ -58,6 +58,7 @@ def lib():
     L.sage_destroy.argtypes = [vp]
     L.sage_destroy.restype = None
     L.sage_sync.argtypes = [vp]
+    L.sage_set_projection_mode.argtypes = [vp, i32]
     L.sage_fd_sketch_export.argtypes = [vp, vp]
     L.sage_basis_export.argtypes = [vp, vp]
     L.sage_set_basis.argtypes = [vp, vp, i32]
@@ -134,6 +135,10 @@ class Sage:
         assert Vt.is_cuda and Vt.is_contiguous() and Vt.dtype == self.torch.float32 and Vt.shape[1] == self.D
         _check(self.L.sage_set_basis(self.h, _ptr(Vt), Vt.shape[0]), "sage_set_basis")
         self.k = int(Vt.shape[0])
+
+    def set_projection_mode(self, mode):
+        """0: bf16-split matrix cores when the rows allow it (default); 1: always fp32 matrix cores."""
+        _check(self.L.sage_set_projection_mode(self.h, int(mode)), "sage_set_projection_mode")
 
     def score(self, G):
         G = self._rows(G)

@@ -37,6 +37,10 @@ struct sage_ctx {
     int k = 0, KP = 0;
     float* Vblk = nullptr;
     int Vblk_KP = 0;
+    void* Vimg = nullptr;      // bf16 hi/lo chunk images of the basis (score_split.hip); built when the rows allow it
+    size_t Vimg_bytes = 0;
+    bool img_ok = false;
+    int proj_mode = SAGE_PROJ_AUTO;
     float* zhat = nullptr;
     int64_t cap_rows = 0, n_scored = 0;
     bool fixed_cap = false;
@@ -124,7 +128,7 @@ void reset_scoring(sage_ctx* c) {
 
 int ensure_score_buffers(sage_ctx* c) {
     if (!c->ssum) ALLOC(c->ssum, 128 * sizeof(double));
-    if (!c->cons_partial) ALLOC(c->cons_partial, (size_t)(SCORE_CHUNK / 16) * 128 * sizeof(double));
+    if (!c->cons_partial) ALLOC(c->cons_partial, (size_t)(SCORE_CHUNK / 4) * 128 * sizeof(double));  // one per 4 rows
     if (!c->zhat) {
         ALLOC(c->zhat, (size_t)c->cap_rows * 128 * sizeof(float));
     }
@@ -141,6 +145,27 @@ int ensure_vblk(sage_ctx* c, int KP) {
     }
     ALLOC(c->Vblk, (size_t)c->d.S * KP * DC * sizeof(float));
     c->Vblk_KP = KP;
+    return SAGE_OK;
+}
+
+// After Vblk holds a new basis: build the bf16 hi/lo images when the split projection can be used for this D.
+int finish_basis(sage_ctx* c) {
+    c->img_ok = false;
+    if (c->proj_mode == SAGE_PROJ_F32) return SAGE_OK;
+    if (!split_path_ok(nullptr, c->dtype, c->d)) return SAGE_OK;  // nullptr is "aligned": only D is judged here
+    const size_t need = basis_image_bytes(c->KP, c->dtype, c->d);
+    if (need > c->Vimg_bytes) {
+        if (c->Vimg) {
+            HIPCHK(hipStreamSynchronize(c->st));
+            (void)hipFree(c->Vimg);
+            c->Vimg = nullptr;
+            c->Vimg_bytes = 0;
+        }
+        ALLOC(c->Vimg, need);
+        c->Vimg_bytes = need;
+    }
+    RUN(K_REBUILD, launch_basis_split(c->Vblk, c->KP, c->dtype, c->Vimg, c->d, c->st));
+    c->img_ok = true;
     return SAGE_OK;
 }
 
@@ -254,7 +279,7 @@ void sage_destroy(sage_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->st);
     void* ptrs[] = {c->B,       c->gram_partial, c->ew.C, c->ew.Y, c->ew.C2, c->ew.Y2, c->ew.Q,         c->ew.diag0, c->ew.stat,
-                    c->ew.pos,  c->ew.lam,       c->Mt,   c->acc,          c->Vblk,         c->zhat,     c->proj_partial,
+                    c->ew.pos,  c->ew.lam,       c->Mt,   c->acc,          c->Vblk,         c->Vimg,      c->zhat,     c->proj_partial,
                     c->cons_partial, c->ssum,    c->alpha};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -305,9 +330,18 @@ int sage_fd_basis(sage_ctx* c, int k) {
     RUN(K_REBUILD, launch_rebuild(c->B, c->Mt, c->Vblk, KP, KP, false, c->d, c->st));
     c->k = k;
     c->KP = KP;
+    rc = finish_basis(c);
+    if (rc != SAGE_OK) return rc;
     c->has_basis = true;
     reset_scoring(c);
     return ensure_score_buffers(c);
+}
+
+int sage_set_projection_mode(sage_ctx* c, int mode) {
+    if (!c || (mode != SAGE_PROJ_AUTO && mode != SAGE_PROJ_F32)) return SAGE_ERR_ARG;
+    c->proj_mode = mode;
+    c->has_basis = false;
+    return SAGE_OK;
 }
 
 int sage_set_basis(sage_ctx* c, const float* Vt, int k) {
@@ -318,6 +352,8 @@ int sage_set_basis(sage_ctx* c, const float* Vt, int k) {
     HIPCHK(launch_import_rows(Vt, k, c->Vblk, KP, c->d, c->st));
     c->k = k;
     c->KP = KP;
+    rc = finish_basis(c);
+    if (rc != SAGE_OK) return rc;
     c->has_basis = true;
     reset_scoring(c);
     return ensure_score_buffers(c);
@@ -347,7 +383,8 @@ int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) {
     const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
     while (rows > 0) {
         int64_t R = rows < SCORE_CHUNK ? rows : SCORE_CHUNK;
-        ScorePlan p = score_plan(R, c->d, c->num_cu);
+        const bool split = c->img_ok && split_path_ok(g, c->dtype, c->d);
+        ScorePlan p = split ? score_split_plan(R, c->dtype, c->d, c->num_cu) : score_plan(R, c->d, c->num_cu);
         size_t need = (size_t)p.splits * R * c->KP;
         if (need > c->proj_partial_floats) {
             if (c->proj_partial) {
@@ -360,7 +397,10 @@ int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) {
             ALLOC(c->proj_partial, want * sizeof(float));
             c->proj_partial_floats = want;
         }
-        RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
+        if (split)
+            RUN(K_PROJECT, launch_project_split(g, c->dtype, R, c->Vimg, c->KP, c->proj_partial, p, c->d, c->st));
+        else
+            RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
         RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, p.splits,
                                              c->zhat + (size_t)c->n_scored * c->k, c->cons_partial, c->ssum, c->st));
         c->n_scored += R;

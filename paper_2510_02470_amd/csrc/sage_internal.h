@@ -111,6 +111,17 @@ hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk
 hipError_t launch_score_finalize(const float* partial, int64_t R, int KP, int k, int splits, float* zhat_out,
                                  double* cons_partial, double* ssum, hipStream_t st);
 
+// score_split.hip: the same projection on the bf16 matrix cores with the basis split as hi + lo (bf16 each).
+// The basis is kept as per-chunk LDS images built once per basis by launch_basis_split (from the fp32 slabs).
+// Usable when every row starts on a 16-byte boundary (split_path_ok); ScorePlan::slabs_per_split then counts
+// chunks of 128 row bytes.
+bool split_path_ok(const void* G, int dtype, const Dims& d);
+size_t basis_image_bytes(int KP, int dtype, const Dims& d);
+hipError_t launch_basis_split(const float* Vblk, int KP, int dtype, void* img, const Dims& d, hipStream_t st);
+ScorePlan score_split_plan(int64_t R, int dtype, const Dims& d, int num_cu);
+hipError_t launch_project_split(const void* G, int dtype, int64_t R, const void* img, int KP, float* partial,
+                                const ScorePlan& p, const Dims& d, hipStream_t st);
+
 // select.hip
 hipError_t launch_cosine(const float* zhat, int64_t N, int k, const double* ssum, float* alpha, hipStream_t st);
 struct SelectWork {

@@ -147,52 +147,91 @@ __global__ __launch_bounds__(256) void project_kernel(const T* __restrict__ G, i
         }
 }
 
-// 16 rows per work-group, one wave per row at a time; lane j holds coordinates j and j + 64.
-// Writes zhat (R x k, fp32) and cons_partial[block][128] (fp64 sums of the block's zhat).
+// Sum of the split-K partial projections, normalisation and consensus partial sums.
+// 4 rows per work-group, one after the other; for a row each of the 4 waves adds a quarter of the splits (in order,
+// eight independent loads at a time), the quarters are added in wave order, and lane j then holds coordinates j and
+// j + 64. Writes zhat (R x k, fp32) and cons_partial[block][128] (fp64 sums of the block's zhat). All in fp64, fixed
+// order: the result does not depend on timing.
+constexpr int FIN_ROWS = 4;
 __global__ __launch_bounds__(256) void score_finalize_kernel(const float* __restrict__ partial, int64_t R, int KP, int k,
                                                              int splits, float* __restrict__ zhat,
                                                              double* __restrict__ cons_partial) {
-    __shared__ double red[4][128];
+    __shared__ double zs[4][128];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const bool on0 = lane < KP, on1 = lane + 64 < KP;
+    const int s_lo = (int)((int64_t)wave * splits / 4), s_hi = (int)((int64_t)(wave + 1) * splits / 4);
     double cons0 = 0.0, cons1 = 0.0;
-    for (int q = 0; q < 4; ++q) {
-        int64_t r = (int64_t)blockIdx.x * 16 + wave * 4 + q;
+    for (int q = 0; q < FIN_ROWS; ++q) {
+        const int64_t r = (int64_t)blockIdx.x * FIN_ROWS + q;
         if (r >= R) break;
         double z0 = 0.0, z1 = 0.0;
-        for (int s = 0; s < splits; ++s) {
-            const float* p = partial + ((int64_t)s * R + r) * KP;
-            if (lane < k) z0 += (double)p[lane];
-            if (lane + 64 < k) z1 += (double)p[lane + 64];
+        for (int s = s_lo; s < s_hi; s += 8) {
+            float v0[8], v1[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int ss = s + u < s_hi ? s + u : s_hi - 1;  // repeats are not added
+                const float* p = partial + ((int64_t)ss * R + r) * KP;
+                v0[u] = on0 ? p[lane] : 0.f;
+                v1[u] = on1 ? p[lane + 64] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s + u < s_hi) {
+                    z0 += (double)v0[u];
+                    z1 += (double)v1[u];
+                }
         }
-        double q2 = z0 * z0 + z1 * z1;
-        for (int o = 32; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
-        double nrm = sqrt(q2);
-        float h0 = 0.f, h1 = 0.f;
-        if (nrm > 0.0) {
-            h0 = (float)(z0 / nrm);
-            h1 = (float)(z1 / nrm);
+        zs[wave][lane] = z0;
+        zs[wave][lane + 64] = z1;
+        __syncthreads();
+        if (wave == 0) {
+            z0 = ((zs[0][lane] + zs[1][lane]) + zs[2][lane]) + zs[3][lane];
+            z1 = ((zs[0][lane + 64] + zs[1][lane + 64]) + zs[2][lane + 64]) + zs[3][lane + 64];
+            if (lane >= k) z0 = 0.0;
+            if (lane + 64 >= k) z1 = 0.0;
+            double q2 = z0 * z0 + z1 * z1;
+            for (int o = 32; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
+            const double nrm = sqrt(q2);
+            float h0 = 0.f, h1 = 0.f;
+            if (nrm > 0.0) {
+                h0 = (float)(z0 / nrm);
+                h1 = (float)(z1 / nrm);
+            }
+            if (lane < k) zhat[r * k + lane] = h0;
+            if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
+            cons0 += (double)h0;
+            cons1 += (double)h1;
         }
-        if (lane < k) zhat[r * k + lane] = h0;
-        if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
-        cons0 += (double)h0;
-        cons1 += (double)h1;
+        __syncthreads();
     }
-    red[wave][lane] = cons0;
-    red[wave][lane + 64] = cons1;
-    __syncthreads();
-    if (tid < 128) {
-        double s = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
-        cons_partial[(int64_t)blockIdx.x * 128 + tid] = s;
+    if (wave == 0) {
+        cons_partial[(int64_t)blockIdx.x * 128 + lane] = cons0;
+        cons_partial[(int64_t)blockIdx.x * 128 + lane + 64] = cons1;
     }
 }
 
-__global__ __launch_bounds__(128) void consensus_add_kernel(const double* __restrict__ cons_partial, int nblocks, int k,
-                                                            double* __restrict__ ssum) {
-    int j = threadIdx.x;
-    if (j >= k) return;
+// ssum[j] += sum over blocks of cons_partial[block][j]: thread (group g = tid / 128, coordinate j = tid % 128) adds
+// blocks g, g + 8, ... in order, the 8 group sums are then added in group order.
+__global__ __launch_bounds__(1024) void consensus_add_kernel(const double* __restrict__ cons_partial, int nblocks, int k,
+                                                             double* __restrict__ ssum) {
+    __shared__ double red[8][128];
+    const int j = threadIdx.x & 127, g = threadIdx.x >> 7;
     double s = 0.0;
-    for (int b = 0; b < nblocks; ++b) s += cons_partial[(int64_t)b * 128 + j];
-    ssum[j] += s;
+    for (int b = g; b < nblocks; b += 32) {
+        double v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = (b + 8 * u < nblocks) ? cons_partial[(int64_t)(b + 8 * u) * 128 + j] : 0.0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += v[u];
+    }
+    red[g][j] = s;
+    __syncthreads();
+    if (g == 0 && j < k) {
+        double t = 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t += red[u][j];
+        ssum[j] += t;
+    }
 }
 
 ScorePlan score_plan(int64_t R, const Dims& d, int num_cu) {
@@ -239,10 +278,10 @@ hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk
 
 hipError_t launch_score_finalize(const float* partial, int64_t R, int KP, int k, int splits, float* zhat_out,
                                  double* cons_partial, double* ssum, hipStream_t st) {
-    int nblocks = (int)((R + 15) / 16);
+    int nblocks = (int)((R + FIN_ROWS - 1) / FIN_ROWS);
     hipLaunchKernelGGL(score_finalize_kernel, dim3(nblocks), dim3(256), 0, st, partial, R, KP, k, splits, zhat_out,
                        cons_partial);
-    hipLaunchKernelGGL(consensus_add_kernel, dim3(1), dim3(128), 0, st, cons_partial, nblocks, k, ssum);
+    hipLaunchKernelGGL(consensus_add_kernel, dim3(1), dim3(1024), 0, st, cons_partial, nblocks, k, ssum);
     return hipGetLastError();
 }
 

@@ -106,6 +106,10 @@ def _small_workloads():
         "cfg4_small": W[4].scaled(N=1100, D=4096, batch=512),
         "cfg5_small_bf16": W[5].scaled(N=1300, D=3000, batch=1024),
         "odd_ell": W[1].scaled(N=400, D=333, ell=23, k=7, batch=50),
+        # rows that start on 16-byte boundaries with a ragged last chunk: the bf16-split projection, every tile count
+        "cfg3_k64_f32_aligned": W[3].scaled(N=700, D=5136, batch=300),
+        "cfg5_k64_bf16_aligned": W[5].scaled(N=700, D=3016, ell=128, k=64, batch=333),
+        "cfg5_k20_bf16_aligned": W[5].scaled(N=600, D=1096, ell=64, k=20, batch=600),
     }
 
 
@@ -153,13 +157,18 @@ def test_sketch_is_deterministic():
 
 
 # ------------------------------------------------------------------------------------------ scoring parity
-@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg3_small", "cfg4_small", "cfg5_small_bf16", "odd_ell"])
-def test_scores_with_oracle_basis(name):
+# mode 0: bf16-split matrix cores where the rows are 16-byte aligned (else fp32); mode 1: fp32 matrix cores always
+@pytest.mark.parametrize("name,mode", [("cfg1", 0), ("cfg1", 1), ("cfg2_small", 0), ("cfg3_small", 0), ("cfg4_small", 0),
+                                       ("cfg4_small", 1), ("cfg5_small_bf16", 0), ("cfg5_small_bf16", 1), ("odd_ell", 0),
+                                       ("cfg3_k64_f32_aligned", 0), ("cfg5_k64_bf16_aligned", 0),
+                                       ("cfg5_k20_bf16_aligned", 0)])
+def test_scores_with_oracle_basis(name, mode):
     """Stage-isolated: both sides project on the oracle's basis, so only the scoring arithmetic is compared."""
     B = _binding()
     w, G, o, oidx = _oracle_run(name)
     V = o.V
     s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    s.set_projection_mode(mode)
     s.set_basis(torch.from_numpy(V.astype(np.float32)).cuda())
     o2 = Oracle(w.ell, w.D, 1)
     o2.set_basis(V.astype(np.float32).astype(np.float64))  # the very same (fp32-rounded) basis on both sides
