@@ -47,16 +47,10 @@ __device__ __forceinline__ int img_piece(int cc, int p) {
     else return cc * 4 + (p ^ ((cc >> 1) & 3));
 }
 
-// First column of chunk c: c*KC, except that the last chunk is moved back to end exactly at column D (so that a
-// lane never reads beyond its row); the columns it then shares with the chunk before are zero in its image.
-__host__ __device__ inline int64_t chunk_start(int64_t c, int KC, int64_t D) {
-    int64_t s = c * KC;
-    return s + KC > D ? D - KC : s;
-}
-
-// One thread writes one 16-byte piece. Vblk is the fp32 column-slab basis (KP rows). Needs D >= KC.
+// One thread writes one 16-byte piece. Vblk is the fp32 column-slab basis (KP rows); columns >= D are zero there and
+// columns >= Dp are written as zero here.
 template <int KC>
-__global__ __launch_bounds__(256) void basis_split_kernel(const float* __restrict__ Vblk, int KP, int64_t D,
+__global__ __launch_bounds__(256) void basis_split_kernel(const float* __restrict__ Vblk, int KP, int64_t Dp,
                                                           int64_t chunks, u32x4* __restrict__ img) {
     constexpr int PPR = KC / 8;
     const int64_t per_chunk = (int64_t)2 * KP * PPR;
@@ -66,12 +60,14 @@ __global__ __launch_bounds__(256) void basis_split_kernel(const float* __restric
     const int rem = (int)(i % per_chunk);
     const int cc = rem / PPR, p = rem % PPR;
     const int row = cc < KP ? cc : cc - KP;
-    const int64_t d0 = chunk_start(c, KC, D) + p * 8;
+    const int64_t d0 = c * KC + p * 8;
     float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int64_t d = d0 + e;
-        v[e] = (d >= c * KC) ? Vblk[blk_off(d, row, KP)] : 0.f;  // d < D always
+    for (int e = 0; e < 8; ++e) v[e] = 0.f;
+    if (d0 < Dp) {  // 8 | DC: the piece lies inside one slab
+        const float* src = Vblk + blk_off(d0, row, KP);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[e];
     }
     u32x4 out;
 #pragma unroll
@@ -94,9 +90,9 @@ hipError_t launch_basis_split(const float* Vblk, int KP, int dtype, void* img, c
     const int64_t total = chunks * 2 * KP * (KC / 8);
     dim3 grid((unsigned)((total + 255) / 256));
     if (KC == 64)
-        hipLaunchKernelGGL(basis_split_kernel<64>, grid, dim3(256), 0, st, Vblk, KP, d.D, chunks, (u32x4*)img);
+        hipLaunchKernelGGL(basis_split_kernel<64>, grid, dim3(256), 0, st, Vblk, KP, d.Dp, chunks, (u32x4*)img);
     else
-        hipLaunchKernelGGL(basis_split_kernel<32>, grid, dim3(256), 0, st, Vblk, KP, d.D, chunks, (u32x4*)img);
+        hipLaunchKernelGGL(basis_split_kernel<32>, grid, dim3(256), 0, st, Vblk, KP, d.Dp, chunks, (u32x4*)img);
     return hipGetLastError();
 }
 
@@ -107,24 +103,6 @@ size_t basis_image_bytes(int KP, int dtype, const Dims& d) {
 }
 
 // ---- projection -------------------------------------------------------------------------------------------
-// Row operand of one chunk for one 32-row tile: 4 pieces of 16 bytes per lane.
-//   bf16 rows: piece j (k-step j) = columns 16 j + 8 h .. + 8 of the chunk.
-//   fp32 rows: pieces 2j, 2j + 1   = columns 16 j + 8 h .. + 8 of the chunk (two k-steps per chunk).
-// The address is (wave-uniform chunk base) + (32-bit lane offset) + (compile-time piece offset), which lets the
-// loads use the scalar-base addressing form: one offset register per row tile.
-template <typename T>
-struct RowOp {
-    u32x4 v[4];
-};
-
-template <typename T>
-__device__ __forceinline__ void load_piece(RowOp<T>& a, const char* __restrict__ chunk_base, unsigned lane_off, int q) {
-    int off;
-    if constexpr (sizeof(T) == 2) off = 32 * q;
-    else off = 64 * (q >> 1) + 16 * (q & 1);
-    a.v[q] = *reinterpret_cast<const u32x4*>(chunk_base + lane_off + off);
-}
-
 // fp32 pieces (8 values in two u32x4) -> bf16 hi and lo operands
 __device__ __forceinline__ void split8(const u32x4& x0, const u32x4& x1, u32x4& hi, u32x4& lo) {
 #pragma unroll
@@ -137,18 +115,37 @@ __device__ __forceinline__ void split8(const u32x4& x0, const u32x4& x1, u32x4& 
     }
 }
 
+// Rows of a batch are D * sizeof(T) bytes apart, which in general is not a multiple of the 128-byte memory line, so a
+// row's k-th 128 bytes straddle two lines and a kernel that walks every row in steps of 128 bytes from the row
+// start fetches most lines twice. Here a wave only holds rows whose start addresses are congruent modulo 128 (rows
+// w, w + 8, w + 16, ... of the work-group's 512: 8 * pitch is a multiple of 128 because the pitch is a multiple of 16)
+// and walks them in line-aligned windows: with phi = (row address mod 128) / (bytes of 8 columns), window m of the
+// wave is the 128 bytes that start 8*phi columns before column m*KC. Its basis operand is then the last phi pieces
+// of image m-1 followed by the first PPR-phi pieces of image m, so LDS keeps a ring of three images (m-1, m, and
+// m+1 on its way in). The first and the last window of a split reach into the neighbouring splits; those pieces
+// of the row operand are zeroed.
+//
+// Work-group = 512 threads = 8 waves (two per SIMD), one per CU, 512 batch rows x KP basis columns; a wave owns 64
+// rows (2 accumulator row tiles) x KP columns. Row operands go straight from global memory to registers, the pieces
+// of window m+2 being requested as soon as the matrix cores are done with the same pieces of window m; images are
+// streamed with direct global->LDS loads.
+template <typename T>
+struct RowOp {
+    u32x4 v[4];  // bf16 rows: v[j] = k-step j; fp32 rows: v[2j], v[2j+1] = k-step j
+};
+
 template <int NT, typename T>  // NT = KP / 32
-__global__ __launch_bounds__(256, 2) void project_split_kernel(const T* __restrict__ G, int64_t R,
+__global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restrict__ G, int64_t R,
                                                                const u32x4* __restrict__ img,
                                                                float* __restrict__ partial, int row_tiles, int64_t D,
                                                                int64_t chunks_total, int64_t chunks_per_split) {
     constexpr int KP = NT * 32;
     constexpr int KC = 128 / (int)sizeof(T);
-    constexpr int PPR = KC / 8;
+    constexpr int PPR = KC / 8;        // pieces (8 columns) per window
+    constexpr int PB = 8 * (int)sizeof(T);  // bytes of a piece in a row: 16 or 32
     constexpr int IMG = 2 * KP * PPR;  // 16-byte pieces per image
-    constexpr int ROUNDS = IMG / 256;  // staging rounds of the work-group (IMG is a multiple of 256)
-    constexpr int KS = KC / 16;        // matrix-core k-steps per chunk
-    __shared__ u32x4 lds[2 * IMG];
+    constexpr int KS = KC / 16;        // matrix-core k-steps per window
+    extern __shared__ u32x4 lds[];     // 3 * IMG
 
     const int id = blockIdx.x;
     const int xcd = id & 7, y = id >> 3;
@@ -157,26 +154,48 @@ __global__ __launch_bounds__(256, 2) void project_split_kernel(const T* __restri
     const int64_t c0 = (int64_t)split * chunks_per_split;
     int64_t c1 = c0 + chunks_per_split;
     if (c1 > chunks_total) c1 = chunks_total;
+    const int64_t nc = c1 - c0;
+    const int64_t nv = nc > 0 ? nc + 1 : 0;  // windows c0 .. c1
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
-    const int64_t row_base = (int64_t)rt * 256 + wave * 64;
+    const int64_t S = D * (int64_t)sizeof(T);  // row pitch in bytes
+    const int64_t row0 = (int64_t)rt * 512;
+    // phase of this wave's rows, in pieces
+    const int phi = (int)(((reinterpret_cast<uintptr_t>(G) + (uintptr_t)((row0 + wave) * S)) & 127) / PB);
 
-    // byte offset of this lane's first piece from the first row of the work-group's row tile; rows >= R repeat row R-1
-    const char* gwg = reinterpret_cast<const char*>(G) + (int64_t)rt * 256 * D * (int64_t)sizeof(T);
-    unsigned loff[2];
+    // Lane offsets are taken from gbase = (first row of the work-group) - 128 bytes, so that they are never negative;
+    // every offset is clamped to its own row, so no lane reads outside the batch (pieces outside the row meet zeros
+    // of the image or are zeroed below). Rows >= R repeat row R-1; their results are not written.
+    const char* gbase = reinterpret_cast<const char*>(G) + row0 * S - 128;
+    unsigned lbase[2];
+    const unsigned back = (unsigned)(PB * phi) - (unsigned)(PB * h);  // lbase - back = offset of the row's first byte
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        int64_t r = row_base + t * 32 + n;
+        int64_t r = row0 + wave + 8 * (t * 32 + n);
         if (r > R - 1) r = R - 1;
-        loff[t] = (unsigned)((r - (int64_t)rt * 256) * D * (int64_t)sizeof(T)) + (unsigned)(h * (sizeof(T) == 2 ? 16 : 32));
+        lbase[t] = (unsigned)((r - row0) * S) + 128u - back;
     }
-    auto chunk_ptr = [&](int64_t c) { return gwg + chunk_start(c, KC, D) * (int64_t)sizeof(T); };
-    // LDS piece index of this lane's basis operand for k-step j, column tile 0 (tile ct adds ct * 32 * PPR)
+    // piece x of window m for row tile t
+    auto load_piece = [&](RowOp<T>& a, int t, int64_t m, int x) {
+        const int xoff = sizeof(T) == 2 ? 32 * x : 64 * (x >> 1) + 16 * (x & 1);
+        const unsigned lo = lbase[t] + back, hi = lo + (unsigned)S - 16u;
+        unsigned o = lbase[t] + (unsigned)(m * 128) + (unsigned)xoff;
+        o = o < lo ? lo : o;
+        o = o > hi ? hi : o;
+        a.v[x] = *reinterpret_cast<const u32x4*>(gbase + o);
+    };
+    // LDS piece index (inside one image, column tile 0) of this lane's basis operand for k-step j, and whether it
+    // lies in the previous image
     int boff[KS];
+    bool prev[KS];
 #pragma unroll
-    for (int j = 0; j < KS; ++j) boff[j] = img_piece<KC>(n, 2 * j + h);
+    for (int j = 0; j < KS; ++j) {
+        const int q = 2 * j + h;
+        prev[j] = q < phi;
+        boff[j] = img_piece<KC>(n, (q - phi) & (PPR - 1));
+    }
 
     f32x16 acc[2][NT];
 #pragma unroll
@@ -186,37 +205,56 @@ __global__ __launch_bounds__(256, 2) void project_split_kernel(const T* __restri
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[t][ct][i] = 0.f;
 
-    auto stage = [&](int64_t c, int buf) {
-        const u32x4* src = img + c * IMG + tid;
+    auto image_of = [&](int64_t c) {  // images outside the matrix repeat the nearest one (finite data, never counted)
+        return c < 0 ? (int64_t)0 : (c > chunks_total - 1 ? chunks_total - 1 : c);
+    };
+    auto stage = [&](int64_t c, int slot) {
+        const u32x4* src = img + image_of(c) * IMG + tid;
 #pragma unroll
-        for (int q = 0; q < ROUNDS; ++q)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + q * 256),
-                                             (__attribute__((address_space(3))) void*)(lds + buf * IMG + q * 256 + wave * 64),
+        for (int q = 0; q < IMG / 512; ++q)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + q * 512),
+                                             (__attribute__((address_space(3))) void*)(lds + slot * IMG + q * 512 + wave * 64),
                                              16, 0, 0);
+        if constexpr (IMG % 512 != 0) {  // IMG = 256 (KP = 32, fp32 rows): half a round
+            if (wave < 4)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
+                                                 (__attribute__((address_space(3))) void*)(lds + slot * IMG + wave * 64), 16,
+                                                 0, 0);
+        }
     };
-    // The split's chunks are visited in rotated order (start = a multiple of the split index): with a power-of-two
-    // row pitch all work-groups would otherwise walk the same low address bits, i.e. the same memory channels, in
-    // lock step. The work-groups of one split (different row tiles) keep the same order and share the images in L2.
-    // Visits beyond the last repeat the last chunk (prefetches whose data is never used).
-    const int64_t nc = c1 - c0;
-    const int64_t phase = nc > 0 ? ((int64_t)split * 37) % nc : 0;
-    auto chunk_of = [&](int64_t i) {
-        int64_t c = c0 + (i < nc ? i : nc - 1) + phase;
-        return c >= c1 ? c - nc : c;
-    };
-    // One visit. Step s = (k-step j, column tile ct) in order; the basis operand of step s + 2 is fetched from LDS
+
+    // One window. Step s = (k-step j, column tile ct) in order; the basis operand of step s + 1 is fetched from LDS
     // before the matrix-core instructions of step s are issued, and the scheduler may not move anything across a
-    // step (left alone it hoists a whole chunk of LDS reads and spills). As soon as k-step j is done its row
-    // registers are reloaded with the same pieces of the visit after next, so a row load has two visits to land.
-    auto visit = [&](RowOp<T> (&a)[2], int64_t i, int buf) {
-        stage(chunk_of(i + 1), buf ^ 1);
-        const char* gnext = chunk_ptr(chunk_of(i + 2));
-        const u32x4* vs = lds + buf * IMG;
+    // step (left alone it hoists a whole window of LDS reads and spills). sp / sc / sn: ring slots of images m-1, m
+    // and m+1. a: row operand of this window; afar: buffer that receives window m+2.
+    auto visit = [&](RowOp<T> (&a)[2], RowOp<T> (&afar)[2], int64_t i, int sp, int sc, int sn) {
+        const int64_t m = c0 + i;
+        stage(m + 1, sn);
+        // all 8 row loads of window m+2 together: the four pieces of a line are asked for back to back, while the
+        // line is still on its way or fresh in the vector cache
+        const int64_t m2 = m + 2 > c1 ? c1 : m + 2;  // beyond the last window: repeat it (never used)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) load_piece(afar[t], t, m2, x);
+        if (i == 0 || i == nv - 1) {
+            const bool first = i == 0, last = i == nv - 1;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int q = 2 * (sizeof(T) == 2 ? x : (x >> 1)) + h;
+                    if ((first && q < phi) || (last && q >= phi)) a[t].v[x] = u32x4{0u, 0u, 0u, 0u};
+                }
+        }
+        int baddr[KS];
+#pragma unroll
+        for (int j = 0; j < KS; ++j) baddr[j] = boff[j] + (prev[j] ? sp : sc) * IMG;
         constexpr int STEPS = KS * 2 * NT;
-        u32x4 b[3];
-        b[0] = vs[boff[0]];
-        b[1] = vs[boff[0] + 32 * PPR];
+        u32x4 b[2];
+        b[0] = lds[baddr[0]];
         u32x4 ahi[2], alo[2];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             const int j = s / (2 * NT), ct = s % (2 * NT);
@@ -229,11 +267,11 @@ __global__ __launch_bounds__(256, 2) void project_split_kernel(const T* __restri
                     split8(a[1].v[2 * j], a[1].v[2 * j + 1], ahi[1], alo[1]);
                 }
             }
-            if (s + 2 < STEPS) {
-                const int j2 = (s + 2) / (2 * NT), ct2 = (s + 2) % (2 * NT);
-                b[(s + 2) % 3] = vs[boff[j2] + ct2 * 32 * PPR];
+            if (s + 1 < STEPS) {
+                const int j2 = (s + 1) / (2 * NT), ct2 = (s + 1) % (2 * NT);
+                b[(s + 1) % 2] = lds[baddr[j2] + ct2 * 32 * PPR];
             }
-            const u32x4 bb = b[s % 3];
+            const u32x4 bb = b[s % 2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) acc[t][ct % NT] = mfma_bf16(ahi[t], bb, acc[t][ct % NT]);
             if constexpr (sizeof(T) == 4) {
@@ -243,50 +281,40 @@ __global__ __launch_bounds__(256, 2) void project_split_kernel(const T* __restri
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (ct == 2 * NT - 1) {
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    if constexpr (sizeof(T) == 2) {
-                        load_piece<T>(a[t], gnext, loff[t], j);
-                    } else {
-                        load_piece<T>(a[t], gnext, loff[t], 2 * j);
-                        load_piece<T>(a[t], gnext, loff[t], 2 * j + 1);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
-        // 8 row loads were issued after this visit's image loads: once at most 8 loads are outstanding the image of
-        // the next visit (and every older load) has landed. vmcnt(8), expcnt and lgkmcnt not waited for.
-        // A bare barrier: __syncthreads() carries a release fence, which on this target drains every outstanding
-        // load (vmcnt(0)) and would throw the prefetch distance away. The LDS reads of this visit have all been
-        // consumed by matrix-core instructions above, so there is nothing else to wait for.
-        __builtin_amdgcn_sched_barrier(0);
+        // 8 row loads were issued after this window's image loads: once at most 8 loads are outstanding the next
+        // image (and every older load) has landed. A bare barrier: __syncthreads() carries a release fence, which on
+        // this target drains every outstanding load and would throw the prefetch distance away. The LDS reads of this
+        // window have all been consumed by matrix-core instructions above.
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0x0F78);
-        __builtin_amdgcn_s_barrier();  // every wave has the image, and every wave is done reading this visit's image
+        __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8); expcnt, lgkmcnt not waited for
+        __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    RowOp<T> a[2], an[2];
-    if (nc > 0) {
-        stage(chunk_of(0), 0);
+    RowOp<T> a0[2], a1[2], a2[2];
+    if (nv > 0) {
+        stage(c0 - 1, 0);
+        stage(c0, 1);
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                load_piece<T>(a[t], chunk_ptr(chunk_of(0)), loff[t], q);
-                load_piece<T>(an[t], chunk_ptr(chunk_of(1)), loff[t], q);
+            for (int x = 0; x < 4; ++x) {
+                load_piece(a0[t], t, c0, x);
+                load_piece(a1[t], t, c0 + 1, x);
             }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        // three windows per trip: the row buffers and the ring slots return to their roles
         int64_t i = 0;
-        for (; i + 1 < nc; i += 2) {
-            visit(a, i, 0);
-            visit(an, i + 1, 1);
+        for (; i + 2 < nv; i += 3) {
+            visit(a0, a2, i, 0, 1, 2);
+            visit(a1, a0, i + 1, 1, 2, 0);
+            visit(a2, a1, i + 2, 2, 0, 1);
         }
-        if (i < nc) visit(a, i, 0);
+        if (i < nv) visit(a0, a2, i, 0, 1, 2);
+        if (i + 1 < nv) visit(a1, a0, i + 1, 1, 2, 0);
     }
 
     float* out = partial + (int64_t)split * R * KP;
@@ -296,25 +324,25 @@ __global__ __launch_bounds__(256, 2) void project_split_kernel(const T* __restri
         for (int ct = 0; ct < NT; ++ct)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                int64_t r = row_base + t * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+                const int64_t r = row0 + wave + 8 * (t * 32 + 8 * (i >> 2) + 4 * h + (i & 3));
                 if (r < R) out[r * KP + ct * 32 + n] = acc[t][ct][i];
             }
 }
 
-// Every row must start on a 16-byte boundary, hold at least one chunk, and 256 rows must span < 4 GiB (lane offsets
-// are 32-bit).
+// Every row must start on a multiple of the bytes of 8 columns (16 for bf16, 32 for fp32 rows), hold at least one
+// chunk, and 512 rows plus a line must span < 4 GiB (lane offsets are 32-bit).
 bool split_path_ok(const void* G, int dtype, const Dims& d) {
     const int64_t esz = dtype == SAGE_BF16 ? 2 : 4;
     const int64_t KC = 128 / esz;
-    return (d.D * esz) % 16 == 0 && d.D >= KC && d.D * esz * 256 < ((int64_t)1 << 32) && ((uintptr_t)G) % 16 == 0;
+    return d.D % 8 == 0 && d.D >= KC && d.D * esz * 513 + 256 < ((int64_t)1 << 32) && ((uintptr_t)G) % (8 * esz) == 0;
 }
 
 ScorePlan score_split_plan(int64_t R, int dtype, const Dims& d, int num_cu) {
     ScorePlan p;
     const int KC = dtype == SAGE_BF16 ? 64 : 32;
     const int64_t chunks = (d.D + KC - 1) / KC;
-    p.row_tiles = (int)((R + 255) / 256);
-    int64_t want = ((int64_t)num_cu * 2 + p.row_tiles - 1) / p.row_tiles;
+    p.row_tiles = (int)((R + 511) / 512);
+    int64_t want = ((int64_t)num_cu + p.row_tiles - 1) / p.row_tiles;  // one work-group per CU
     int64_t s = (want + 7) / 8 * 8;
     int64_t smax = ((chunks + 7) / 8 + 7) / 8 * 8;  // at least ~8 chunks per split
     if (s > smax) s = smax;
@@ -325,20 +353,29 @@ ScorePlan score_split_plan(int64_t R, int dtype, const Dims& d, int num_cu) {
     return p;
 }
 
+template <int NT, typename T>
+static hipError_t launch_split_t(const T* G, int64_t R, const void* img, float* partial, const ScorePlan& p,
+                                 const Dims& d, hipStream_t st) {
+    constexpr int KC = 128 / (int)sizeof(T);
+    constexpr size_t LDS = (size_t)3 * 2 * NT * 32 * (KC / 8) * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)project_split_kernel<NT, T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)LDS);
+        attr_set = true;
+    }
+    const int64_t chunks = (d.D + KC - 1) / KC;
+    dim3 grid((unsigned)(p.row_tiles * p.splits));
+    hipLaunchKernelGGL((project_split_kernel<NT, T>), grid, dim3(512), LDS, st, G, R, (const u32x4*)img, partial,
+                       p.row_tiles, d.D, chunks, p.slabs_per_split);
+    return hipGetLastError();
+}
+
 template <int NT>
 static hipError_t launch_split_nt(const void* G, int dtype, int64_t R, const void* img, float* partial,
                                   const ScorePlan& p, const Dims& d, hipStream_t st) {
-    dim3 grid((unsigned)(p.row_tiles * p.splits));
-    if (dtype == SAGE_BF16) {
-        const int64_t chunks = (d.D + 63) / 64;
-        hipLaunchKernelGGL((project_split_kernel<NT, uint16_t>), grid, dim3(256), 0, st, (const uint16_t*)G, R,
-                           (const u32x4*)img, partial, p.row_tiles, d.D, chunks, p.slabs_per_split);
-    } else {
-        const int64_t chunks = (d.D + 31) / 32;
-        hipLaunchKernelGGL((project_split_kernel<NT, float>), grid, dim3(256), 0, st, (const float*)G, R,
-                           (const u32x4*)img, partial, p.row_tiles, d.D, chunks, p.slabs_per_split);
-    }
-    return hipGetLastError();
+    if (dtype == SAGE_BF16) return launch_split_t<NT, uint16_t>((const uint16_t*)G, R, img, partial, p, d, st);
+    return launch_split_t<NT, float>((const float*)G, R, img, partial, p, d, st);
 }
 
 hipError_t launch_project_split(const void* G, int dtype, int64_t R, const void* img, int KP, float* partial,
