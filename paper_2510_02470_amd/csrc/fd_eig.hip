@@ -322,6 +322,8 @@ __global__ __launch_bounds__(256) void jac_cross_kernel(const double* __restrict
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 constexpr int LDX = 68;  // leading dimension of an LDS matrix read as the row operand   (lane -> row l%16, k l/16)
 constexpr int LDQ = 72;  // leading dimension of an LDS matrix read as the column operand (lane -> k l/16, col l%16)
+constexpr int LDQB = 40; // the same for the 32-column half of Q_b (keeps the kernel's LDS under 96 KB, so that it fits
+                         // on a CU beside one work-group of the Gram kernel running on the side stream)
 
 // fp64 matrix-core step acc(16x16) += a(16x4) b(4x16): lane l supplies a[l%16][l/16] and b[l/16][l%16];
 // acc element v of lane l is row 4v + l/16, column l%16.
@@ -339,8 +341,8 @@ __global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict
     if (sweep_done(stat, sweep, tol)) return;
     extern __shared__ double sm[];
     double* X = sm;                // 64 x LDX
-    double* Qb = sm + 64 * LDX;    // 64 x LDQ (32 columns used), later T = X Q_b[:, h]
-    double* Qa = Qb + 64 * LDQ;    // 64 x LDQ
+    double* Qb = sm + 64 * LDX;    // 64 x LDQB (32 columns), later T = X Q_b[:, h]
+    double* Qa = Qb + 64 * LDQB;   // 64 x LDQ
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int np = NP / 64, nb = NP / 32;
     const int half = blockIdx.x & 1;
@@ -379,7 +381,7 @@ __global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             int e = u * 256 + tid;
-            Qb[(e >> 5) * LDQ + (e & 31)] = vb[u];
+            Qb[(e >> 5) * LDQB + (e & 31)] = vb[u];
         }
     }
     __syncthreads();
@@ -390,21 +392,21 @@ __global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict
     for (int k0 = 0; k0 < 64; k0 += 4) {  // T = X Q_b[:, h]
         double av = X[(i0 + l16) * LDX + k0 + lk];
 #pragma unroll
-        for (int jt = 0; jt < 2; ++jt) acc[jt] = mfma64(av, Qb[(k0 + lk) * LDQ + jt * 16 + l16], acc[jt]);
+        for (int jt = 0; jt < 2; ++jt) acc[jt] = mfma64(av, Qb[(k0 + lk) * LDQB + jt * 16 + l16], acc[jt]);
     }
     if (!isY) {
         __syncthreads();  // everyone is done reading Q_b
 #pragma unroll
         for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Qb[(i0 + 4 * v + lk) * LDQ + jt * 16 + l16] = acc[jt][v];
+            for (int v = 0; v < 4; ++v) Qb[(i0 + 4 * v + lk) * LDQB + jt * 16 + l16] = acc[jt][v];
         __syncthreads();
 #pragma unroll
         for (int jt = 0; jt < 2; ++jt) acc[jt] = f64x4{0.0, 0.0, 0.0, 0.0};
         for (int k0 = 0; k0 < 64; k0 += 4) {  // Q_a^T T
             double av = Qa[(k0 + lk) * LDQ + i0 + l16];
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt) acc[jt] = mfma64(av, Qb[(k0 + lk) * LDQ + jt * 16 + l16], acc[jt]);
+            for (int jt = 0; jt < 2; ++jt) acc[jt] = mfma64(av, Qb[(k0 + lk) * LDQB + jt * 16 + l16], acc[jt]);
         }
     }
     const int gcb = (half == 0 ? Ib : Jb) * 32;
@@ -453,10 +455,15 @@ __global__ __launch_bounds__(512) void eig_sort_kernel(const double* __restrict_
 __global__ __launch_bounds__(256) void shrink_coeffs_kernel(const double* __restrict__ Y, const int* __restrict__ pos,
                                                             const double* __restrict__ lam,
                                                             const double* __restrict__ diag0, int NP, int LP, int ell,
-                                                            int frob_r0, int frob_r1, float* __restrict__ Mt,
-                                                            double* __restrict__ acc) {
+                                                            int ra0, int ra1, int rb0, int rb1,
+                                                            float* __restrict__ Mt, double* __restrict__ acc,
+                                                            double* __restrict__ known) {
     int e = blockIdx.x * 256 + threadIdx.x;
     const double delta = lam[ell - 1];
+    if (e < NP) {  // squared norm of new row e: w_e^2 lambda_e
+        double keep = e < ell ? lam[e] - delta : 0.0;
+        known[e] = keep > 0.0 ? keep : 0.0;
+    }
     if (e < NP * LP) {
         int i = e / LP, m = e % LP;
         double lm = lam[m];
@@ -468,7 +475,8 @@ __global__ __launch_bounds__(256) void shrink_coeffs_kernel(const double* __rest
         acc[0] += delta;
         acc[2] = delta;
         double f = 0.0;
-        for (int r = frob_r0; r < frob_r1; ++r) f += diag0[r];
+        for (int r = ra0; r < ra1; ++r) f += diag0[r];
+        for (int r = rb0; r < rb1; ++r) f += diag0[r];
         acc[1] += f;
     }
 }
@@ -477,7 +485,7 @@ __global__ __launch_bounds__(256) void shrink_coeffs_kernel(const double* __rest
 __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restrict__ Y, const int* __restrict__ pos,
                                                            const double* __restrict__ lam,
                                                            const double* __restrict__ diag0, int NP, int KP, int k, int n,
-                                                           int frob_r0, int frob_r1, float* __restrict__ Mt,
+                                                           int ra0, int ra1, int rb0, int rb1, float* __restrict__ Mt,
                                                            double* __restrict__ acc) {
     int e = blockIdx.x * 256 + threadIdx.x;
     const double thr = (double)n * 1.1920928955078125e-07 * lam[0];
@@ -492,13 +500,14 @@ __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restr
     }
     if (e == 0) {
         double f = 0.0;
-        for (int r = frob_r0; r < frob_r1; ++r) f += diag0[r];
+        for (int r = ra0; r < ra1; ++r) f += diag0[r];
+        for (int r = rb0; r < rb1; ++r) f += diag0[r];
         acc[1] += f;
     }
 }
 
 static const size_t DIAG_LDS = (size_t)(2 * 64 * LDA + 64) * sizeof(double);
-static const size_t APPLY_LDS = (size_t)(64 * LDX + 2 * 64 * LDQ) * sizeof(double);
+static const size_t APPLY_LDS = (size_t)(64 * LDX + 64 * LDQB + 64 * LDQ) * sizeof(double);
 
 hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st) {
     static bool attr = false;
@@ -527,19 +536,19 @@ hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int frob_r0, int frob_r1, float* Mt,
+hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int ra0, int ra1, int rb0, int rb1, float* Mt,
                                 double* acc, double tol, hipStream_t st) {
     hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc, tol);
     hipLaunchKernelGGL(shrink_coeffs_kernel, dim3((NP * LP + 255) / 256), dim3(256), 0, st, w.Y, w.pos, w.lam, w.diag0,
-                       NP, LP, ell, frob_r0, frob_r1, Mt, acc);
+                       NP, LP, ell, ra0, ra1, rb0, rb1, Mt, acc, w.known);
     return hipGetLastError();
 }
 
-hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int frob_r0, int frob_r1, float* Mt,
-                               double* acc, double tol, hipStream_t st) {
+hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int ra0, int ra1, int rb0, int rb1,
+                               float* Mt, double* acc, double tol, hipStream_t st) {
     hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc, tol);
     hipLaunchKernelGGL(basis_coeffs_kernel, dim3((NP * KP + 255) / 256), dim3(256), 0, st, w.Y, w.pos, w.lam, w.diag0,
-                       NP, KP, k, n, frob_r0, frob_r1, Mt, acc);
+                       NP, KP, k, n, ra0, ra1, rb0, rb1, Mt, acc);
     return hipGetLastError();
 }
 

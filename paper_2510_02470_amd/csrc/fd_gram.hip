@@ -16,14 +16,35 @@ __device__ __forceinline__ void tile_coords(int t, int& ti, int& tj) {
     tj = t - i * (i + 1) / 2;
 }
 
-// P = NP / 64 row panels. 256 threads = 4 waves; the unit of work is half a tile (32 rows x 64 columns, two
+// P = NP / 64 row panels. Tiles t0 .. t0 + tiles - 1 of the row-major lower-triangle enumeration are computed (t0 > 0
+// leaves out the leading panels whose Gram block the caller already knows). 256 threads = 4 waves; the unit of work is half a tile (32 rows x 64 columns, two
 // 32x32 accumulators); a wave owns up to 3 units, a work-group 12 (6 tiles), and two work-groups share a CU so
 // that one's LDS reads and barrier waits hide under the other's matrix-core work.
 // Dynamic LDS: 2 stages x NP rows x 64 B, 16-byte pieces XOR-swizzled by (row/4)%4 so that the 16 rows read
 // by a quarter wave fall in distinct banks.
+// The buffer is two half buffers of LP = NP/2 rows each (same slab layout): `top` holds matrix rows 0 .. LP-1, `nw`
+// matrix rows LP .. NP-1, of which only the first nfill hold data (the rest are taken as zero, whatever they hold).
+// mode 0: tiles t0 .. t0+tiles-1 of the triangle; mode 1: the rectangle (new rows) x (top rows), tiles row-major;
+// mode 2: the triangle of (new rows) x (new rows).
+__device__ __forceinline__ void gram_tile(int mode, int P, int t0, int idx, int& ti, int& tj) {
+    const int q = P >> 1;
+    if (mode == 0) {
+        tile_coords(t0 + idx, ti, tj);
+    } else if (mode == 1) {
+        ti = q + idx / q;
+        tj = idx % q;
+    } else {
+        tile_coords(idx, ti, tj);
+        ti += q;
+        tj += q;
+    }
+}
+
 template <int P>
-__global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ B, float* __restrict__ partial, int tiles,
-                                                      int wg_per_group, int64_t slabs_total, int64_t slabs_per_group) {
+__global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ top, const float* __restrict__ nw,
+                                                      int nfill, float* __restrict__ partial, int mode, int t0,
+                                                      int tiles, int wg_per_group, int64_t slabs_total,
+                                                      int64_t slabs_per_group) {
     constexpr int NP = P * 64;
     constexpr int STAGE = NP * 4;  // 16-byte pieces per stage
     extern __shared__ f32x4 lds[];
@@ -50,7 +71,7 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ 
         int u = ubase + q;
         on[q] = u < 2 * tiles;
         int ti = 0, tj = 0;
-        if (on[q]) tile_coords(u >> 1, ti, tj);
+        if (on[q]) gram_tile(mode, P, t0, u >> 1, ti, tj);
         arow[q] = ti * 64 + (u & 1) * 32 + l32;
         brow[q] = tj * 64 + l32;
     }
@@ -63,22 +84,34 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ 
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[q][b][i] = 0.f;
 
-    // staging map: slot ps = it*256 + tid holds (row = ps/4, logical piece = (ps%4) ^ ((row/4)%4))
-    int src[P];
+    // staging map: slot ps = it*256 + tid holds (row = ps/4, logical piece = (ps%4) ^ ((row/4)%4)); the row comes from
+    // the top half, the new half, or is zero
+    constexpr int LP = NP / 2;
+    constexpr int HALF4 = LP * 4;  // 16-byte pieces of one half buffer per slab
+    int src[P];                    // piece index inside the half's slab, -1: zero row
+    bool isnew[P];
 #pragma unroll
     for (int it = 0; it < P; ++it) {
         int ps = it * 256 + tid;
         int row = ps >> 2;
         int p = (ps & 3) ^ ((row >> 2) & 3);
-        src[it] = row * 4 + p;
+        isnew[it] = row >= LP;
+        int hr = isnew[it] ? row - LP : row;
+        src[it] = ((isnew[it] && hr >= nfill) || (mode == 2 && !isnew[it])) ? -1 : hr * 4 + p;  // mode 2 never reads top rows
     }
-    const f32x4* Bv = reinterpret_cast<const f32x4*>(B);
+    const f32x4* Tv = reinterpret_cast<const f32x4*>(top);
+    const f32x4* Nv = reinterpret_cast<const f32x4*>(nw);
     f32x4 pre[P];
+    auto fetch = [&](int64_t sl) {
+#pragma unroll
+        for (int it = 0; it < P; ++it) {
+            const f32x4* base = (isnew[it] ? Nv : Tv) + sl * HALF4;
+            pre[it] = src[it] >= 0 ? base[src[it]] : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
 
     if (s0 < s1) {
-        const f32x4* slab = Bv + s0 * STAGE;
-#pragma unroll
-        for (int it = 0; it < P; ++it) pre[it] = slab[src[it]];
+        fetch(s0);
 #pragma unroll
         for (int it = 0; it < P; ++it) lds[it * 256 + tid] = pre[it];
     }
@@ -87,11 +120,7 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ 
     for (int64_t s = s0; s < s1; ++s) {
         const int cur = (int)((s - s0) & 1);
         const bool more = (s + 1 < s1);
-        if (more) {
-            const f32x4* slab = Bv + (s + 1) * STAGE;
-#pragma unroll
-            for (int it = 0; it < P; ++it) pre[it] = slab[src[it]];
-        }
+        if (more) fetch(s + 1);
         const f32x4* st = lds + cur * STAGE;
         // operands of the whole stage are fetched up front, first the pieces of k-half 0 for every unit, then those of
         // k-half 1, which land while the matrix cores work on half 0 (units that are switched off read rows that
@@ -129,7 +158,7 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ 
         __syncthreads();
     }
 
-    // partial[group][tile][64 x 64]; unit u covers rows (u & 1) * 32 .. + 32 of tile u / 2
+    // partial[group][tile - t0][64 x 64]; unit u covers rows (u & 1) * 32 .. + 32 of tile t0 + u / 2
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
         if (!on[q]) continue;
@@ -146,28 +175,63 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ 
     }
 }
 
-// C (NP x NP, fp64, both triangles) = sum over groups of the partial tiles, in group order.
-__global__ __launch_bounds__(256) void gram_reduce_kernel(const float* __restrict__ partial, double* __restrict__ C,
-                                                          int NP, int tiles, int groups) {
+// C (NP x NP, fp64, both triangles) = sum over groups of the partial tiles, in group order. With q = P/2:
+// known_top: tiles with ti < q are not summed, their block is diag(known) (the top rows are the orthogonal rows the
+// last shrink wrote, whose squared norms it recorded). Otherwise tile (ti, tj) comes from source A when its mode
+// covers it, else from source B (mode-1 and mode-2 launches write separate partial buffers).
+struct GramSrc {
+    const float* partial;
+    int mode, t0, tiles, groups;
+};
+__device__ __forceinline__ int gram_src_index(const GramSrc& g, int P, int t, int ti, int tj) {
+    const int q = P >> 1;
+    if (g.mode == 0) return (t >= g.t0 && t < g.t0 + g.tiles) ? t - g.t0 : -1;
+    if (g.mode == 1) return (ti >= q && tj < q) ? (ti - q) * q + tj : -1;
+    return (ti >= q && tj >= q) ? (ti - q) * (ti - q + 1) / 2 + (tj - q) : -1;
+}
+__global__ __launch_bounds__(256) void gram_reduce_kernel(GramSrc a, GramSrc b, double* __restrict__ C, int NP,
+                                                          int known_top, const double* __restrict__ known) {
+    const int P = NP / 64;
     int t = blockIdx.x;
     int e = blockIdx.y * 256 + threadIdx.x;  // 0..4095
     int ti, tj;
     tile_coords(t, ti, tj);
     int r = e >> 6, c = e & 63;
     if (ti == tj && c > r) return;  // the diagonal tiles hold both triangles; keep one
-    double s = 0.0;
-    for (int g = 0; g < groups; ++g) s += (double)partial[((int64_t)g * tiles + t) * 4096 + e];
     int gr = ti * 64 + r, gc = tj * 64 + c;
+    double s = 0.0;
+    if (known_top && ti < (P >> 1)) {
+        if (gr == gc) s = known[gr];
+    } else {
+        int ia = gram_src_index(a, P, t, ti, tj);
+        const GramSrc& g = ia >= 0 ? a : b;
+        int idx = ia >= 0 ? ia : gram_src_index(b, P, t, ti, tj);
+        if (idx >= 0)
+            for (int k = 0; k < g.groups; ++k) s += (double)g.partial[((int64_t)k * g.tiles + idx) * 4096 + e];
+    }
     C[(int64_t)gr * NP + gc] = s;
     C[(int64_t)gc * NP + gr] = s;
 }
 
-GramPlan gram_plan(const Dims& d, int num_cu) {
+// wg_per_cu = 2 fills the chip. wg_per_cu = 1 is for the launch that shares the chip with the eigensolve (side
+// stream): it also leaves 16 CUs (two per XCD) without any of its work-groups, because the eigensolve's pivot
+// kernel needs more registers than remain on a CU that holds one of them.
+GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_per_cu) {
     GramPlan p;
-    int P = d.NP / 64;
-    p.tiles = P * (P + 1) / 2;
+    const int P = d.NP / 64, q = P / 2;
+    p.mode = mode;
+    p.t0 = 0;
+    if (mode == 0) {
+        p.t0 = skip_top ? q * (q + 1) / 2 : 0;
+        p.tiles = P * (P + 1) / 2 - p.t0;
+    } else if (mode == 1) {
+        p.tiles = (P - q) * q;
+    } else {
+        p.tiles = (P - q) * (P - q + 1) / 2;
+    }
     p.wg_per_group = (p.tiles + 5) / 6;
-    int g = (2 * num_cu / p.wg_per_group) / 8 * 8;  // two work-groups per CU
+    const int cus = wg_per_cu == 1 && num_cu > 32 ? num_cu - 16 : num_cu;
+    int g = (wg_per_cu * cus / p.wg_per_group) / 8 * 8;
     if (g < 8) g = 8;
     // keep at least 4 slabs per group so that tiny problems do not drown in partial tiles
     int64_t gmax = ((d.S + 3) / 4 + 7) / 8 * 8;
@@ -179,7 +243,9 @@ GramPlan gram_plan(const Dims& d, int num_cu) {
     return p;
 }
 
-hipError_t launch_gram(const float* B, float* partial, const GramPlan& p, const Dims& d, hipStream_t st) {
+hipError_t launch_gram(const float* top, const float* nw, int nfill, float* partial, const GramPlan& p, const Dims& d,
+                       hipStream_t st) {
+    if (p.tiles <= 0) return hipSuccess;
     dim3 grid((unsigned)(p.groups * p.wg_per_group));
     size_t lds = (size_t)2 * d.NP * 64;
     switch (d.NP / 64) {
@@ -190,8 +256,8 @@ hipError_t launch_gram(const float* B, float* partial, const GramPlan& p, const 
             (void)hipFuncSetAttribute((const void*)gram_kernel<PP>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);   \
             attr_set = true;                                                                                        \
         }                                                                                                           \
-        hipLaunchKernelGGL(gram_kernel<PP>, grid, dim3(256), lds, st, B, partial, p.tiles, p.wg_per_group, d.S,     \
-                           p.slabs_per_group);                                                                      \
+        hipLaunchKernelGGL(gram_kernel<PP>, grid, dim3(256), lds, st, top, nw, nfill, partial, p.mode, p.t0, p.tiles,    \
+                           p.wg_per_group, d.S, p.slabs_per_group);                                                 \
     } break;
         SAGE_GRAM_CASE(1)
         SAGE_GRAM_CASE(2)
@@ -204,8 +270,14 @@ hipError_t launch_gram(const float* B, float* partial, const GramPlan& p, const 
     return hipGetLastError();
 }
 
-hipError_t launch_gram_reduce(const float* partial, double* C, const GramPlan& p, const Dims& d, hipStream_t st) {
-    hipLaunchKernelGGL(gram_reduce_kernel, dim3(p.tiles, 16), dim3(256), 0, st, partial, C, d.NP, p.tiles, p.groups);
+// a, b: the launches whose partial tiles make up C (b may be null); known: NP doubles, read when known_top
+hipError_t launch_gram_reduce(const float* partial_a, const GramPlan& a, const float* partial_b, const GramPlan* b,
+                              double* C, bool known_top, const double* known, const Dims& d, hipStream_t st) {
+    const int P = d.NP / 64;
+    GramSrc sa{partial_a, a.mode, a.t0, a.tiles, a.groups};
+    GramSrc sb{partial_b, b ? b->mode : 0, b ? b->t0 : 0, b ? b->tiles : 0, b ? b->groups : 0};
+    hipLaunchKernelGGL(gram_reduce_kernel, dim3(P * (P + 1) / 2, 16), dim3(256), 0, st, sa, sb, C, d.NP, known_top ? 1 : 0,
+                       known);
     return hipGetLastError();
 }
 

@@ -28,13 +28,15 @@ __global__ __launch_bounds__(256) void insert_kernel(const T* __restrict__ G, in
     *dst = make_float4(v[0], v[1], v[2], v[3]);
 }
 
-hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* B, const Dims& d, hipStream_t st) {
+hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* half, int half_rows, const Dims& d,
+                         hipStream_t st) {
     if (rows <= 0) return hipSuccess;
     dim3 grid((unsigned)((d.S * 4 + 255) / 256), (unsigned)rows);
     if (dtype == SAGE_BF16)
-        hipLaunchKernelGGL(insert_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)G, row0, B, d.NP, d.D, d.S);
+        hipLaunchKernelGGL(insert_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)G, row0, half, half_rows, d.D,
+                           d.S);
     else
-        hipLaunchKernelGGL(insert_kernel<float>, grid, dim3(256), 0, st, (const float*)G, row0, B, d.NP, d.D, d.S);
+        hipLaunchKernelGGL(insert_kernel<float>, grid, dim3(256), 0, st, (const float*)G, row0, half, half_rows, d.D, d.S);
     return hipGetLastError();
 }
 
@@ -67,6 +69,29 @@ __global__ __launch_bounds__(256) void import_kernel(const float* __restrict__ i
 hipError_t launch_import_rows(const float* in, int nrows, float* Bblk, int NPdst, const Dims& d, hipStream_t st) {
     dim3 grid((unsigned)((d.Dp + 255) / 256), (unsigned)NPdst);
     hipLaunchKernelGGL(import_kernel, grid, dim3(256), 0, st, in, nrows, Bblk, NPdst, d.D, d.Dp);
+    return hipGetLastError();
+}
+
+// out[r][c] = in[map(r)][both ? map(c) : c] with map = buffer-row order -> matrix index: r < ell -> r,
+// ell <= r < 2 ell -> LP + r - ell, then the padding indices in ascending order.
+__device__ __forceinline__ int probe_map(int r, int LP, int ell) {
+    if (r < ell) return r;
+    if (r < 2 * ell) return LP + r - ell;
+    int k = r - 2 * ell;                    // k-th padding index
+    return k < LP - ell ? ell + k : LP + ell + (k - (LP - ell));
+}
+__global__ __launch_bounds__(256) void probe_permute_kernel(const double* __restrict__ in, double* __restrict__ out, int NP,
+                                                            int LP, int ell, int both) {
+    int r = blockIdx.x;
+    int mr = probe_map(r, LP, ell);
+    for (int c = threadIdx.x; c < NP; c += 256) {
+        int mc = both ? probe_map(c, LP, ell) : c;
+        out[(int64_t)r * NP + c] = in[(int64_t)mr * NP + mc];
+    }
+}
+
+hipError_t launch_probe_permute(const double* in, double* out, int NP, int LP, int ell, bool both, hipStream_t st) {
+    hipLaunchKernelGGL(probe_permute_kernel, dim3(NP), dim3(256), 0, st, in, out, NP, LP, ell, both ? 1 : 0);
     return hipGetLastError();
 }
 

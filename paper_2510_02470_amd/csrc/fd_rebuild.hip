@@ -4,9 +4,11 @@
 // Phase I, "S <- Sigma' V^T"), in place on the sketch, and the scoring basis V_k^T = diag(1/sigma) Y_k^T B
 // (Algorithm 1, "Freeze S for scoring"), written to its own buffer.
 //
+// The buffer is two half buffers of LP = NP/2 rows (same slab layout): `top` = matrix rows 0 .. LP-1, `nw` = matrix rows
+// LP .. NP-1 of which the first nfill hold data (the others count as zero, whatever they hold).
 // A wave owns 32 columns for the whole product: it reads all NP buffer rows of those columns (its B operand comes
 // straight from global memory, one 128 B line per row pair), keeps the MP x 32 result in accumulators, and only
-// then writes. Nobody else touches those columns, so the update is safely in place. The coefficient matrix
+// then writes. Nobody else touches those columns, so the update is safely in place (out == top). The coefficient matrix
 // streams through LDS in chunks of 16 buffer rows shared by the 4 waves of the work-group; it is stored in the
 // order the matrix cores consume it (see coeff_offset), so a lane fetches the 8 coefficients of a chunk with two
 // 16-byte LDS reads.
@@ -15,9 +17,9 @@
 namespace sage {
 
 template <int MT>  // MT = MP / 32 accumulator tiles per wave
-__global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict__ B, const float* __restrict__ Mc,
-                                                         float* __restrict__ out, int NP, int out_NP, int zero_tail,
-                                                         int64_t Dp) {
+__global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict__ top, const float* __restrict__ nw,
+                                                         int nfill, const float* __restrict__ Mc,
+                                                         float* __restrict__ out, int NP, int out_NP, int64_t Dp) {
     constexpr int MP = MT * 32;
     constexpr int CHUNK4 = 16 * MP / 4;  // 16-byte pieces per stage (16 buffer rows x MP coefficients)
     constexpr int PER = CHUNK4 / 256;    // pieces per thread per stage (MT / 2 ... at least 1)
@@ -30,7 +32,23 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
     const int64_t d = ((int64_t)blockIdx.x * 4 + wave) * 32 + c;  // this lane's column
     const bool live = d < Dp;  // Dp is a multiple of 16: the last 32-column group may overhang by 16
     const int64_t dc = live ? d : Dp - 1;
-    const float* bcol = B + ((dc / DC) * NP) * (int64_t)DC + (dc % DC) + (int64_t)h * DC;  // row h of this column
+    const int LP = NP >> 1;
+    const int64_t coff = ((dc / DC) * LP) * (int64_t)DC + (dc % DC) + (int64_t)h * DC;  // row h of this column, either half
+    const float* tcol = top + coff;
+    const float* ncol = nw + coff;
+    // rows 16*stg + 2*s + h of the matrix: stage stg lies in the top half when stg < LP/16. Rows of the new half are
+    // always loaded (they exist) and zeroed afterwards when they are not in use.
+    auto fetch_b = [&](int stg, float (&b)[8]) {
+        const int r0 = stg * 16;
+        const bool isnew = r0 >= LP;
+        const float* bn = isnew ? ncol + (int64_t)(r0 - LP) * DC : tcol + (int64_t)r0 * DC;
+        const int limit = isnew ? nfill - (r0 - LP) - h : 0x7fffffff;  // 2*s < limit: row in use
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            float v = bn[(int64_t)(2 * s) * DC];
+            b[s] = 2 * s < limit ? v : 0.f;
+        }
+    };
 
     f32x16 acc[MT];
 #pragma unroll
@@ -42,8 +60,7 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
     float bpre[8];
     f32x4 mpre[PERC];
     // prologue: stage 0
-#pragma unroll
-    for (int s = 0; s < 8; ++s) bpre[s] = bcol[(int64_t)(2 * s) * DC];
+    fetch_b(0, bpre);
 #pragma unroll
     for (int u = 0; u < PERC; ++u)
         if (u * 256 + tid < CHUNK4) Ms[0][u * 256 + tid] = Mv[u * 256 + tid];
@@ -59,9 +76,7 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
         for (int s = 0; s < 8; ++s) bcur[s] = bpre[s];
         const bool more = stg + 1 < nstage;
         if (more) {
-            const float* bn = bcol + (int64_t)(stg + 1) * 16 * DC;
-#pragma unroll
-            for (int s = 0; s < 8; ++s) bpre[s] = bn[(int64_t)(2 * s) * DC];
+            fetch_b(stg + 1, bpre);
 #pragma unroll
             for (int u = 0; u < PERC; ++u)
                 if (u * 256 + tid < CHUNK4) mpre[u] = Mv[(int64_t)(stg + 1) * CHUNK4 + u * 256 + tid];
@@ -98,22 +113,21 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
             int r = m * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
             out[out_base + (int64_t)r * DC] = acc[m][i];
         }
-    if (zero_tail) {
-        for (int r = MP + h; r < out_NP; r += 2) out[out_base + (int64_t)r * DC] = 0.f;
-    }
 }
 
-hipError_t launch_rebuild(const float* B, const float* Mc, float* out, int out_NP, int MP, bool zero_tail,
+hipError_t launch_rebuild(const float* top, const float* nw, int nfill, const float* Mc, float* out, int out_NP, int MP,
                           const Dims& d, hipStream_t st) {
     dim3 grid((unsigned)((d.Dp + 127) / 128));
-    int zt = zero_tail ? 1 : 0;
+#define SAGE_RB(MT)                                                                                                  \
+    hipLaunchKernelGGL(rebuild_kernel<MT>, grid, dim3(256), 0, st, top, nw, nfill, Mc, out, d.NP, out_NP, d.Dp)
     switch (MP / 32) {
-        case 1: hipLaunchKernelGGL(rebuild_kernel<1>, grid, dim3(256), 0, st, B, Mc, out, d.NP, out_NP, zt, d.Dp); break;
-        case 2: hipLaunchKernelGGL(rebuild_kernel<2>, grid, dim3(256), 0, st, B, Mc, out, d.NP, out_NP, zt, d.Dp); break;
-        case 4: hipLaunchKernelGGL(rebuild_kernel<4>, grid, dim3(256), 0, st, B, Mc, out, d.NP, out_NP, zt, d.Dp); break;
-        case 8: hipLaunchKernelGGL(rebuild_kernel<8>, grid, dim3(256), 0, st, B, Mc, out, d.NP, out_NP, zt, d.Dp); break;
+        case 1: SAGE_RB(1); break;
+        case 2: SAGE_RB(2); break;
+        case 4: SAGE_RB(4); break;
+        case 8: SAGE_RB(8); break;
         default: return hipErrorInvalidValue;
     }
+#undef SAGE_RB
     return hipGetLastError();
 }
 

@@ -22,15 +22,31 @@ struct sage_ctx {
     hipStream_t st = nullptr;
     int num_cu = 256;
 
-    float* B = nullptr;
-    GramPlan gp{};
+    // The 2*ell-row buffer is kept as two half buffers of LP rows each (column-slab layout): `top` holds buffer rows
+    // 0 .. ell-1 (after a shrink: the rows it wrote), nw[cur] holds buffer rows ell .. 2*ell-1 as they arrive. Two new
+    // halves alternate so that the rows of the next cycle can be stored, and their own Gram block formed, on a side
+    // stream while the eigensolve of the current cycle runs.
+    float* top = nullptr;
+    float* nw[2] = {nullptr, nullptr};
+    int cur = 0;
+    hipStream_t st2 = nullptr;                   // side stream (only when the Gram has >= 2 row panels)
+    hipEvent_t ev_mark = nullptr;                // context stream: the Gram matrix of the current cycle is complete
+    hipEvent_t ev_side[2] = {nullptr, nullptr};  // side stream: rows stored in nw[i] and their Gram block formed
+    bool pre_stored = false;       // the side stream has stored the next ell rows of the running call in nw[cur]
+    bool new_block_ready = false;  // ... and their Gram block is (or will be, see ev_side) in gram_partial_new[cur]
+    GramPlan gp{};        // whole lower triangle
+    GramPlan gp_skip{};   // without the top x top block (known after a shrink)
+    GramPlan gp_cross{};  // new rows x top rows
+    GramPlan gp_new{};    // new rows x new rows, one work-group per CU (it shares the chip with the eigensolve)
+    bool top_shrunk = false;  // top holds exactly what the last shrink wrote
     float* gram_partial = nullptr;
+    float* gram_partial_new[2] = {nullptr, nullptr};
     EigWork ew{};
     float* Mt = nullptr;
     double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps
 
-    int fill = 0;
-    int counted_base = 0;  // buffer rows [counted_base, fill) are not yet in frob2
+    int fill_top = 0, fill_new = 0;  // rows in use in top (0..ell) and in nw[cur] (0..ell)
+    int cnt_top = 0, cnt_new = 0;    // of those, rows already counted in frob2
     int64_t rows_seen = 0, n_shrinks = 0;
 
     bool has_basis = false;
@@ -102,22 +118,61 @@ int pad_pow2_32(int v) {
     return p;
 }
 
-int decompose(sage_ctx* c, double tol) {
-    RUN(K_GRAM, launch_gram(c->B, c->gram_partial, c->gp, c->d, c->st));
-    RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->ew.C, c->gp, c->d, c->st));
+bool use_side(const sage_ctx* c) { return c->st2 != nullptr; }
+
+// Gram + eigensolve of the buffer as it stands. After a shrink the top rows are orthogonal with known squared norms
+// (lambda_j - delta), so their block is not recomputed.
+int decompose(sage_ctx* c, double tol, bool full) {
+    const bool skip = !full && c->top_shrunk && c->gp_skip.t0 > 0;
+    const GramPlan& gp = skip ? c->gp_skip : c->gp;
+    RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, gp, c->d, c->st));
+    RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
     RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, c->st));
     return SAGE_OK;
 }
 
-int shrink(sage_ctx* c) {
-    int rc = decompose(c, JACOBI_TOL_SHRINK);
-    if (rc != SAGE_OK) return rc;
-    RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, c->d.LP, c->d.ell, c->counted_base, c->d.n, c->Mt, c->acc,
-                                      JACOBI_TOL_SHRINK, c->st));
-    RUN(K_REBUILD, launch_rebuild(c->B, c->Mt, c->B, c->d.NP, c->d.LP, true, c->d, c->st));
-    c->fill = c->d.ell;
-    c->counted_base = c->d.ell;
+// The buffer is full: shrink it (Method, FD paragraph). Leaves top = the ell new rows and the other new half current.
+// next / next_rows: what is left of the running update call after this buffer. If a whole further cycle of rows is
+// there, they are stored in the other new half and their own Gram block is formed on the side stream while the
+// eigensolve runs on the context stream (neither needs its result, and the eigensolve leaves most of the chip idle).
+int shrink(sage_ctx* c, const void* next, int64_t next_rows) {
+    const int LP = c->d.LP, ell = c->d.ell;
+    if (c->new_block_ready) {
+        // the new x new block came from the side stream; only new x top is left
+        HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, c->gp_cross, c->d, c->st));
+        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->gp_cross, c->gram_partial_new[c->cur], &c->gp_new, c->ew.C,
+                                         true, c->ew.known, c->d, c->st));
+    } else {
+        const bool skip = c->top_shrunk && c->gp_skip.t0 > 0;
+        const GramPlan& gp = skip ? c->gp_skip : c->gp;
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, gp, c->d, c->st));
+        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
+    }
+    c->new_block_ready = false;
+    const bool ahead = use_side(c) && !c->prof && next_rows >= ell;
+    if (ahead) {
+        // The other half was last read by the rebuild before last, which precedes the mark on the context stream.
+        const int o = c->cur ^ 1;
+        HIPCHK(hipEventRecord(c->ev_mark, c->st));
+        HIPCHK(hipStreamWaitEvent(c->st2, c->ev_mark, 0));
+        HIPCHK(launch_insert(next, c->dtype, ell, 0, c->nw[o], LP, c->d, c->st2));
+        HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], c->gp_new, c->d, c->st2));
+        HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
+    }
+    RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->st));
+    RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, LP, ell, c->cnt_top, c->fill_top, LP + c->cnt_new, LP + c->fill_new,
+                                      c->Mt, c->acc, JACOBI_TOL_SHRINK, c->st));
+    RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], ell, c->Mt, c->top, LP, LP, c->d, c->st));
+    if (use_side(c)) c->cur ^= 1;  // two new halves alternate; with a single Gram panel there is only nw[0]
+    c->fill_top = ell;
+    c->cnt_top = ell;
+    c->fill_new = 0;
+    c->cnt_new = 0;
+    c->pre_stored = ahead;
+    c->new_block_ready = ahead;
     c->n_shrinks += 1;
+    c->top_shrunk = true;
     return SAGE_OK;
 }
 
@@ -235,7 +290,13 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
         return SAGE_ERR_HIP;
     }
     c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    c->gp = gram_plan(c->d, c->num_cu);
+    const int P = c->d.NP / 64;
+    c->gp = gram_plan(c->d, c->num_cu, 0, false, 2);
+    c->gp_skip = gram_plan(c->d, c->num_cu, 0, P >= 2, 2);
+    if (P >= 2) {
+        c->gp_cross = gram_plan(c->d, c->num_cu, 1, false, 2);
+        c->gp_new = gram_plan(c->d, c->num_cu, 2, false, 1);
+    }
     c->fixed_cap = max_rows > 0;
     c->cap_rows = max_rows > 0 ? max_rows : 65536;
 
@@ -244,7 +305,7 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
         return rc;
     };
     const int NP = c->d.NP;
-    size_t bbytes = (size_t)c->d.S * NP * DC * sizeof(float);
+    size_t hbytes = (size_t)c->d.S * c->d.LP * DC * sizeof(float);  // one half buffer
 #define CALLOC(ptr, bytes)                                                        \
     do {                                                                          \
         if (hipMalloc((void**)&(ptr), (bytes)) != hipSuccess) {                   \
@@ -252,8 +313,23 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
             return fail(SAGE_ERR_ALLOC);                                          \
         }                                                                         \
     } while (0)
-    CALLOC(c->B, bbytes);
-    CALLOC(c->gram_partial, c->gp.partial_floats * sizeof(float));
+    CALLOC(c->top, hbytes);
+    CALLOC(c->nw[0], hbytes);
+    {
+        size_t pf = c->gp.partial_floats;
+        if (c->gp_skip.partial_floats > pf) pf = c->gp_skip.partial_floats;
+        if (c->gp_cross.partial_floats > pf) pf = c->gp_cross.partial_floats;
+        CALLOC(c->gram_partial, pf * sizeof(float));
+    }
+    if (P >= 2) {
+        CALLOC(c->nw[1], hbytes);
+        CALLOC(c->gram_partial_new[0], c->gp_new.partial_floats * sizeof(float));
+        CALLOC(c->gram_partial_new[1], c->gp_new.partial_floats * sizeof(float));
+        if (hipStreamCreateWithFlags(&c->st2, hipStreamNonBlocking) != hipSuccess) return fail(SAGE_ERR_HIP);
+        if (hipEventCreateWithFlags(&c->ev_mark, hipEventDisableTiming) != hipSuccess) return fail(SAGE_ERR_HIP);
+        for (int i = 0; i < 2; ++i)
+            if (hipEventCreateWithFlags(&c->ev_side[i], hipEventDisableTiming) != hipSuccess) return fail(SAGE_ERR_HIP);
+    }
     CALLOC(c->ew.C, (size_t)NP * NP * sizeof(double));
     CALLOC(c->ew.Y, (size_t)NP * NP * sizeof(double));
     CALLOC(c->ew.C2, (size_t)NP * NP * sizeof(double));
@@ -263,10 +339,12 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     CALLOC(c->ew.stat, 32 * sizeof(double));
     CALLOC(c->ew.pos, (size_t)NP * sizeof(int));
     CALLOC(c->ew.lam, (size_t)NP * sizeof(double));
+    CALLOC(c->ew.known, (size_t)NP * sizeof(double));
     CALLOC(c->Mt, (size_t)NP * c->d.LP * sizeof(float));
     CALLOC(c->acc, 8 * sizeof(double));
 #undef CALLOC
-    if (hipMemsetAsync(c->B, 0, bbytes, c->st) != hipSuccess) return fail(SAGE_ERR_HIP);
+    // only the top half must start as zeros: rows of a new half beyond its fill are never read
+    if (hipMemsetAsync(c->top, 0, hbytes, c->st) != hipSuccess) return fail(SAGE_ERR_HIP);
     if (hipMemsetAsync(c->acc, 0, 8 * sizeof(double), c->st) != hipSuccess) return fail(SAGE_ERR_HIP);
     if (hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) return fail(SAGE_ERR_HIP);
     *out = c;
@@ -278,11 +356,17 @@ int sage_fd_create(sage_ctx** out, int ell, int64_t D) { return sage_fd_create_e
 void sage_destroy(sage_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->st);
-    void* ptrs[] = {c->B,       c->gram_partial, c->ew.C, c->ew.Y, c->ew.C2, c->ew.Y2, c->ew.Q,         c->ew.diag0, c->ew.stat,
-                    c->ew.pos,  c->ew.lam,       c->Mt,   c->acc,          c->Vblk,         c->Vimg,      c->zhat,     c->proj_partial,
-                    c->cons_partial, c->ssum,    c->alpha};
+    if (c->st2) (void)hipStreamSynchronize(c->st2);
+    void* ptrs[] = {c->top,     c->nw[0],    c->nw[1],  c->gram_partial, c->gram_partial_new[0], c->gram_partial_new[1],
+                    c->ew.C,    c->ew.Y,     c->ew.C2,  c->ew.Y2,        c->ew.Q,    c->ew.diag0, c->ew.stat,
+                    c->ew.pos,  c->ew.lam,   c->ew.known, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
+                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    if (c->st2) (void)hipStreamDestroy(c->st2);
+    hipEvent_t evs[] = {c->ev_mark, c->ev_side[0], c->ev_side[1]};
+    for (hipEvent_t e : evs)
+        if (e) (void)hipEventDestroy(e);
     free_select_work(c->sw);
     if (c->ev0) (void)hipEventDestroy(c->ev0);
     if (c->ev1) (void)hipEventDestroy(c->ev1);
@@ -301,18 +385,34 @@ int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
     c->has_basis = false;
     const char* g = (const char*)G_batch;
     const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
+    const int ell = c->d.ell, LP = c->d.LP;
     while (rows > 0) {
-        int take = (int)((int64_t)(c->d.n - c->fill) < rows ? (c->d.n - c->fill) : rows);
-        RUN(K_INSERT, launch_insert(g, c->dtype, take, c->fill, c->B, c->d, c->st));
-        c->fill += take;
+        int take;
+        if (c->fill_top < ell) {
+            // first fill of the buffer: rows go into the top half
+            take = (int)((int64_t)(ell - c->fill_top) < rows ? (ell - c->fill_top) : rows);
+            RUN(K_INSERT, launch_insert(g, c->dtype, take, c->fill_top, c->top, LP, c->d, c->st));
+            c->fill_top += take;
+        } else if (c->pre_stored) {
+            // the previous shrink of this call has had these ell rows stored already (side stream)
+            take = ell;
+            c->pre_stored = false;
+            c->fill_new = ell;
+        } else {
+            take = (int)((int64_t)(ell - c->fill_new) < rows ? (ell - c->fill_new) : rows);
+            RUN(K_INSERT, launch_insert(g, c->dtype, take, c->fill_new, c->nw[c->cur], LP, c->d, c->st));
+            c->fill_new += take;
+        }
         c->rows_seen += take;
         g += (size_t)take * c->d.D * esz;
         rows -= take;
-        if (c->fill == c->d.n) {
-            int rc = shrink(c);
+        if (c->fill_new == ell) {
+            int rc = shrink(c, g, rows);
             if (rc != SAGE_OK) return rc;
         }
     }
+    // Side-stream work is always picked up by a shrink of the same call (it waits for ev_side), so when this call's
+    // work is complete on the context stream nothing reads the batch any more.
     return SAGE_OK;
 }
 
@@ -322,12 +422,13 @@ int sage_fd_basis(sage_ctx* c, int k) {
     const int KP = pad_pow2_32(k);
     int rc = ensure_vblk(c, KP);
     if (rc != SAGE_OK) return rc;
-    rc = decompose(c, JACOBI_TOL_BASIS);
+    rc = decompose(c, JACOBI_TOL_BASIS, false);
     if (rc != SAGE_OK) return rc;
-    RUN(K_COEFF, launch_basis_coeffs(c->ew, c->d.NP, KP, k, c->d.n, c->counted_base, c->fill, c->Mt, c->acc,
-                                     JACOBI_TOL_BASIS, c->st));
-    c->counted_base = c->fill;
-    RUN(K_REBUILD, launch_rebuild(c->B, c->Mt, c->Vblk, KP, KP, false, c->d, c->st));
+    RUN(K_COEFF, launch_basis_coeffs(c->ew, c->d.NP, KP, k, c->d.n, c->cnt_top, c->fill_top, c->d.LP + c->cnt_new,
+                                     c->d.LP + c->fill_new, c->Mt, c->acc, JACOBI_TOL_BASIS, c->st));
+    c->cnt_top = c->fill_top;
+    c->cnt_new = c->fill_new;
+    RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Vblk, KP, KP, c->d, c->st));
     c->k = k;
     c->KP = KP;
     rc = finish_basis(c);
@@ -457,7 +558,12 @@ int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* 
 
 int sage_fd_sketch_export(sage_ctx* c, float* B_out) {
     if (!c || !B_out) return SAGE_ERR_ARG;
-    HIPCHK(launch_export_rows(c->B, c->d.NP, c->d.n, B_out, c->d, c->st));
+    const int ell = c->d.ell;
+    HIPCHK(launch_export_rows(c->top, c->d.LP, ell, B_out, c->d, c->st));
+    HIPCHK(launch_export_rows(c->nw[c->cur], c->d.LP, c->fill_new, B_out + (size_t)ell * c->d.D, c->d, c->st));
+    if (c->fill_new < ell)
+        HIPCHK(hipMemsetAsync(B_out + (size_t)(ell + c->fill_new) * c->d.D, 0,
+                              (size_t)(ell - c->fill_new) * c->d.D * sizeof(float), c->st));
     HIPCHK(hipStreamSynchronize(c->st));
     return SAGE_OK;
 }
@@ -503,28 +609,24 @@ int sage_stats(sage_ctx* c, sage_stats_t* out) {
     HIPCHK(hipMemcpyAsync(acc, c->acc, sizeof(acc), hipMemcpyDeviceToHost, c->st));
     HIPCHK(hipStreamSynchronize(c->st));
     double pending = 0.0;
-    if (c->counted_base < c->fill) {
+    if (c->cnt_top < c->fill_top || c->cnt_new < c->fill_new) {
         // rows inserted since the last decomposition: add their squared norms from a Gram of the buffer
-        int rc = SAGE_OK;
-        {
-            sage_ctx* cc = c;
-            (void)cc;
-            hipError_t e = launch_gram(c->B, c->gram_partial, c->gp, c->d, c->st);
-            if (e == hipSuccess) e = launch_gram_reduce(c->gram_partial, c->ew.C, c->gp, c->d, c->st);
-            if (e != hipSuccess) rc = SAGE_ERR_HIP;
-        }
-        if (rc != SAGE_OK) return rc;
-        const int NP = c->d.NP;
+        hipError_t e = launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp, c->d, c->st);
+        if (e == hipSuccess)
+            e = launch_gram_reduce(c->gram_partial, c->gp, nullptr, nullptr, c->ew.C, false, c->ew.known, c->d, c->st);
+        if (e != hipSuccess) return SAGE_ERR_HIP;
+        const int NP = c->d.NP, LP = c->d.LP;
         double* diag = (double*)malloc(sizeof(double) * NP);
         if (!diag) return SAGE_ERR_ALLOC;
-        hipError_t e = hipMemcpy2DAsync(diag, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double),
-                                        NP, hipMemcpyDeviceToHost, c->st);
+        e = hipMemcpy2DAsync(diag, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double), NP,
+                             hipMemcpyDeviceToHost, c->st);
         if (e == hipSuccess) e = hipStreamSynchronize(c->st);
         if (e != hipSuccess) {
             free(diag);
             return SAGE_ERR_HIP;
         }
-        for (int r = c->counted_base; r < c->fill; ++r) pending += diag[r];
+        for (int r = c->cnt_top; r < c->fill_top; ++r) pending += diag[r];
+        for (int r = c->cnt_new; r < c->fill_new; ++r) pending += diag[LP + r];
         free(diag);
     }
     out->rows_seen = c->rows_seen;
@@ -534,22 +636,23 @@ int sage_stats(sage_ctx* c, sage_stats_t* out) {
     out->frob2 = acc[1] + pending;
     out->last_delta = acc[2];
     out->last_sweeps = (int)acc[3];
-    out->fill = c->fill;
+    out->fill = c->fill_top + c->fill_new;
     return SAGE_OK;
 }
 
 int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, double* lam_out, int* n_pad) {
     if (!c) return SAGE_ERR_ARG;
-    const int NP = c->d.NP;
+    const int NP = c->d.NP, LP = c->d.LP, ell = c->d.ell;
     if (n_pad) *n_pad = NP;
-    HIPCHK(launch_gram(c->B, c->gram_partial, c->gp, c->d, c->st));
-    HIPCHK(launch_gram_reduce(c->gram_partial, c->ew.C, c->gp, c->d, c->st));
-    if (C_out)
-        HIPCHK(hipMemcpyAsync(C_out, c->ew.C, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    if (!C_out && !eig) return SAGE_OK;
+    HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp, c->d, c->st));
+    HIPCHK(launch_gram_reduce(c->gram_partial, c->gp, nullptr, nullptr, c->ew.C, false, c->ew.known, c->d, c->st));
+    // Inside the library matrix index LP + j stands for buffer row ell + j; the probe reports buffer-row order
+    // (rows 0 .. 2*ell-1, padding last).
+    if (C_out) HIPCHK(launch_probe_permute(c->ew.C, C_out, NP, LP, ell, true, c->st));
     if (eig) {
         HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, c->st));
-        if (Y_out)
-            HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+        if (Y_out) HIPCHK(launch_probe_permute(c->ew.Y, Y_out, NP, LP, ell, false, c->st));
         if (lam_out)
             HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double),
                                     NP, hipMemcpyDeviceToDevice, c->st));

@@ -42,22 +42,31 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_floa
 
 // ---- kernel launchers (each enqueues on `st` and returns hipGetLastError()) ---------------------------------
 // fd_insert.hip
-hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* B, const Dims& d, hipStream_t st);
+// copy `rows` batch rows into rows row0.. of a half buffer (half_rows rows per slab)
+hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* half, int half_rows, const Dims& d,
+                         hipStream_t st);
+hipError_t launch_probe_permute(const double* in, double* out, int NP, int LP, int ell, bool both, hipStream_t st);
 hipError_t launch_export_rows(const float* Bblk, int NPsrc, int nrows, float* out, const Dims& d, hipStream_t st);
 hipError_t launch_import_rows(const float* in, int nrows, float* Bblk, int NPdst, const Dims& d, hipStream_t st);
 hipError_t launch_zero_rows(float* Bblk, int NP, int r0, int r1, const Dims& d, hipStream_t st);
 
 // fd_gram.hip
+// The buffer is two half buffers (top: matrix rows 0 .. LP-1, new: matrix rows LP .. NP-1, the first nfill in use).
 struct GramPlan {
-    int tiles;        // 64x64 lower-triangle tiles = P(P+1)/2, P = NP/64
+    int mode;         // 0: tiles t0.. of the lower triangle; 1: new rows x top rows; 2: new rows x new rows (triangle)
+    int t0;           // mode 0: first tile computed (the top x top block before it is known to the caller)
+    int tiles;        // 64x64 tiles computed
     int wg_per_group; // ceil(tiles / 6): a work-group computes 12 half-tiles
     int groups;       // split-K groups (multiple of 8)
     int64_t slabs_per_group;
     size_t partial_floats; // groups * tiles * 4096
 };
-GramPlan gram_plan(const Dims& d, int num_cu);
-hipError_t launch_gram(const float* B, float* partial, const GramPlan& p, const Dims& d, hipStream_t st);
-hipError_t launch_gram_reduce(const float* partial, double* C, const GramPlan& p, const Dims& d, hipStream_t st);
+GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_per_cu);
+hipError_t launch_gram(const float* top, const float* nw, int nfill, float* partial, const GramPlan& p, const Dims& d,
+                       hipStream_t st);
+// C = sum of the partial tiles of launch a and (if given) launch b; known_top: the top x top block is diag(known)
+hipError_t launch_gram_reduce(const float* partial_a, const GramPlan& a, const float* partial_b, const GramPlan* b,
+                              double* C, bool known_top, const double* known, const Dims& d, hipStream_t st);
 
 // fd_eig.hip
 struct EigWork {
@@ -70,6 +79,7 @@ struct EigWork {
     double* stat;   // [0] trace, [1..MAXSWEEP] per-sweep max |off| / trace
     int* pos;       // NP: pos[rank] = column of Y holding the rank-th largest eigenvalue
     double* lam;    // NP: eigenvalues sorted descending
+    double* known;  // NP: squared norms of the rows the last shrink wrote (lambda_j - delta, 0 from row ell-1 on)
 };
 constexpr int MAX_SWEEPS = 14;
 // Stopping rule: a sweep records the largest |c_pq| / trace(C) it met before rotating; the solve ends after the
@@ -79,10 +89,11 @@ constexpr double JACOBI_TOL_SHRINK = 1e-7;
 constexpr double JACOBI_TOL_BASIS = 1e-9;
 hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st);
 // scalars on device: acc[0] sum_delta, acc[1] frob2, acc[2] last_delta, acc[3] sweeps used (as double)
-hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int frob_r0, int frob_r1, float* Mt,
+// frob2 += diag0 over matrix indices [ra0, ra1) and [rb0, rb1) (the rows not yet counted in ||A||_F^2)
+hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int ra0, int ra1, int rb0, int rb1, float* Mt,
                                 double* acc, double tol, hipStream_t st);
-hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int frob_r0, int frob_r1, float* Mt,
-                               double* acc, double tol, hipStream_t st);
+hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int ra0, int ra1, int rb0, int rb1,
+                               float* Mt, double* acc, double tol, hipStream_t st);
 
 // Where the coefficient M[m][i] (output row m < MP, buffer row i < NP) is stored for the rebuild kernel: chunks of
 // 16 buffer rows; inside a chunk [i & 1][m][(i & 15) >> 1], i.e. the 8 values a matrix-core lane needs are
@@ -94,9 +105,9 @@ __host__ __device__ inline int64_t coeff_offset(int i, int m, int MP) {
     return (int64_t)(i >> 4) * 16 * MP + ((h * MP + m) * 2 + piece) * 4 + (s & 3);
 }
 
-// fd_rebuild.hip: out[0:MP] = M * B over every column; Mc holds the NP x MP coefficients in coeff_offset order.
-// zero_tail: also clear buffer rows MP..NP-1 (shrink). out may alias B (in place) when out_NP == NP.
-hipError_t launch_rebuild(const float* B, const float* Mc, float* out, int out_NP, int MP, bool zero_tail,
+// fd_rebuild.hip: out[0:MP] = M * B over every column, B = [top; first nfill rows of nw; zeros]; Mc holds the NP x MP
+// coefficients in coeff_offset order; out has out_NP rows per slab and may be `top` itself (in place).
+hipError_t launch_rebuild(const float* top, const float* nw, int nfill, const float* Mc, float* out, int out_NP, int MP,
                           const Dims& d, hipStream_t st);
 
 // score.hip
