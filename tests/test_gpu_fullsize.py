@@ -1,0 +1,107 @@
+"""GPU checks at the full row width of the benchmark workload (config 5: D = 2,049,000 bf16 rows, ell = 256, k = 128,
+batches of 1024), in the launch configuration bench.py times. The CPU oracle cannot run a whole pass at this width
+in a test, so the checks are: the scoring arithmetic against a plain fp64 computation on the same bytes (numpy
+matmul as the one library step, column block by column block), sampled Gram entries computed one by one, and
+properties of the sketch that hold at any size (Method, FD paragraph; Algorithm 1).
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_2510_02470_amd import inputs  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64_rows(Gd, lo, hi):
+    """Columns [lo, hi) of a device batch as float64 on the host (bf16 / fp32 widened exactly)."""
+    return Gd[:, lo:hi].to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def test_scoring_at_full_width_matches_fp64():
+    """z = V^T g, zhat, consensus, cosine and selection for 2 x 1024 rows of full width against fp64 on the same bytes.
+    Both sides use the same given basis (random rows: the arithmetic does not need it to be orthonormal)."""
+    from paper_2510_02470_amd.binding import Sage
+
+    w = inputs.WORKLOADS[5]
+    ds = inputs.DeviceStream(w, w_dtype=torch.bfloat16)
+    batches = [ds.batch(b) for b in range(2)]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(12345)
+    V = torch.randn((w.k, w.D), generator=g, device="cuda", dtype=torch.float32) / np.sqrt(w.D)
+    s = Sage(w.ell, w.D, dtype=w.dtype, max_rows=2 * w.batch)
+    s.set_basis(V)
+    for b in batches:
+        s.score(b)
+    idx = s.select(0.05).cpu().numpy()
+    alpha = s.scores().cpu().numpy()
+    zhat = s.zhat().cpu().numpy()
+    # plain definition in fp64, column blocks of 2^16
+    N = 2 * w.batch
+    Z = np.zeros((N, w.k))
+    step = 1 << 16
+    for lo in range(0, w.D, step):
+        hi = min(w.D, lo + step)
+        Vb = V[:, lo:hi].cpu().numpy().astype(np.float64)
+        for i, b in enumerate(batches):
+            Z[i * w.batch:(i + 1) * w.batch] += _f64_rows(b, lo, hi) @ Vb.T
+    q = np.sqrt((Z * Z).sum(axis=1))
+    Zh = np.where(q[:, None] > 0, Z / np.where(q > 0, q, 1.0)[:, None], 0.0)
+    ssum = Zh.sum(axis=0)
+    u = ssum / np.sqrt((ssum * ssum).sum())
+    al = np.clip(Zh @ u, -1.0, 1.0)
+    assert np.abs(zhat - Zh).max() <= 1e-5
+    assert np.abs(alpha - al).max() <= 1e-4
+    m = int(np.floor(0.05 * N + 0.5))
+    assert len(idx) == m and idx.tolist() == oracle.topm_f32(alpha, m).tolist()
+    ref = set(np.lexsort((np.arange(N), -al))[:m].tolist())
+    tau = np.sort(al)[::-1][m - 1]
+    for i in set(idx.tolist()) ^ ref:
+        assert abs(al[i] - tau) <= 1e-4
+
+
+def test_update_at_full_width_properties_and_sampled_gram():
+    """Three batches (11 shrink cycles, the side-stream path included) at full width: sampled Gram entries against
+    fp64 dot products of the exported rows; after the stream the shrunk rows are orthogonal, row ell-1 on is zero,
+    and the energy bookkeeping holds: frob2 = sum ||g||^2, ell * sum(delta) <= ||A||_F^2 - ||B||_F^2."""
+    from paper_2510_02470_amd.binding import Sage
+
+    w = inputs.WORKLOADS[5]
+    ell = w.ell
+    ds = inputs.DeviceStream(w, w_dtype=torch.bfloat16)
+    s = Sage(ell, w.D, dtype=w.dtype)
+    fro = 0.0
+    for b in range(3):
+        G = ds.batch(b)
+        fro += float((G.to(torch.float32).double() ** 2).sum())
+        s.fd_update(G)
+    # 100 more rows so that the buffer holds shrunk rows and raw rows
+    G = ds.batch(3, rows=100)
+    fro += float((G.to(torch.float32).double() ** 2).sum())
+    s.fd_update(G)
+    del G
+    st = s.stats()
+    assert st.n_shrinks == 11 and st.fill == ell + 100 and st.rows_seen == 3 * w.batch + 100
+    assert abs(st.frob2 - fro) <= 1e-5 * fro
+    assert 0.0 <= st.sum_delta <= fro / ell
+    B = s.sketch()
+    assert not bool(B[ell - 1:ell].any()) and not bool(B[ell + 100:].any())
+    b2 = float((B.double() ** 2).sum())
+    assert ell * st.sum_delta <= (fro - b2) + 1e-5 * fro
+    # sampled Gram entries of the buffer (matrix cores, split over D) against fp64 dot products
+    Cm, _, _ = s.probe_gram_eig(False)
+    Cm = Cm.cpu().numpy()
+    rng = np.random.default_rng(5)
+    rows = sorted(set(rng.integers(0, ell + 100, size=10).tolist()) | {0, ell - 2, ell, ell + 99})
+    Bs = B[rows].cpu().numpy().astype(np.float64)
+    ref = Bs @ Bs.T
+    got = Cm[np.ix_(rows, rows)]
+    scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref))).max()
+    assert np.abs(got - ref).max() <= 2e-5 * scale  # fp32 accumulation of ~25,000 products per split
+    # the rows a shrink wrote are mutually orthogonal (relative to their norms)
+    T = B[:ell - 1].double()
+    Ct = (T @ T.T).cpu().numpy()
+    off = np.abs(Ct - np.diag(np.diag(Ct)))
+    assert off.max() <= 1e-5 * np.diag(Ct).max()

@@ -147,6 +147,29 @@ def test_sketch_covariance_matches_oracle(name):
         assert ev.min() >= -1e-5 * fro and ev.max() <= st.sum_delta + 1e-5 * fro
 
 
+@pytest.mark.parametrize("ell,D,cycles,batch", [(64, 1024, 600, 256), (128, 512, 60, 1000)])
+def test_long_stream_error_does_not_accumulate(ell, D, cycles, batch):
+    """Hundreds of shrink cycles: the GPU path takes the Gram block of the rows a shrink wrote as known (diagonal) and
+    forms the block of the next rows ahead of time on a side stream; its rounding must not pile up over a long
+    stream. Same bar as the short runs, against the oracle's Gram route."""
+    w = inputs.WORKLOADS[2].scaled(N=ell * (cycles + 1) + 17, D=D, ell=ell, k=ell // 2, batch=batch, r=48)
+    G = inputs.generate_numpy(w)
+    o, _ = run_oracle(w, G, mode=1, score=False)
+    s, _ = run_gpu(w, G, score=False)
+    st = s.stats()
+    assert st.n_shrinks == o.n_shrinks == cycles and st.fill == o.fill
+    A64 = G.astype(np.float64)
+    fro = (A64 ** 2).sum()
+    Bg = s.sketch().cpu().numpy()
+    err = cov_diff_spec_norm(Bg, o.B) / fro
+    assert err <= COV_TOL, err
+    assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro
+    assert abs(st.frob2 - fro) <= 1e-5 * fro
+    diff = A64.T @ A64 - Bg.astype(np.float64).T @ Bg.astype(np.float64)
+    ev = np.linalg.eigvalsh(diff)
+    assert ev.min() >= -1e-5 * fro and ev.max() <= st.sum_delta + 1e-5 * fro
+
+
 def test_sketch_is_deterministic():
     w = inputs.WORKLOADS[1].scaled(N=700)
     G = inputs.generate_numpy(w)
