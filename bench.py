@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--workload", type=int, default=5, choices=[3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB copy kernel (untimed): the known traffic that rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -89,9 +92,22 @@ def main():
     esz = 2 if w.dtype == "bf16" else 4
     ell, n, D, k = w.ell, 2 * w.ell, w.D, w.k
 
+    if args.copy_probe:
+        from paper_2510_02470_amd.binding import copy_probe
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        copy_probe(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ds = inputs.DeviceStream(w, w_dtype=torch.bfloat16)
     batches = [ds.batch(b) for b in range(W + K)]  # resident in HBM before anything is timed
     torch.cuda.synchronize()
+
+    def note(msg):   # progress on stderr (stdout carries the one JSON line)
+        print("bench: " + msg, file=sys.stderr, flush=True)
+
+    note("inputs resident")
 
     def run_pass(s, timed):
         """W warm-up steps then K steps of the whole path; returns the event times of the K steps (ms)."""
@@ -103,6 +119,7 @@ def main():
             s.score(batches[b])
         s.select(w.keep)
         torch.cuda.synchronize()
+        note("warm-up done")
         t0 = time.perf_counter()
         ev[0].record()
         for b in range(W, W + K):
@@ -117,6 +134,7 @@ def main():
         ev[4].record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        note("timed steps done")
         ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(4)]
         return ms, wall, idx
 
@@ -165,6 +183,7 @@ def main():
         s.profile_enable(False)
         s.close()
         del s
+        note("per-kernel pass done")
         traffic = {}
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic_cfg%d.json" % args.workload)
         if os.path.exists(tpath):

@@ -185,6 +185,14 @@ int sage_probe_gram_eig(sage_ctx* ctx, double* C_out, int eig, double* Y_out, do
 int sage_probe_eig_matrix(sage_ctx* ctx, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out);
 
 /*
+ * A plain device-to-device copy kernel of `bytes` bytes (16 bytes per work-item; bytes and both DEVICE pointers
+ * multiples of 16), asynchronous on hip_stream. Harnesses run it under a profiler to learn what the memory-traffic
+ * counters report for a known amount of traffic (bytes read, bytes written), and scale the readings of the path's
+ * kernels by that.
+ */
+int sage_copy_probe(void* dst, const void* src, int64_t bytes, void* hip_stream);
+
+/*
  * Per-kernel timing for harnesses: when enabled, every kernel launch is bracketed by HIP events on the
  * context's stream (this serialises host and device, so whole-call timings taken while it is on are not
  * representative). sage_profile_read waits, then reports the accumulated milliseconds and launch count of

@@ -20,7 +20,7 @@ EXPORTS = (
     "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_basis", "sage_score", "sage_select",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix",
-    "sage_profile_enable",
+    "sage_profile_enable", "sage_copy_probe",
     "sage_profile_read", "sage_strerror",
 )
 
@@ -69,6 +69,7 @@ def lib():
     L.sage_topm.argtypes = [vp, i64, i64, vp, vp]
     L.sage_probe_gram_eig.argtypes = [vp, vp, i32, vp, vp, C.POINTER(i32)]
     L.sage_probe_eig_matrix.argtypes = [vp, vp, vp, vp, vp]
+    L.sage_copy_probe.argtypes = [vp, vp, i64, vp]
     L.sage_profile_enable.argtypes = [vp, i32]
     L.sage_profile_read.argtypes = [vp, i32, C.POINTER(dbl), C.POINTER(i64)]
     L.sage_strerror.argtypes = [i32]
@@ -213,6 +214,16 @@ class Sage:
             _check(self.L.sage_profile_read(self.h, i, C.byref(ms), C.byref(n)), "sage_profile_read")
             out[name] = (ms.value, n.value)
         return out
+
+
+def copy_probe(dst, src):
+    """Plain copy kernel src -> dst (same byte size, multiple of 16): the calibration kernel for traffic counters."""
+    import torch
+
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and src.is_cuda and dst.is_cuda
+    stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().sage_copy_probe(_ptr(dst), _ptr(src), nbytes, C.c_void_p(stream)), "sage_copy_probe")
 
 
 def topm(alpha, m):

@@ -95,6 +95,20 @@ hipError_t launch_probe_permute(const double* in, double* out, int NP, int LP, i
     return hipGetLastError();
 }
 
+// plain copy, 16 bytes per thread (harnesses time / count it to calibrate hardware counters)
+__global__ __launch_bounds__(256) void plain_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst, int64_t n16) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+hipError_t launch_plain_copy(const void* src, void* dst, int64_t bytes, hipStream_t st) {
+    const int64_t n16 = bytes / 16;
+    if (n16 <= 0) return hipSuccess;
+    hipLaunchKernelGGL(plain_copy_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (const f32x4*)src,
+                       (f32x4*)dst, n16);
+    return hipGetLastError();
+}
+
 // zero buffer rows [r0, r1) in every slab
 __global__ __launch_bounds__(256) void zero_rows_kernel(float* __restrict__ Bblk, int NP, int r0, int r1, int64_t S) {
     int per_slab = (r1 - r0) * 4;  // float4 pieces per slab

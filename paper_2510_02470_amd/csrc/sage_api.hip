@@ -676,6 +676,12 @@ int sage_probe_eig_matrix(sage_ctx* c, const double* C_in, double* Y_out, double
     return SAGE_OK;
 }
 
+int sage_copy_probe(void* dst, const void* src, int64_t bytes, void* hip_stream) {
+    if (!dst || !src || bytes < 0 || bytes % 16 != 0 || ((uintptr_t)dst | (uintptr_t)src) % 16 != 0) return SAGE_ERR_ARG;
+    if (launch_plain_copy(src, dst, bytes, (hipStream_t)hip_stream) != hipSuccess) return SAGE_ERR_HIP;
+    return SAGE_OK;
+}
+
 int sage_profile_enable(sage_ctx* c, int on) {
     if (!c) return SAGE_ERR_ARG;
     c->prof = on != 0;

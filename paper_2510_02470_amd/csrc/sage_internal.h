@@ -45,6 +45,7 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_floa
 // copy `rows` batch rows into rows row0.. of a half buffer (half_rows rows per slab)
 hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* half, int half_rows, const Dims& d,
                          hipStream_t st);
+hipError_t launch_plain_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
 hipError_t launch_probe_permute(const double* in, double* out, int NP, int LP, int ell, bool both, hipStream_t st);
 hipError_t launch_export_rows(const float* Bblk, int NPsrc, int nrows, float* out, const Dims& d, hipStream_t st);
 hipError_t launch_import_rows(const float* in, int nrows, float* Bblk, int NPdst, const Dims& d, hipStream_t st);
