@@ -52,7 +52,8 @@ typedef struct {
     double sum_delta;    /* sum of the delta of every shrink: upper bound on ||A^T A - B^T B||_2 */
     double frob2;        /* ||A||_F^2 of the rows seen, fp32 products accumulated in fp32/fp64 */
     double last_delta;   /* delta of the most recent shrink */
-    int last_sweeps;     /* Jacobi sweeps used by the most recent eigensolve */
+    int last_sweeps;     /* Jacobi sweeps used by the most recent eigensolve (100 + the sweeps launched if they did
+                            not reach the tolerance; the next solves then launch the full number) */
     int fill;            /* buffer rows in use, 0..2*ell-1 */
 } sage_stats_t;
 
@@ -180,7 +181,7 @@ int sage_probe_gram_eig(sage_ctx* ctx, double* C_out, int eig, double* Y_out, do
  * Stage probe: run the context's Jacobi eigensolve on a symmetric matrix given by the caller. C_in: DEVICE,
  * n_pad*n_pad doubles (n_pad as reported by sage_probe_gram_eig), left untouched. Y_out, lam_out as above.
  * sweep_stat_out: DEVICE, 18 doubles: [0] trace, [1+s] largest |off-diagonal| / trace met in sweep s (0 for
- * sweeps that were skipped), [17] unused. Outputs may be NULL. The sketch is not modified. Waits.
+ * sweeps that were skipped), [17] the number of sweeps launched. Outputs may be NULL. The sketch is not modified. Waits.
  */
 int sage_probe_eig_matrix(sage_ctx* ctx, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out);
 

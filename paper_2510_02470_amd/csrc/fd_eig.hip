@@ -87,7 +87,8 @@ __device__ __forceinline__ void rot_params_fast(double app, double aqq, double a
 
 // Y = I, diag0 = diag(C), stat[0] = trace(C), stat[1..] = 0. grid = NP blocks of 256.
 __global__ __launch_bounds__(256) void jac_init_kernel(const double* __restrict__ C, double* __restrict__ Y,
-                                                       double* __restrict__ diag0, double* __restrict__ stat, int NP) {
+                                                       double* __restrict__ diag0, double* __restrict__ stat, int NP,
+                                                       int max_sweeps) {
     int row = blockIdx.x;
     for (int c = threadIdx.x; c < NP; c += 256) Y[(int64_t)row * NP + c] = (c == row) ? 1.0 : 0.0;
     if (row == 0) {
@@ -107,6 +108,7 @@ __global__ __launch_bounds__(256) void jac_init_kernel(const double* __restrict_
             stat[0] = tr > 0.0 ? tr : 0.0;
         }
         if (threadIdx.x >= 1 && threadIdx.x <= MAX_SWEEPS + 1) stat[threadIdx.x] = 0.0;
+        if (threadIdx.x == MAX_SWEEPS + 3) stat[MAX_SWEEPS + 3] = (double)max_sweeps;
     }
 }
 
@@ -424,6 +426,7 @@ __global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict
 __global__ __launch_bounds__(512) void eig_sort_kernel(const double* __restrict__ C, const double* __restrict__ stat,
                                                        int* __restrict__ pos, double* __restrict__ lam, int NP,
                                                        double* __restrict__ acc, double tol) {
+    // stat[17] holds the number of sweeps that were launched (written by jac_init_kernel)
     __shared__ double l[512];
     int j = threadIdx.x;
     double v = 0.0;
@@ -443,8 +446,9 @@ __global__ __launch_bounds__(512) void eig_sort_kernel(const double* __restrict_
         lam[rank] = v;
     }
     if (j == 0) {
-        int used = MAX_SWEEPS;
-        for (int s = 0; s < MAX_SWEEPS; ++s)
+        const int launched = (int)stat[MAX_SWEEPS + 3];
+        int used = launched + SWEEPS_NOT_CONVERGED;  // the measurement after the last launched sweep was still > tol
+        for (int s = 0; s <= launched && s <= MAX_SWEEPS; ++s)
             if (stat[1 + s] <= tol) { used = s; break; }
         acc[3] = (double)used;
     }
@@ -509,19 +513,21 @@ __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restr
 static const size_t DIAG_LDS = (size_t)(2 * 64 * LDA + 64) * sizeof(double);
 static const size_t APPLY_LDS = (size_t)(64 * LDX + 64 * LDQB + 64 * LDQ) * sizeof(double);
 
-hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st) {
+hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st) {
     static bool attr = false;
     if (!attr) {
         (void)hipFuncSetAttribute((const void*)jac_diag_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)DIAG_LDS);
         (void)hipFuncSetAttribute((const void*)jac_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)APPLY_LDS);
         attr = true;
     }
-    hipLaunchKernelGGL(jac_init_kernel, dim3(NP), dim3(256), 0, st, w.C, w.Y, w.diag0, w.stat, NP);
+    if (max_sweeps > MAX_SWEEPS) max_sweeps = MAX_SWEEPS;
+    if (max_sweeps < 1) max_sweeps = 1;
+    hipLaunchKernelGGL(jac_init_kernel, dim3(NP), dim3(256), 0, st, w.C, w.Y, w.diag0, w.stat, NP, max_sweeps);
     const int np = NP / 64, nb = NP / 32;
     // nb is even, so every sweep starts and ends on buffer 0: that is where the result is, whenever it converged
     double* Cb[2] = {w.C, w.C2};
     double* Yb[2] = {w.Y, w.Y2};
-    for (int sweep = 0; sweep < MAX_SWEEPS; ++sweep) {
+    for (int sweep = 0; sweep < max_sweeps; ++sweep) {
         hipLaunchKernelGGL(jac_measure_kernel, dim3(NP / 16), dim3(256), 0, st, w.C, w.stat, NP, sweep, tol);
         for (int s = 0; s < nb; ++s) {
             const int cur = s & 1;
@@ -533,6 +539,8 @@ hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st) {
                                Yb[cur ^ 1], w.Q, w.stat, NP, sweep, s, tol);
         }
     }
+    // what the last launched sweep left: eig_sort_kernel tells a converged solve from one that ran out of sweeps
+    hipLaunchKernelGGL(jac_measure_kernel, dim3(NP / 16), dim3(256), 0, st, w.C, w.stat, NP, max_sweeps, tol);
     return hipGetLastError();
 }
 

@@ -45,6 +45,14 @@ struct sage_ctx {
     float* Mt = nullptr;
     double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps
 
+    // Sweeps to launch for a shrink's eigensolve: what the last read-back solve needed, plus one. The count comes back
+    // through pinned host memory without the host ever waiting for it.
+    int sweep_cap = MAX_SWEEPS;
+    double* h_sweeps = nullptr;                    // pinned, SWEEP_RING slots
+    hipEvent_t ev_sweeps[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool sweeps_pending[4] = {false, false, false, false};
+    int sweeps_next = 0;
+
     int fill_top = 0, fill_new = 0;  // rows in use in top (0..ell) and in nw[cur] (0..ell)
     int cnt_top = 0, cnt_new = 0;    // of those, rows already counted in frob2
     int64_t rows_seen = 0, n_shrinks = 0;
@@ -120,6 +128,38 @@ int pad_pow2_32(int v) {
 
 bool use_side(const sage_ctx* c) { return c->st2 != nullptr; }
 
+constexpr int SWEEP_RING = 4;
+
+// Pick up the sweep counts that have arrived and set the number of sweeps to launch next.
+void poll_sweeps(sage_ctx* c) {
+    for (int i = 0; i < SWEEP_RING; ++i) {
+        if (!c->sweeps_pending[i]) continue;
+        hipError_t e = hipEventQuery(c->ev_sweeps[i]);
+        if (e == hipErrorNotReady) {
+            (void)hipGetLastError();
+            continue;
+        }
+        c->sweeps_pending[i] = false;
+        if (e != hipSuccess) continue;
+        const int used = (int)c->h_sweeps[i];
+        if (used >= SWEEPS_NOT_CONVERGED) c->sweep_cap = MAX_SWEEPS;  // ran out: launch them all next time
+        else c->sweep_cap = used + 1 < 3 ? 3 : (used + 1 > MAX_SWEEPS ? MAX_SWEEPS : used + 1);
+    }
+}
+
+// After a shrink's coefficient kernels: send the sweep count (acc[3]) home.
+void post_sweeps(sage_ctx* c) {
+    const int i = c->sweeps_next;
+    if (c->sweeps_pending[i] || !c->h_sweeps) return;  // slot still in flight: skip this one
+    if (hipMemcpyAsync(c->h_sweeps + i, c->acc + 3, sizeof(double), hipMemcpyDeviceToHost, c->st) != hipSuccess ||
+        hipEventRecord(c->ev_sweeps[i], c->st) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+    }
+    c->sweeps_pending[i] = true;
+    c->sweeps_next = (i + 1) % SWEEP_RING;
+}
+
 // Gram + eigensolve of the buffer as it stands. After a shrink the top rows are orthogonal with known squared norms
 // (lambda_j - delta), so their block is not recomputed.
 int decompose(sage_ctx* c, double tol, bool full) {
@@ -127,7 +167,7 @@ int decompose(sage_ctx* c, double tol, bool full) {
     const GramPlan& gp = skip ? c->gp_skip : c->gp;
     RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, gp, c->d, c->st));
     RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
-    RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, c->st));
+    RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, MAX_SWEEPS, c->st));
     return SAGE_OK;
 }
 
@@ -160,10 +200,12 @@ int shrink(sage_ctx* c, const void* next, int64_t next_rows) {
         HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], c->gp_new, c->d, c->st2));
         HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
     }
-    RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->st));
+    poll_sweeps(c);
+    RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweep_cap, c->st));
     RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, LP, ell, c->cnt_top, c->fill_top, LP + c->cnt_new, LP + c->fill_new,
                                       c->Mt, c->acc, JACOBI_TOL_SHRINK, c->st));
     RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], ell, c->Mt, c->top, LP, LP, c->d, c->st));
+    post_sweeps(c);
     if (use_side(c)) c->cur ^= 1;  // two new halves alternate; with a single Gram panel there is only nw[0]
     c->fill_top = ell;
     c->cnt_top = ell;
@@ -347,6 +389,12 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     if (hipMemsetAsync(c->top, 0, hbytes, c->st) != hipSuccess) return fail(SAGE_ERR_HIP);
     if (hipMemsetAsync(c->acc, 0, 8 * sizeof(double), c->st) != hipSuccess) return fail(SAGE_ERR_HIP);
     if (hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) return fail(SAGE_ERR_HIP);
+    if (hipHostMalloc((void**)&c->h_sweeps, SWEEP_RING * sizeof(double), hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        c->h_sweeps = nullptr;  // not fatal: every solve then launches all its sweeps
+    }
+    for (int i = 0; i < SWEEP_RING; ++i)
+        if (hipEventCreateWithFlags(&c->ev_sweeps[i], hipEventDisableTiming) != hipSuccess) return fail(SAGE_ERR_HIP);
     *out = c;
     return SAGE_OK;
 }
@@ -364,7 +412,9 @@ void sage_destroy(sage_ctx* c) {
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (c->st2) (void)hipStreamDestroy(c->st2);
-    hipEvent_t evs[] = {c->ev_mark, c->ev_side[0], c->ev_side[1]};
+    if (c->h_sweeps) (void)hipHostFree(c->h_sweeps);
+    hipEvent_t evs[] = {c->ev_mark, c->ev_side[0], c->ev_side[1], c->ev_sweeps[0], c->ev_sweeps[1], c->ev_sweeps[2],
+                        c->ev_sweeps[3]};
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
     free_select_work(c->sw);
@@ -651,7 +701,7 @@ int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, doub
     // (rows 0 .. 2*ell-1, padding last).
     if (C_out) HIPCHK(launch_probe_permute(c->ew.C, C_out, NP, LP, ell, true, c->st));
     if (eig) {
-        HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, c->st));
+        HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, MAX_SWEEPS, c->st));
         if (Y_out) HIPCHK(launch_probe_permute(c->ew.Y, Y_out, NP, LP, ell, false, c->st));
         if (lam_out)
             HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double),
@@ -665,7 +715,7 @@ int sage_probe_eig_matrix(sage_ctx* c, const double* C_in, double* Y_out, double
     if (!c || !C_in) return SAGE_ERR_ARG;
     const int NP = c->d.NP;
     HIPCHK(hipMemcpyAsync(c->ew.C, C_in, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
-    HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, c->st));
+    HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, MAX_SWEEPS, c->st));
     if (Y_out) HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
     if (lam_out)
         HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double), NP,

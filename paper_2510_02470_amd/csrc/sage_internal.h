@@ -88,7 +88,10 @@ constexpr int MAX_SWEEPS = 14;
 // matrix (~1e-7 trace); the scoring basis is taken once per pass and is solved tighter.
 constexpr double JACOBI_TOL_SHRINK = 1e-7;
 constexpr double JACOBI_TOL_BASIS = 1e-9;
-hipError_t launch_eig(const EigWork& w, int NP, double tol, hipStream_t st);
+// max_sweeps <= MAX_SWEEPS sweeps are launched (sweeps after convergence return at once). acc[3] of the coefficient
+// kernels then holds the sweeps that were needed, or max_sweeps + SWEEPS_NOT_CONVERGED when they did not suffice.
+constexpr int SWEEPS_NOT_CONVERGED = 100;
+hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st);
 // scalars on device: acc[0] sum_delta, acc[1] frob2, acc[2] last_delta, acc[3] sweeps used (as double)
 // frob2 += diag0 over matrix indices [ra0, ra1) and [rb0, rb1) (the rows not yet counted in ||A||_F^2)
 hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int ra0, int ra1, int rb0, int rb1, float* Mt,
