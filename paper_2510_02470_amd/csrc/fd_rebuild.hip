@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
     constexpr int PER = CHUNK4 / 256;    // pieces per thread per stage (MT / 2 ... at least 1)
     static_assert(CHUNK4 % 256 == 0 || CHUNK4 < 256, "chunk must tile the work-group");
     constexpr int PERC = PER > 0 ? PER : 1;
-    __shared__ f32x4 Ms[2][CHUNK4];
+    __shared__ f32x4 Ms[3][CHUNK4];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c = lane & 31, h = lane >> 5;
@@ -37,17 +37,19 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
     const float* tcol = top + coff;
     const float* ncol = nw + coff;
     // rows 16*stg + 2*s + h of the matrix: stage stg lies in the top half when stg < LP/16. Rows of the new half are
-    // always loaded (they exist) and zeroed afterwards when they are not in use.
+    // always loaded (they exist); those not in use are zeroed when the stage consumes them (use_b), not here, so
+    // that nothing waits for a load right after issuing it.
     auto fetch_b = [&](int stg, float (&b)[8]) {
         const int r0 = stg * 16;
-        const bool isnew = r0 >= LP;
-        const float* bn = isnew ? ncol + (int64_t)(r0 - LP) * DC : tcol + (int64_t)r0 * DC;
-        const int limit = isnew ? nfill - (r0 - LP) - h : 0x7fffffff;  // 2*s < limit: row in use
+        const float* bn = r0 >= LP ? ncol + (int64_t)(r0 - LP) * DC : tcol + (int64_t)r0 * DC;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            float v = bn[(int64_t)(2 * s) * DC];
-            b[s] = 2 * s < limit ? v : 0.f;
-        }
+        for (int s = 0; s < 8; ++s) b[s] = bn[(int64_t)(2 * s) * DC];
+    };
+    auto use_b = [&](int stg, const float (&b)[8], float (&o)[8]) {
+        const int r0 = stg * 16;
+        const int limit = r0 >= LP ? nfill - (r0 - LP) - h : 0x7fffffff;  // 2*s < limit: row in use
+#pragma unroll
+        for (int s = 0; s < 8; ++s) o[s] = 2 * s < limit ? b[s] : 0.f;
     };
 
     f32x16 acc[MT];
@@ -59,49 +61,68 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
     const f32x4* Mv = reinterpret_cast<const f32x4*>(Mc);
     float bpre[8];
     f32x4 mpre[PERC];
-    // prologue: stage 0
+    // prologue: coefficients of stages 0 and 1 into LDS, row operand of stage 0 on its way
+    const int nstage = NP / 16;
     fetch_b(0, bpre);
 #pragma unroll
     for (int u = 0; u < PERC; ++u)
-        if (u * 256 + tid < CHUNK4) Ms[0][u * 256 + tid] = Mv[u * 256 + tid];
+        if (u * 256 + tid < CHUNK4) {
+            Ms[0][u * 256 + tid] = Mv[u * 256 + tid];
+            if (nstage > 1) Ms[1][u * 256 + tid] = Mv[(int64_t)CHUNK4 + u * 256 + tid];
+        }
     __syncthreads();
 
-    // LDS piece of (half h, coefficient row m, logical piece p): ((h * MP + m) * 2 + (p ^ ((m >> 3) & 1)))
+    // LDS piece of (half h, coefficient row m, logical piece p): ((h * MP + m) * 2 + (p ^ ((m >> 3) & 1))).
+    // The coefficient pieces are read from LDS while the matrix cores work: those of the second k-half of a stage
+    // during its first half, those of the first k-half of the next stage during its second half (one read per four
+    // matrix-core instructions, pinned by scheduling barriers). Three LDS buffers: stage s reads buffers s and s+1 and
+    // fills buffer s+2 (mod 3), which was last read in stage s-1.
     const int x = (c >> 3) & 1;
-    const int nstage = NP / 16;
+    int lbase[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) lbase[m] = (h * MP + m * 32 + c) * 2;
+    f32x4 a0[MT], a1[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) a0[m] = Ms[0][lbase[m] + x];
+    int cur = 0;
     for (int stg = 0; stg < nstage; ++stg) {
-        const int cur = stg & 1;
+        const int nxt = cur == 2 ? 0 : cur + 1, far = nxt == 2 ? 0 : nxt + 1;
         float bcur[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) bcur[s] = bpre[s];
-        const bool more = stg + 1 < nstage;
-        if (more) {
-            fetch_b(stg + 1, bpre);
+        use_b(stg, bpre, bcur);
+        const bool more = stg + 1 < nstage, more2 = stg + 2 < nstage;
+        // the coefficient loads first: waiting for them (to put them in LDS) then leaves the row loads in flight
+        if (more2) {
 #pragma unroll
             for (int u = 0; u < PERC; ++u)
-                if (u * 256 + tid < CHUNK4) mpre[u] = Mv[(int64_t)(stg + 1) * CHUNK4 + u * 256 + tid];
+                if (u * 256 + tid < CHUNK4) mpre[u] = Mv[(int64_t)(stg + 2) * CHUNK4 + u * 256 + tid];
         }
-        f32x4 a[MT][2];
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            const int base = (h * MP + m * 32 + c) * 2;
-            a[m][0] = Ms[cur][base + x];
-            a[m][1] = Ms[cur][base + (x ^ 1)];
-        }
-        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads ahead of the matrix-core block
-#pragma unroll
-        for (int p = 0; p < 2; ++p)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int m = 0; m < MT; ++m) acc[m] = mfma32(a[m][p][e], bcur[4 * p + e], acc[m]);
+        if (more) fetch_b(stg + 1, bpre);
         __builtin_amdgcn_sched_barrier(0);
-        if (more) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {  // first k-half; fetch a1[i]
+            a1[i] = Ms[cur][lbase[i] + (x ^ 1)];
+#pragma unroll
+            for (int j = 4 * i; j < 4 * i + 4; ++j) acc[j % MT] = mfma32(a0[j % MT][j / MT], bcur[j / MT], acc[j % MT]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {  // second k-half; fetch the next stage's a0[i] (its last use was above)
+            if (more) a0[i] = Ms[nxt][lbase[i] + x];
+#pragma unroll
+            for (int j = 4 * i; j < 4 * i + 4; ++j) acc[j % MT] = mfma32(a1[j % MT][j / MT], bcur[4 + j / MT], acc[j % MT]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more2) {
 #pragma unroll
             for (int u = 0; u < PERC; ++u)
-                if (u * 256 + tid < CHUNK4) Ms[cur ^ 1][u * 256 + tid] = mpre[u];
+                if (u * 256 + tid < CHUNK4) Ms[far][u * 256 + tid] = mpre[u];
         }
-        __syncthreads();
+        // A bare barrier after the LDS traffic: __syncthreads() would also wait for the row loads still in flight.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): vmcnt and expcnt not waited for
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        cur = nxt;
     }
 
     if (!live) return;
