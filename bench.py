@@ -159,7 +159,7 @@ def main():
     gram_tiles = (n // 64) * (n // 64 + 1) // 2 - (ell // 64) * (ell // 64 + 1) // 2   # top x top block is known
     algo = {
         # work per launch: (bound, executed flops or algorithmic bytes)
-        "gram": ("mfma", gram_tiles * tile_flop),
+        "gram": ("mfma", gram_tiles * tile_flop),          # per cycle; split over the cycle's launches below
         "rebuild": ("mfma", 2.0 * ell * n * D),
         "project": ("hbm", w.batch * (esz * D + 4.0 * k) + 4.0 * k * D),
         "insert": ("hbm", (esz + 4.0) * ell * D),
@@ -195,6 +195,8 @@ def main():
             e = {"avg_ms": ms / cnt, "launches": cnt, "total_ms": ms}
             if name in algo:
                 bound, work = algo[name]
+                if name == "gram":   # two launches per cycle (new x new block, new x top block): rate over both
+                    work = work * pr["rebuild"][1] / cnt
                 rate = work / (ms / cnt * 1e-3)
                 e["bound"] = bound
                 e["achieved"] = rate / 1e12 if bound == "mfma" else rate / 1e9

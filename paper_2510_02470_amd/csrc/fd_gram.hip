@@ -175,6 +175,124 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const float* __restrict__ 
     }
 }
 
+// The (new rows) x (top rows) rectangle for NP = 512, with wider wave tiles than gram_kernel's: a wave owns 128 new rows
+// x 64 top rows (8 accumulator tiles), so the 256 x 256 rectangle is exactly 8 wave tiles = 2 work-groups per column
+// range -- no idle wave slots, a third less staging traffic than 3 work-groups, and 12 operand reads per 64
+// matrix-core instructions instead of 18 per 48. Same staging, LDS layout and partial-tile output as gram_kernel
+// in mode 1 (tile index (ti - 4) * 4 + tj).
+__global__ __launch_bounds__(256, 2) void gram_cross8_kernel(const float* __restrict__ top, const float* __restrict__ nw,
+                                                             int nfill, float* __restrict__ partial,
+                                                             int64_t slabs_total, int64_t slabs_per_group) {
+    constexpr int P = 8, NP = 512, LP = 256;
+    constexpr int STAGE = NP * 4;
+    constexpr int HALF4 = LP * 4;
+    extern __shared__ f32x4 lds[];
+
+    const int id = blockIdx.x;
+    const int xcd = id & 7;
+    const int y = id >> 3;
+    const int w = y & 1;  // 2 work-groups per group
+    const int group = (y >> 1) * 8 + xcd;
+    int64_t s0 = (int64_t)group * slabs_per_group;
+    int64_t s1 = s0 + slabs_per_group;
+    if (s1 > slabs_total) s1 = slabs_total;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wt = w * 4 + wave;          // wave tile 0..7
+    const int ag = wt >> 2, bg = wt & 3;  // new rows 128*ag .. + 128, top rows 64*bg .. + 64
+    const int arow = LP + ag * 128 + l32; // + 32 * i, i < 4 (matrix row index: new half starts at LP)
+    const int brow = bg * 64 + l32;       // + 32 * cb
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][b][e] = 0.f;
+
+    int src[P];
+#pragma unroll
+    for (int it = 0; it < P; ++it) {
+        int ps = it * 256 + tid;
+        int row = ps >> 2;
+        int p = (ps & 3) ^ ((row >> 2) & 3);
+        int hr = row >= LP ? row - LP : row;
+        src[it] = (row >= LP && hr >= nfill) ? -1 : hr * 4 + p;
+    }
+    const f32x4* Tv = reinterpret_cast<const f32x4*>(top);
+    const f32x4* Nv = reinterpret_cast<const f32x4*>(nw);
+    f32x4 pre[P];
+    auto fetch = [&](int64_t sl) {
+#pragma unroll
+        for (int it = 0; it < P; ++it) {
+            const f32x4* base = (it >= P / 2 ? Nv : Tv) + sl * HALF4;  // rows it*64 .. : the new half from it = 4 on
+            pre[it] = src[it] >= 0 ? base[src[it]] : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    if (s0 < s1) {
+        fetch(s0);
+#pragma unroll
+        for (int it = 0; it < P; ++it) lds[it * 256 + tid] = pre[it];
+    }
+    __syncthreads();
+
+    for (int64_t s = s0; s < s1; ++s) {
+        const int cur = (int)((s - s0) & 1);
+        const bool more = (s + 1 < s1);
+        if (more) fetch(s + 1);
+        const f32x4* st = lds + cur * STAGE;
+        f32x4 a[2][4], b[2][2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int p = 2 * j + h;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ra = arow + 32 * i;
+                a[j][i] = st[ra * 4 + (p ^ ((ra >> 2) & 3))];
+            }
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const int rb = brow + 32 * cb;
+                b[j][cb] = st[rb * 4 + (p ^ ((rb >> 2) & 3))];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above: the scheduler would sink each next to its use
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb) acc[i][cb] = mfma32(a[j][i][c], b[j][cb][c], acc[i][cb]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+            f32x4* nx = lds + (cur ^ 1) * STAGE;
+#pragma unroll
+            for (int it = 0; it < P; ++it) nx[it * 256 + tid] = pre[it];
+        }
+        __syncthreads();
+    }
+
+    // tiles (ti - 4, tj) = (2*ag + i/2, bg); rows (i & 1) * 32 .. + 32 of the tile
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int tidx = (2 * ag + (i >> 1)) * 4 + bg;
+        float* out = partial + ((int64_t)group * 16 + tidx) * 4096 + (i & 1) * 2048;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int r = 8 * (e >> 2) + 4 * h + (e & 3);
+                int c = cb * 32 + l32;
+                out[r * 64 + c] = acc[i][cb][e];
+            }
+    }
+}
+
 // C (NP x NP, fp64, both triangles) = sum over groups of the partial tiles, in group order. With q = P/2:
 // known_top: tiles with ti < q are not summed, their block is diag(known) (the top rows are the orthogonal rows the
 // last shrink wrote, whose squared norms it recorded). Otherwise tile (ti, tj) comes from source A when its mode
@@ -206,8 +324,19 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(GramSrc a, GramSrc b, 
         int ia = gram_src_index(a, P, t, ti, tj);
         const GramSrc& g = ia >= 0 ? a : b;
         int idx = ia >= 0 ? ia : gram_src_index(b, P, t, ti, tj);
-        if (idx >= 0)
-            for (int k = 0; k < g.groups; ++k) s += (double)g.partial[((int64_t)k * g.tiles + idx) * 4096 + e];
+        if (idx >= 0) {
+            const float* p0 = g.partial + (int64_t)idx * 4096 + e;
+            const int64_t gstride = (int64_t)g.tiles * 4096;
+            int k = 0;
+            for (; k + 8 <= g.groups; k += 8) {  // eight loads in flight, added in group order
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = p0[(k + u) * gstride];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s += (double)v[u];
+            }
+            for (; k < g.groups; ++k) s += (double)p0[k * gstride];
+        }
     }
     C[(int64_t)gr * NP + gc] = s;
     C[(int64_t)gc * NP + gr] = s;
@@ -230,6 +359,7 @@ GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_pe
         p.tiles = (P - q) * (P - q + 1) / 2;
     }
     p.wg_per_group = (p.tiles + 5) / 6;
+    if (mode == 1 && P == 8) p.wg_per_group = 2;  // gram_cross8_kernel: 8 wave tiles of 128 x 64
     const int cus = wg_per_cu == 1 && num_cu > 32 ? num_cu - 16 : num_cu;
     int g = (wg_per_cu * cus / p.wg_per_group) / 8 * 8;
     if (g < 8) g = 8;
@@ -248,6 +378,15 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
     if (p.tiles <= 0) return hipSuccess;
     dim3 grid((unsigned)(p.groups * p.wg_per_group));
     size_t lds = (size_t)2 * d.NP * 64;
+    if (p.mode == 1 && d.NP == 512) {
+        static bool attr8 = false;
+        if (!attr8) {
+            (void)hipFuncSetAttribute((const void*)gram_cross8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+            attr8 = true;
+        }
+        hipLaunchKernelGGL(gram_cross8_kernel, grid, dim3(256), lds, st, top, nw, nfill, partial, d.S, p.slabs_per_group);
+        return hipGetLastError();
+    }
     switch (d.NP / 64) {
 #define SAGE_GRAM_CASE(PP)                                                                                          \
     case PP: {                                                                                                      \

@@ -38,6 +38,7 @@ struct sage_ctx {
     GramPlan gp_skip{};   // without the top x top block (known after a shrink)
     GramPlan gp_cross{};  // new rows x top rows
     GramPlan gp_new{};    // new rows x new rows, one work-group per CU (it shares the chip with the eigensolve)
+    GramPlan gp_new2{};   // the same block with the chip to itself (context stream, when there was nothing to look ahead to)
     bool top_shrunk = false;  // top holds exactly what the last shrink wrote
     float* gram_partial = nullptr;
     float* gram_partial_new[2] = {nullptr, nullptr};
@@ -177,12 +178,19 @@ int decompose(sage_ctx* c, double tol, bool full) {
 // eigensolve runs on the context stream (neither needs its result, and the eigensolve leaves most of the chip idle).
 int shrink(sage_ctx* c, const void* next, int64_t next_rows) {
     const int LP = c->d.LP, ell = c->d.ell;
-    if (c->new_block_ready) {
-        // the new x new block came from the side stream; only new x top is left
-        HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
+    if (c->new_block_ready || (c->top_shrunk && c->gp_cross.tiles > 0)) {
+        // The top x top block is known. The new x new block came from the side stream, or is formed here when there
+        // was nothing to look ahead to (first cycle of a call); then only new x top is left.
+        const GramPlan* gn = &c->gp_new;
+        if (c->new_block_ready) {
+            HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
+        } else {
+            gn = &c->gp_new2;
+            RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial_new[c->cur], *gn, c->d, c->st));
+        }
         RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, c->gp_cross, c->d, c->st));
-        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->gp_cross, c->gram_partial_new[c->cur], &c->gp_new, c->ew.C,
-                                         true, c->ew.known, c->d, c->st));
+        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->gp_cross, c->gram_partial_new[c->cur], gn, c->ew.C, true,
+                                         c->ew.known, c->d, c->st));
     } else {
         const bool skip = c->top_shrunk && c->gp_skip.t0 > 0;
         const GramPlan& gp = skip ? c->gp_skip : c->gp;
@@ -338,6 +346,7 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     if (P >= 2) {
         c->gp_cross = gram_plan(c->d, c->num_cu, 1, false, 2);
         c->gp_new = gram_plan(c->d, c->num_cu, 2, false, 1);
+        c->gp_new2 = gram_plan(c->d, c->num_cu, 2, false, 2);
     }
     c->fixed_cap = max_rows > 0;
     c->cap_rows = max_rows > 0 ? max_rows : 65536;
@@ -365,8 +374,10 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     }
     if (P >= 2) {
         CALLOC(c->nw[1], hbytes);
-        CALLOC(c->gram_partial_new[0], c->gp_new.partial_floats * sizeof(float));
-        CALLOC(c->gram_partial_new[1], c->gp_new.partial_floats * sizeof(float));
+        const size_t pn = c->gp_new.partial_floats > c->gp_new2.partial_floats ? c->gp_new.partial_floats
+                                                                                : c->gp_new2.partial_floats;
+        CALLOC(c->gram_partial_new[0], pn * sizeof(float));
+        CALLOC(c->gram_partial_new[1], pn * sizeof(float));
         if (hipStreamCreateWithFlags(&c->st2, hipStreamNonBlocking) != hipSuccess) return fail(SAGE_ERR_HIP);
         if (hipEventCreateWithFlags(&c->ev_mark, hipEventDisableTiming) != hipSuccess) return fail(SAGE_ERR_HIP);
         for (int i = 0; i < 2; ++i)
