@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=16)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", type=int, default=5, choices=[3, 4, 5])
+    ap.add_argument("--workload", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -89,6 +89,8 @@ def main():
     torch.cuda.set_device(0)
     w = inputs.WORKLOADS[args.workload]
     K, W = args.steps, max(1, args.warmup)
+    if (W + K) * w.batch > w.N:          # small workloads: no more steps than the stream has batches
+        K = max(1, w.N // w.batch - W)
     esz = 2 if w.dtype == "bf16" else 4
     ell, n, D, k = w.ell, 2 * w.ell, w.D, w.k
 

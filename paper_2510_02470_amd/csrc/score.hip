@@ -148,66 +148,54 @@ __global__ __launch_bounds__(256) void project_kernel(const T* __restrict__ G, i
 }
 
 // Sum of the split-K partial projections, normalisation and consensus partial sums.
-// 4 rows per work-group, one after the other; for a row each of the 4 waves adds a quarter of the splits (in order,
-// eight independent loads at a time), the quarters are added in wave order, and lane j then holds coordinates j and
-// j + 64. Writes zhat (R x k, fp32) and cons_partial[block][128] (fp64 sums of the block's zhat). All in fp64, fixed
-// order: the result does not depend on timing.
+// One wave per row (4 rows per work-group): lane j holds coordinates j and j + 64 and adds the splits in order, sixteen
+// independent loads at a time. Writes zhat (R x k, fp32) and cons_partial[block][128] (fp64 sums of the block's
+// zhat, the four rows added in wave order). All in fp64, fixed order: the result does not depend on timing.
 constexpr int FIN_ROWS = 4;
 __global__ __launch_bounds__(256) void score_finalize_kernel(const float* __restrict__ partial, int64_t R, int KP, int k,
                                                              int splits, float* __restrict__ zhat,
                                                              double* __restrict__ cons_partial) {
-    __shared__ double zs[4][128];
+    __shared__ double cs[4][128];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool on0 = lane < KP, on1 = lane + 64 < KP;
-    const int s_lo = (int)((int64_t)wave * splits / 4), s_hi = (int)((int64_t)(wave + 1) * splits / 4);
-    double cons0 = 0.0, cons1 = 0.0;
-    for (int q = 0; q < FIN_ROWS; ++q) {
-        const int64_t r = (int64_t)blockIdx.x * FIN_ROWS + q;
-        if (r >= R) break;
+    const int64_t r = (int64_t)blockIdx.x * FIN_ROWS + wave;
+    float h0 = 0.f, h1 = 0.f;
+    if (r < R) {
         double z0 = 0.0, z1 = 0.0;
-        for (int s = s_lo; s < s_hi; s += 8) {
-            float v0[8], v1[8];
+        const float* p0 = partial + r * KP + lane;
+        const int64_t sstride = R * KP;
+        for (int s = 0; s < splits; s += 16) {
+            float v0[16], v1[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int ss = s + u < s_hi ? s + u : s_hi - 1;  // repeats are not added
-                const float* p = partial + ((int64_t)ss * R + r) * KP;
-                v0[u] = on0 ? p[lane] : 0.f;
-                v1[u] = on1 ? p[lane + 64] : 0.f;
+            for (int u = 0; u < 16; ++u) {
+                const int ss = s + u < splits ? s + u : splits - 1;  // repeats are not added
+                v0[u] = on0 ? p0[ss * sstride] : 0.f;
+                v1[u] = on1 ? p0[ss * sstride + 64] : 0.f;
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (s + u < s_hi) {
+            for (int u = 0; u < 16; ++u)
+                if (s + u < splits) {
                     z0 += (double)v0[u];
                     z1 += (double)v1[u];
                 }
         }
-        zs[wave][lane] = z0;
-        zs[wave][lane + 64] = z1;
-        __syncthreads();
-        if (wave == 0) {
-            z0 = ((zs[0][lane] + zs[1][lane]) + zs[2][lane]) + zs[3][lane];
-            z1 = ((zs[0][lane + 64] + zs[1][lane + 64]) + zs[2][lane + 64]) + zs[3][lane + 64];
-            if (lane >= k) z0 = 0.0;
-            if (lane + 64 >= k) z1 = 0.0;
-            double q2 = z0 * z0 + z1 * z1;
-            for (int o = 32; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
-            const double nrm = sqrt(q2);
-            float h0 = 0.f, h1 = 0.f;
-            if (nrm > 0.0) {
-                h0 = (float)(z0 / nrm);
-                h1 = (float)(z1 / nrm);
-            }
-            if (lane < k) zhat[r * k + lane] = h0;
-            if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
-            cons0 += (double)h0;
-            cons1 += (double)h1;
+        if (lane >= k) z0 = 0.0;
+        if (lane + 64 >= k) z1 = 0.0;
+        double q2 = z0 * z0 + z1 * z1;
+        for (int o = 32; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
+        const double nrm = sqrt(q2);
+        if (nrm > 0.0) {
+            h0 = (float)(z0 / nrm);
+            h1 = (float)(z1 / nrm);
         }
-        __syncthreads();
+        if (lane < k) zhat[r * k + lane] = h0;
+        if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
     }
-    if (wave == 0) {
-        cons_partial[(int64_t)blockIdx.x * 128 + lane] = cons0;
-        cons_partial[(int64_t)blockIdx.x * 128 + lane + 64] = cons1;
-    }
+    cs[wave][lane] = (double)h0;
+    cs[wave][lane + 64] = (double)h1;
+    __syncthreads();
+    if (tid < 128)
+        cons_partial[(int64_t)blockIdx.x * 128 + tid] = ((cs[0][tid] + cs[1][tid]) + cs[2][tid]) + cs[3][tid];
 }
 
 // ssum[j] += sum over blocks of cons_partial[block][j]: thread (group g = tid / 128, coordinate j = tid % 128) adds
