@@ -85,6 +85,10 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
  * w_j = sqrt(max(lambda_j - delta, 0) / lambda_j) (fp32 matrix cores), rows ell.. zeroed.
  * G_batch: DEVICE, rows x D of the context's dtype. rows >= 0 (0 is a no-op). Asynchronous on the context's
  * stream. Invalidates a basis made earlier. The host never reads device data in this call.
+ * When a call ends exactly on a full buffer, that shrink is left for the next sage_fd_update (which can then overlap
+ * part of it with the storing of its own first rows) or for the first call that looks at the sketch (sage_fd_basis,
+ * sage_stats, the exports and probes); results are the same either way. Part of the work runs on a second stream
+ * owned by the context; the batch is free for reuse once the call's work is complete on the context's stream.
  */
 int sage_fd_update(sage_ctx* ctx, const void* G_batch, int64_t rows);
 

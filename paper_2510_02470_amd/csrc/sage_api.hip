@@ -32,6 +32,7 @@ struct sage_ctx {
     hipStream_t st2 = nullptr;                   // side stream (only when the Gram has >= 2 row panels)
     hipEvent_t ev_mark = nullptr;                // context stream: the Gram matrix of the current cycle is complete
     hipEvent_t ev_side[2] = {nullptr, nullptr};  // side stream: rows stored in nw[i] and their Gram block formed
+    bool pending_shrink = false;   // the buffer is full, its shrink waits for the next update call (see sage_fd_update)
     bool pre_stored = false;       // the side stream has stored the next ell rows of the running call in nw[cur]
     bool new_block_ready = false;  // ... and their Gram block is (or will be, see ev_side) in gram_partial_new[cur]
     GramPlan gp{};        // whole lower triangle
@@ -224,6 +225,13 @@ int shrink(sage_ctx* c, const void* next, int64_t next_rows) {
     c->n_shrinks += 1;
     c->top_shrunk = true;
     return SAGE_OK;
+}
+
+// A shrink that was left for the next update call: do it now (something wants to see the sketch).
+int flush_pending(sage_ctx* c) {
+    if (!c->pending_shrink) return SAGE_OK;
+    c->pending_shrink = false;
+    return shrink(c, nullptr, 0);
 }
 
 void reset_scoring(sage_ctx* c) {
@@ -447,6 +455,13 @@ int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
     const char* g = (const char*)G_batch;
     const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
     const int ell = c->d.ell, LP = c->d.LP;
+    if (c->pending_shrink) {
+        // the buffer filled up exactly at the end of the previous call: with this call's rows at hand the shrink can
+        // look ahead
+        c->pending_shrink = false;
+        int rc = shrink(c, g, rows);
+        if (rc != SAGE_OK) return rc;
+    }
     while (rows > 0) {
         int take;
         if (c->fill_top < ell) {
@@ -468,12 +483,19 @@ int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
         g += (size_t)take * c->d.D * esz;
         rows -= take;
         if (c->fill_new == ell) {
-            int rc = shrink(c, g, rows);
-            if (rc != SAGE_OK) return rc;
+            if (rows == 0 && use_side(c) && c->top_shrunk && !c->prof) {
+                // Nothing to look ahead to: leave the shrink to the next update call, which brings rows (whoever
+                // looks at the sketch first does it otherwise). The side stream may still be reading this batch for
+                // the half just completed: the context stream waits for it, so that the batch is free once this
+                // call's work is complete there.
+                c->pending_shrink = true;
+                if (c->new_block_ready) HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
+            } else {
+                int rc = shrink(c, g, rows);
+                if (rc != SAGE_OK) return rc;
+            }
         }
     }
-    // Side-stream work is always picked up by a shrink of the same call (it waits for ev_side), so when this call's
-    // work is complete on the context stream nothing reads the batch any more.
     return SAGE_OK;
 }
 
@@ -481,7 +503,9 @@ int sage_fd_basis(sage_ctx* c, int k) {
     if (!c) return SAGE_ERR_ARG;
     if (k < 1 || k > c->d.ell - 1 || k > 128) return SAGE_ERR_ARG;
     const int KP = pad_pow2_32(k);
-    int rc = ensure_vblk(c, KP);
+    int rc = flush_pending(c);
+    if (rc != SAGE_OK) return rc;
+    rc = ensure_vblk(c, KP);
     if (rc != SAGE_OK) return rc;
     rc = decompose(c, JACOBI_TOL_BASIS, false);
     if (rc != SAGE_OK) return rc;
@@ -619,6 +643,8 @@ int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* 
 
 int sage_fd_sketch_export(sage_ctx* c, float* B_out) {
     if (!c || !B_out) return SAGE_ERR_ARG;
+    int rcf = flush_pending(c);
+    if (rcf != SAGE_OK) return rcf;
     const int ell = c->d.ell;
     HIPCHK(launch_export_rows(c->top, c->d.LP, ell, B_out, c->d, c->st));
     HIPCHK(launch_export_rows(c->nw[c->cur], c->d.LP, c->fill_new, B_out + (size_t)ell * c->d.D, c->d, c->st));
@@ -666,6 +692,8 @@ int sage_zhat_export(sage_ctx* c, float* zhat_out) {
 
 int sage_stats(sage_ctx* c, sage_stats_t* out) {
     if (!c || !out) return SAGE_ERR_ARG;
+    int rcf = flush_pending(c);
+    if (rcf != SAGE_OK) return rcf;
     double acc[8];
     HIPCHK(hipMemcpyAsync(acc, c->acc, sizeof(acc), hipMemcpyDeviceToHost, c->st));
     HIPCHK(hipStreamSynchronize(c->st));
@@ -706,6 +734,8 @@ int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, doub
     const int NP = c->d.NP, LP = c->d.LP, ell = c->d.ell;
     if (n_pad) *n_pad = NP;
     if (!C_out && !eig) return SAGE_OK;
+    int rcf = flush_pending(c);
+    if (rcf != SAGE_OK) return rcf;
     HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp, c->d, c->st));
     HIPCHK(launch_gram_reduce(c->gram_partial, c->gp, nullptr, nullptr, c->ew.C, false, c->ew.known, c->d, c->st));
     // Inside the library matrix index LP + j stands for buffer row ell + j; the probe reports buffer-row order
