@@ -101,6 +101,14 @@ int sage_fd_update(sage_ctx* ctx, const void* G_batch, int64_t rows);
 int sage_fd_basis(sage_ctx* ctx, int k);
 
 /*
+ * As sage_fd_basis, but row j of the basis is sqrt(max(sigma_j^2 - delta, 0)) v_j^T with delta = sigma_ell^2 of the
+ * buffer as it stands: the first k rows of the sketch S = Sigma' V^T that a shrink would write, so that sage_score
+ * computes the paper's own projection z = S g (Method, "Two-pass scoring"; Algorithm 1, Phase II) on its k leading
+ * rows. Right after a shrink these are the sketch rows themselves. The sketch is left unchanged.
+ */
+int sage_fd_basis_weighted(sage_ctx* ctx, int k);
+
+/*
  * Pass 2 (Algorithm 1, Phase II, first line): for each row g of the batch z = V_k^T g, zhat = z/||z||_2 (0 if
  * z = 0); zhat is stored at the row's example index and added to the consensus sum.
  * G_batch: DEVICE, rows x D of the context's dtype. Needs a basis (else SAGE_ERR_STATE). Asynchronous.
@@ -116,6 +124,24 @@ int sage_score(sage_ctx* ctx, const void* G_batch, int64_t rows);
  * cap = 0 and m = 0). out_m: HOST, receives m. Waits for the stream. May be called again (e.g. another rate).
  */
 int sage_select(sage_ctx* ctx, double keep_rate, int64_t* out_idx, int64_t cap, int64_t* out_m);
+
+/*
+ * Class-balanced variant, CB-SAGE (Algorithm 1, "if class balance required"; "Agreement Scoring and Selection").
+ * sage_score_labeled is sage_score with the class label of every row: labels: DEVICE, `rows` int32, each in
+ * [0, n_classes) of the later sage_select_cb call (checked there). A pass must be scored entirely with labels to be
+ * selected class by class (SAGE_ERR_STATE otherwise); sage_select may still be called on it.
+ *
+ * sage_select_cb: for every class c, zbar_c = mean of zhat over its rows, u_c = zbar_c / ||zbar_c||_2 (0 if the sum is 0),
+ * alpha_i = <zhat_i, u_c(i)> clamped to [-1, 1] (-0 stored as +0), and the k_c rows of the class that are greatest under
+ * (alpha descending, index ascending) are kept, with k_c = floor(keep_rate * N_c + 0.5) -- the paper leaves the k_c
+ * open; this takes the same rate in every class, so that sum(k_c) is the subset size. All kept indices are written in
+ * ascending order. out_idx: DEVICE, room for `cap` int64 (SAGE_ERR_CAPACITY if sum(k_c) > cap); out_m: HOST, receives
+ * sum(k_c). 1 <= n_classes <= 65536. A label outside [0, n_classes) gives SAGE_ERR_ARG. Waits for the stream.
+ * sage_scores / sage_scores_export then give these class-wise scores. Class sums are accumulated in 64-bit fixed
+ * point (2^-40 resolution), so the result does not depend on the order in which the device adds.
+ */
+int sage_score_labeled(sage_ctx* ctx, const void* G_batch, const int32_t* labels, int64_t rows);
+int sage_select_cb(sage_ctx* ctx, double keep_rate, int n_classes, int64_t* out_idx, int64_t cap, int64_t* out_m);
 
 /* Release the context and everything it owns (waits for its stream). NULL is allowed. */
 void sage_destroy(sage_ctx* ctx);

@@ -37,6 +37,7 @@ def _load():
         getattr(L, name).argtypes = [vp, vp, i64]
         getattr(L, name).restype = i32
     L.orc_basis.argtypes = [vp, i32]
+    L.orc_basis_weighted.argtypes = [vp, i32]
     L.orc_set_basis.argtypes = [vp, vp, i32]
     L.orc_select.argtypes = [vp, dbl, vp, i64, vp]
     L.orc_topm_f32.argtypes = [vp, i64, i64, vp]
@@ -98,8 +99,9 @@ class Oracle:
         rc = fn(self.h, G.ctypes.data, G.shape[0])
         assert rc == 0
 
-    def basis(self, k):
-        rc = self.L.orc_basis(self.h, int(k))
+    def basis(self, k, weighted=False):
+        """weighted: rows sqrt(sigma_j^2 - delta) v_j^T (the sketch rows a shrink would write) instead of v_j^T."""
+        rc = (self.L.orc_basis_weighted if weighted else self.L.orc_basis)(self.h, int(k))
         if rc != 0:
             raise ValueError("basis: need 1 <= k <= ell-1")
         self.k = int(k)
@@ -127,6 +129,12 @@ class Oracle:
         if rc != 0:
             raise RuntimeError("select failed rc=%d" % rc)
         return out[: m.value].copy()
+
+    def select_cb(self, keep_rate, labels, n_classes):
+        """Class-balanced selection (Algorithm 1, "if class balance required"): per class c the unit centroid u_c of the
+        stored zhat of its rows, alpha_i = <zhat_i, u_c(i)> clamped, and the k_c = floor(keep*N_c + 0.5) rows of the
+        class greatest under (alpha as float32 descending, index ascending). Returns (alpha float64, indices ascending)."""
+        return cb_scores_and_selection(self.zhat, labels, n_classes, keep_rate)
 
     # ---- views (copies) ----
     def _arr(self, ptr, shape):
@@ -225,6 +233,46 @@ def topm_f32(alpha, m):
     if rc != 0:
         raise ValueError("need 0 <= m <= N")
     return out[: int(m)].copy()
+
+
+def cb_alpha(zhat, labels, n_classes):
+    """alpha_i = clamp(<zhat_i, u_c(i)>, -1, 1) with u_c = sum of the class's zhat, normalised (0 if the sum is 0)."""
+    zhat = np.asarray(zhat, dtype=np.float64)
+    labels = np.asarray(labels)
+    alpha = np.zeros(zhat.shape[0])
+    for c in range(int(n_classes)):
+        rows = np.nonzero(labels == c)[0]
+        if rows.size == 0:
+            continue
+        s = np.zeros(zhat.shape[1])
+        for i in rows:               # plain ordered sum, as the definition reads
+            s += zhat[i]
+        nrm = float(np.sqrt(np.dot(s, s)))
+        u = s / nrm if nrm > 0.0 else np.zeros_like(s)
+        alpha[rows] = np.clip(zhat[rows] @ u, -1.0, 1.0)
+    return alpha
+
+
+def cb_select_from_alpha(alpha, labels, n_classes, keep_rate):
+    """Per class the k_c = floor(keep*N_c + 0.5) rows greatest under (float32 alpha descending, index ascending);
+    all kept indices ascending."""
+    a32 = np.asarray(alpha).astype(np.float32)
+    a32 = np.where(a32 == 0, np.float32(0), a32)     # -0 -> +0
+    labels = np.asarray(labels)
+    kept = []
+    for c in range(int(n_classes)):
+        rows = np.nonzero(labels == c)[0]
+        kc = keep_count(keep_rate, rows.size)
+        if kc == 0:
+            continue
+        order = sorted(rows.tolist(), key=lambda i: (-float(a32[i]), i))
+        kept.extend(order[:kc])
+    return np.array(sorted(kept), dtype=np.int64)
+
+
+def cb_scores_and_selection(zhat, labels, n_classes, keep_rate):
+    alpha = cb_alpha(zhat, labels, n_classes)
+    return alpha, cb_select_from_alpha(alpha, labels, n_classes, keep_rate)
 
 
 def keep_count(keep_rate, N):

@@ -317,8 +317,12 @@ int orc_update_bf16(orc_ctx *c, const uint16_t *G, int64_t rows) {
     return 0;
 }
 
-/* Freeze: top-k right singular vectors of the buffer as it stands; no shrink; B unchanged. */
-int orc_basis(orc_ctx *c, int k) {
+/* Freeze: top-k right singular vectors of the buffer as it stands; no shrink; B unchanged.
+ * weighted = 0: rows v_j^T (the reading used by default, see the header).
+ * weighted = 1: rows sqrt(max(sigma_j^2 - delta, 0)) v_j^T with delta = sigma_ell^2, i.e. the first k rows of the
+ *   sketch S = Sigma' V^T that a shrink of the buffer would write -- the paper's own projection z = S g ("Two-pass
+ *   scoring"; Algorithm 1, Phase II), restricted to k rows. Right after a shrink these are the sketch rows themselves. */
+static int basis_common(orc_ctx *c, int k, int weighted) {
     if (k < 1 || k > c->ell - 1 || k > 1024) return -1;
     decompose(c);
     free(c->V); free(c->s); free(c->zhat); free(c->alpha);
@@ -327,16 +331,24 @@ int orc_basis(orc_ctx *c, int k) {
     c->zhat = NULL; c->alpha = NULL; c->n_scored = 0; c->cap_scored = 0;
     c->k = k;
     double thr = (double)c->n * 1.1920928955078125e-07 * c->sig2[0]; /* n * 2^-23 * sigma_1^2 */
+    double delta = c->sig2[c->ell - 1];
     for (int j = 0; j < k; ++j) {
         double s2 = c->sig2[j];
         if (s2 <= thr || s2 <= 0.0) continue; /* rank-deficient: v_j := 0 */
-        double inv = 1.0 / sqrt(s2);
+        double f = 1.0 / sqrt(s2);            /* W holds sigma_j v_j^T */
+        if (weighted) {
+            double keep = s2 - delta;
+            f = keep > 0.0 ? sqrt(keep / s2) : 0.0;
+        }
         const double *w = c->W + (int64_t)j * c->D;
         double *v = c->V + (int64_t)j * c->D;
-        for (int64_t d = 0; d < c->D; ++d) v[d] = w[d] * inv;
+        for (int64_t d = 0; d < c->D; ++d) v[d] = w[d] * f;
     }
     return 0;
 }
+
+int orc_basis(orc_ctx *c, int k) { return basis_common(c, k, 0); }
+int orc_basis_weighted(orc_ctx *c, int k) { return basis_common(c, k, 1); }
 
 /* test hook: take a basis given by the caller (k x D, rows v_j^T) */
 int orc_set_basis(orc_ctx *c, const double *Vt, int k) {

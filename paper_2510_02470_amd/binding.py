@@ -17,7 +17,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 
 # every symbol include/sage.h declares
 EXPORTS = (
-    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_basis", "sage_score", "sage_select",
+    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix",
     "sage_profile_enable", "sage_copy_probe",
@@ -53,8 +53,11 @@ def lib():
     L.sage_fd_create_ex.argtypes = [C.POINTER(vp), i32, i64, i32, i64, vp]
     L.sage_fd_update.argtypes = [vp, vp, i64]
     L.sage_fd_basis.argtypes = [vp, i32]
+    L.sage_fd_basis_weighted.argtypes = [vp, i32]
     L.sage_score.argtypes = [vp, vp, i64]
     L.sage_select.argtypes = [vp, dbl, vp, i64, C.POINTER(i64)]
+    L.sage_score_labeled.argtypes = [vp, vp, vp, i64]
+    L.sage_select_cb.argtypes = [vp, dbl, i32, vp, i64, C.POINTER(i64)]
     L.sage_destroy.argtypes = [vp]
     L.sage_destroy.restype = None
     L.sage_sync.argtypes = [vp]
@@ -128,8 +131,11 @@ class Sage:
         G = self._rows(G)
         _check(self.L.sage_fd_update(self.h, _ptr(G), G.shape[0]), "sage_fd_update")
 
-    def fd_basis(self, k):
-        _check(self.L.sage_fd_basis(self.h, int(k)), "sage_fd_basis")
+    def fd_basis(self, k, weighted=False):
+        if weighted:
+            _check(self.L.sage_fd_basis_weighted(self.h, int(k)), "sage_fd_basis_weighted")
+        else:
+            _check(self.L.sage_fd_basis(self.h, int(k)), "sage_fd_basis")
         self.k = int(k)
 
     def set_basis(self, Vt):
@@ -144,6 +150,21 @@ class Sage:
     def score(self, G):
         G = self._rows(G)
         _check(self.L.sage_score(self.h, _ptr(G), G.shape[0]), "sage_score")
+
+    def score_labeled(self, G, labels):
+        G = self._rows(G)
+        assert labels.is_cuda and labels.is_contiguous() and labels.dtype == self.torch.int32
+        assert labels.numel() == G.shape[0]
+        _check(self.L.sage_score_labeled(self.h, _ptr(G), _ptr(labels), G.shape[0]), "sage_score_labeled")
+
+    def select_cb(self, keep_rate, n_classes, cap=None):
+        st = self.stats()
+        cap = st.n_scored if cap is None else int(cap)
+        out = self.torch.empty(max(cap, 1), dtype=self.torch.int64, device="cuda")
+        m = C.c_int64(0)
+        _check(self.L.sage_select_cb(self.h, float(keep_rate), int(n_classes), _ptr(out), cap, C.byref(m)),
+               "sage_select_cb")
+        return out[: m.value]
 
     def select(self, keep_rate, cap=None):
         st = self.stats()

@@ -486,19 +486,26 @@ __global__ __launch_bounds__(256) void shrink_coeffs_kernel(const double* __rest
 }
 
 // Basis coefficients: v_m^T = y_m^T B / sqrt(lambda_m) for m < k, or 0 when lambda_m <= n 2^-23 lambda_1.
+// weighted: the row is scaled by sqrt(max(lambda_m - delta, 0)) with delta = lambda_ell, which makes it the m-th row of
+// the sketch a shrink of the buffer would write (the paper's own projection z = S g, "Two-pass scoring").
 __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restrict__ Y, const int* __restrict__ pos,
                                                            const double* __restrict__ lam,
                                                            const double* __restrict__ diag0, int NP, int KP, int k, int n,
-                                                           int ra0, int ra1, int rb0, int rb1, float* __restrict__ Mt,
-                                                           double* __restrict__ acc) {
+                                                           int ell, int weighted, int ra0, int ra1, int rb0, int rb1,
+                                                           float* __restrict__ Mt, double* __restrict__ acc) {
     int e = blockIdx.x * 256 + threadIdx.x;
     const double thr = (double)n * 1.1920928955078125e-07 * lam[0];
+    const double delta = lam[ell - 1];
     if (e < NP * KP) {
         int i = e / KP, m = e % KP;
         float out = 0.f;
         if (m < k) {
             double lm = lam[m];
-            if (lm > thr && lm > 0.0) out = (float)(Y[(int64_t)i * NP + pos[m]] / sqrt(lm));
+            if (lm > thr && lm > 0.0) {
+                double f = 1.0 / sqrt(lm);
+                if (weighted) f = lm - delta > 0.0 ? sqrt((lm - delta) / lm) : 0.0;
+                out = (float)(Y[(int64_t)i * NP + pos[m]] * f);
+            }
         }
         Mt[coeff_offset(i, m, KP)] = out;
     }
@@ -552,11 +559,11 @@ hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int r
     return hipGetLastError();
 }
 
-hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int ra0, int ra1, int rb0, int rb1,
-                               float* Mt, double* acc, double tol, hipStream_t st) {
+hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int ell, bool weighted, int ra0, int ra1,
+                               int rb0, int rb1, float* Mt, double* acc, double tol, hipStream_t st) {
     hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc, tol);
     hipLaunchKernelGGL(basis_coeffs_kernel, dim3((NP * KP + 255) / 256), dim3(256), 0, st, w.Y, w.pos, w.lam, w.diag0,
-                       NP, KP, k, n, ra0, ra1, rb0, rb1, Mt, acc);
+                       NP, KP, k, n, ell, weighted ? 1 : 0, ra0, ra1, rb0, rb1, Mt, acc);
     return hipGetLastError();
 }
 

@@ -69,6 +69,10 @@ struct sage_ctx {
     int proj_mode = SAGE_PROJ_AUTO;
     float* zhat = nullptr;
     int64_t cap_rows = 0, n_scored = 0;
+    int* labels = nullptr;       // class label of every scored row (sage_score_labeled), same capacity as zhat
+    int64_t n_labeled = 0;       // rows of the current pass that came with a label
+    void* cb_work = nullptr;     // work space of the class-balanced selection
+    size_t cb_work_bytes = 0;
     bool fixed_cap = false;
     float* proj_partial = nullptr;
     size_t proj_partial_floats = 0;
@@ -236,6 +240,7 @@ int flush_pending(sage_ctx* c) {
 
 void reset_scoring(sage_ctx* c) {
     c->n_scored = 0;
+    c->n_labeled = 0;
     c->alpha_n = 0;
 }
 
@@ -427,7 +432,7 @@ void sage_destroy(sage_ctx* c) {
     void* ptrs[] = {c->top,     c->nw[0],    c->nw[1],  c->gram_partial, c->gram_partial_new[0], c->gram_partial_new[1],
                     c->ew.C,    c->ew.Y,     c->ew.C2,  c->ew.Y2,        c->ew.Q,    c->ew.diag0, c->ew.stat,
                     c->ew.pos,  c->ew.lam,   c->ew.known, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
-                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha};
+                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (c->st2) (void)hipStreamDestroy(c->st2);
@@ -499,7 +504,13 @@ int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
     return SAGE_OK;
 }
 
-int sage_fd_basis(sage_ctx* c, int k) {
+static int basis_impl(sage_ctx* c, int k, bool weighted);
+
+int sage_fd_basis(sage_ctx* c, int k) { return basis_impl(c, k, false); }
+
+int sage_fd_basis_weighted(sage_ctx* c, int k) { return basis_impl(c, k, true); }
+
+static int basis_impl(sage_ctx* c, int k, bool weighted) {
     if (!c) return SAGE_ERR_ARG;
     if (k < 1 || k > c->d.ell - 1 || k > 128) return SAGE_ERR_ARG;
     const int KP = pad_pow2_32(k);
@@ -509,8 +520,8 @@ int sage_fd_basis(sage_ctx* c, int k) {
     if (rc != SAGE_OK) return rc;
     rc = decompose(c, JACOBI_TOL_BASIS, false);
     if (rc != SAGE_OK) return rc;
-    RUN(K_COEFF, launch_basis_coeffs(c->ew, c->d.NP, KP, k, c->d.n, c->cnt_top, c->fill_top, c->d.LP + c->cnt_new,
-                                     c->d.LP + c->fill_new, c->Mt, c->acc, JACOBI_TOL_BASIS, c->st));
+    RUN(K_COEFF, launch_basis_coeffs(c->ew, c->d.NP, KP, k, c->d.n, c->d.ell, weighted, c->cnt_top, c->fill_top,
+                                     c->d.LP + c->cnt_new, c->d.LP + c->fill_new, c->Mt, c->acc, JACOBI_TOL_BASIS, c->st));
     c->cnt_top = c->fill_top;
     c->cnt_new = c->fill_new;
     RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Vblk, KP, KP, c->d, c->st));
@@ -545,7 +556,16 @@ int sage_set_basis(sage_ctx* c, const float* Vt, int k) {
     return ensure_score_buffers(c);
 }
 
-int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) {
+static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64_t rows);
+
+int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) { return score_impl(c, G_batch, nullptr, rows); }
+
+int sage_score_labeled(sage_ctx* c, const void* G_batch, const int32_t* labels, int64_t rows) {
+    if (rows > 0 && !labels) return SAGE_ERR_ARG;
+    return score_impl(c, G_batch, labels, rows);
+}
+
+static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64_t rows) {
     if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     if (rows == 0) return SAGE_OK;
@@ -563,7 +583,24 @@ int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) {
         }
         (void)hipFree(c->zhat);
         c->zhat = nz;
+        if (c->labels) {
+            int* nl = nullptr;
+            ALLOC(nl, (size_t)ncap * sizeof(int));
+            if (hipMemcpyAsync(nl, c->labels, (size_t)c->n_scored * sizeof(int), hipMemcpyDeviceToDevice, c->st) !=
+                    hipSuccess ||
+                hipStreamSynchronize(c->st) != hipSuccess) {
+                (void)hipFree(nl);
+                return SAGE_ERR_HIP;
+            }
+            (void)hipFree(c->labels);
+            c->labels = nl;
+        }
         c->cap_rows = ncap;
+    }
+    if (labels) {
+        if (!c->labels) ALLOC(c->labels, (size_t)c->cap_rows * sizeof(int));
+        HIPCHK(hipMemcpyAsync(c->labels + c->n_scored, labels, (size_t)rows * sizeof(int), hipMemcpyDeviceToDevice, c->st));
+        if (c->n_labeled == c->n_scored) c->n_labeled += rows;  // stays behind for good once an unlabeled batch came
     }
     const char* g = (const char*)G_batch;
     const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
@@ -621,6 +658,53 @@ int sage_select(sage_ctx* c, double keep_rate, int64_t* out_idx, int64_t cap, in
     RUN(K_SELECT, launch_cosine(c->zhat, N, c->k, c->ssum, c->alpha, c->st));
     c->alpha_n = N;
     RUN(K_SELECT, launch_topm(c->alpha, N, m, out_idx, c->sw, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_select_cb(sage_ctx* c, double keep_rate, int n_classes, int64_t* out_idx, int64_t cap, int64_t* out_m) {
+    if (!c || !out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0) || n_classes < 1 || n_classes > 65536)
+        return SAGE_ERR_ARG;
+    if (!c->has_basis) return SAGE_ERR_STATE;
+    const int64_t N = c->n_scored;
+    if (c->n_labeled != N) return SAGE_ERR_STATE;  // every row of the pass must have come with a label
+    *out_m = 0;
+    if (N > c->alpha_cap) {
+        if (c->alpha) {
+            HIPCHK(hipStreamSynchronize(c->st));
+            (void)hipFree(c->alpha);
+            c->alpha = nullptr;
+        }
+        free_select_work(c->sw);
+        int64_t ncap = N > c->cap_rows ? N : c->cap_rows;
+        ALLOC(c->alpha, (size_t)ncap * sizeof(float));
+        int rc = alloc_select_work(c->sw, ncap);
+        if (rc != SAGE_OK) return rc;
+        c->alpha_cap = ncap;
+    }
+    const size_t need = cb_work_bytes(n_classes, N);
+    if (need > c->cb_work_bytes) {
+        if (c->cb_work) {
+            HIPCHK(hipStreamSynchronize(c->st));
+            (void)hipFree(c->cb_work);
+            c->cb_work = nullptr;
+            c->cb_work_bytes = 0;
+        }
+        ALLOC(c->cb_work, need);
+        c->cb_work_bytes = need;
+    }
+    const CbWork w = cb_work_layout(c->cb_work, n_classes, N);
+    RUN(K_SELECT, launch_cb_scores(c->zhat, c->labels, N, c->k, n_classes, keep_rate, c->alpha, w, c->st));
+    c->alpha_n = N;
+    uint32_t misc[2] = {0, 0};
+    HIPCHK(hipMemcpyAsync(misc, w.misc, sizeof(misc), hipMemcpyDeviceToHost, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    if (misc[1]) return SAGE_ERR_ARG;  // a label outside [0, n_classes)
+    const int64_t m = (int64_t)misc[0];
+    *out_m = m;
+    if (m > cap) return SAGE_ERR_CAPACITY;
+    if (m > 0 && !out_idx) return SAGE_ERR_ARG;
+    if (m > 0) RUN(K_SELECT, launch_cb_select(c->alpha, c->labels, N, n_classes, out_idx, w, c->st));
     HIPCHK(hipStreamSynchronize(c->st));
     return SAGE_OK;
 }

@@ -96,8 +96,9 @@ hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipS
 // frob2 += diag0 over matrix indices [ra0, ra1) and [rb0, rb1) (the rows not yet counted in ||A||_F^2)
 hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int ra0, int ra1, int rb0, int rb1, float* Mt,
                                 double* acc, double tol, hipStream_t st);
-hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int ra0, int ra1, int rb0, int rb1,
-                               float* Mt, double* acc, double tol, hipStream_t st);
+// weighted: rows sqrt(max(lambda_j - lambda_ell, 0)) v_j^T instead of v_j^T
+hipError_t launch_basis_coeffs(const EigWork& w, int NP, int KP, int k, int n, int ell, bool weighted, int ra0, int ra1,
+                               int rb0, int rb1, float* Mt, double* acc, double tol, hipStream_t st);
 
 // Where the coefficient M[m][i] (output row m < MP, buffer row i < NP) is stored for the rebuild kernel: chunks of
 // 16 buffer rows; inside a chunk [i & 1][m][(i & 15) >> 1], i.e. the 8 values a matrix-core lane needs are
@@ -149,5 +150,26 @@ struct SelectWork {
 constexpr int SELECT_BLOCK = 2048;  // keys per block in the compaction passes
 hipError_t launch_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, const SelectWork& w,
                        hipStream_t st);
+
+// select_cb.hip: class-balanced selection (per-class centroid, cosine to it, top k_c of every class)
+struct CbWork {
+    long long* sums;   // C x 128 fixed-point class sums of zhat
+    double* ucls;      // C x 128 unit centroids
+    uint32_t* counts;  // rows per class
+    uint32_t* kc;      // rows kept per class
+    uint32_t* prefix;  // radix-select state: key prefix decided so far (after the index phase: index threshold)
+    uint32_t* remain;  // ... keys still to take among those matching the prefix
+    uint32_t* thr;     // score-key threshold per class
+    uint32_t* hist;    // C x 256 bins
+    uint32_t* misc;    // [0] total kept, [1] a label was out of range
+    uint32_t* blk;     // per block of SELECT_BLOCK rows: rows kept (then their exclusive scan)
+    uint8_t* sel;      // per row: kept
+};
+size_t cb_work_bytes(int C, int64_t N);
+CbWork cb_work_layout(void* base, int C, int64_t N);
+hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int k, int C, double keep, float* alpha,
+                            const CbWork& w, hipStream_t st);
+hipError_t launch_cb_select(const float* alpha, const int* labels, int64_t N, int C, int64_t* out_idx, const CbWork& w,
+                            hipStream_t st);
 
 }  // namespace sage

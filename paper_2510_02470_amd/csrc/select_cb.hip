@@ -1,0 +1,318 @@
+// Class-balanced selection (Algorithm 1, "if class balance required"; "Agreement Scoring and Selection", CB-SAGE):
+// per class c the unit centroid u_c of the normalised projections of its rows, alpha_i = <zhat_i, u_c(i)>, and the
+// top k_c rows of every class, k_c = floor(keep * N_c + 0.5).
+//
+// Everything that decides the result is integer work, so the outcome does not depend on timing:
+//   * class sums are accumulated in 64-bit fixed point (zhat * 2^40, |zhat| <= 1, up to 2^23 rows per class) with
+//     integer atomics -- addition of integers is associative, unlike floating point;
+//   * the k_c-th largest score of every class comes from one radix select run for all classes at once (a 256-bin
+//     histogram per class and byte, four passes over order-preserving 32-bit keys);
+//   * ties at a class threshold go to the lowest row indices: a second radix select, over the row index, among the
+//     rows that sit exactly on their class threshold;
+//   * the selected rows are compacted in ascending row order (per-block counts, scan, emit).
+#include "sage_internal.h"
+
+namespace sage {
+
+constexpr double CB_SCALE = 1099511627776.0;  // 2^40
+
+__device__ __forceinline__ uint32_t cb_key(float a) {  // larger alpha <-> larger key; -0 and +0 share a key
+    uint32_t b = __float_as_uint(a);
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__global__ __launch_bounds__(256) void cb_zero_kernel(uint32_t* __restrict__ counts, long long* __restrict__ sums,
+                                                      uint32_t* __restrict__ hist, uint32_t* __restrict__ misc, int C) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < C) counts[i] = 0;
+    if (i < (int64_t)C * 128) sums[i] = 0;
+    if (i < (int64_t)C * 256) hist[i] = 0;
+    if (i < 4) misc[i] = 0;  // [0] total kept, [1] a label was out of range
+}
+
+// one wave per row: count the row for its class and add its zhat to the class sum (fixed point)
+__global__ __launch_bounds__(256) void cb_accumulate_kernel(const float* __restrict__ zhat, const int* __restrict__ labels,
+                                                            int64_t N, int k, int C, uint32_t* __restrict__ counts,
+                                                            long long* __restrict__ sums, uint32_t* __restrict__ misc) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int64_t r = (int64_t)blockIdx.x * 4 + wave; r < N; r += (int64_t)gridDim.x * 4) {
+        const int c = labels[r];
+        if (c < 0 || c >= C) {
+            if (lane == 0) misc[1] = 1;
+            continue;
+        }
+        if (lane == 0) atomicAdd(&counts[c], 1u);
+        const float* z = zhat + r * k;
+        unsigned long long* s = reinterpret_cast<unsigned long long*>(sums + (int64_t)c * 128);
+        if (lane < k) atomicAdd(&s[lane], (unsigned long long)__double2ll_rn((double)z[lane] * CB_SCALE));
+        if (lane + 64 < k) atomicAdd(&s[lane + 64], (unsigned long long)__double2ll_rn((double)z[lane + 64] * CB_SCALE));
+    }
+}
+
+// one work-group per class: u_c = S_c / ||S_c|| (0 if S_c = 0), k_c, and the start state of the selects
+__global__ __launch_bounds__(128) void cb_unit_kernel(const long long* __restrict__ sums, const uint32_t* __restrict__ counts,
+                                                      int k, double keep, double* __restrict__ ucls,
+                                                      uint32_t* __restrict__ kc, uint32_t* __restrict__ prefix,
+                                                      uint32_t* __restrict__ remain, uint32_t* __restrict__ misc) {
+    __shared__ double red[128];
+    const int c = blockIdx.x, j = threadIdx.x;
+    const double s = j < k ? (double)sums[(int64_t)c * 128 + j] / CB_SCALE : 0.0;
+    red[j] = s * s;
+    __syncthreads();
+    for (int w = 64; w >= 1; w >>= 1) {  // fixed-shape tree
+        if (j < w) red[j] += red[j + w];
+        __syncthreads();
+    }
+    const double nrm = sqrt(red[0]);
+    ucls[(int64_t)c * 128 + j] = nrm > 0.0 ? s / nrm : 0.0;
+    if (j == 0) {
+        const uint32_t n = counts[c];
+        double x = floor(keep * (double)n + 0.5);
+        uint32_t m = x <= 0.0 ? 0u : (x >= (double)n ? n : (uint32_t)x);
+        kc[c] = m;
+        prefix[c] = 0;
+        remain[c] = m;
+        if (m) atomicAdd(&misc[0], m);
+    }
+}
+
+// alpha_i = clamp(<zhat_i, u_c(i)>, -1, 1), -0 stored as +0; one wave per row
+__global__ __launch_bounds__(256) void cb_cosine_kernel(const float* __restrict__ zhat, const int* __restrict__ labels,
+                                                        int64_t N, int k, int C, const double* __restrict__ ucls,
+                                                        float* __restrict__ alpha) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int64_t r = (int64_t)blockIdx.x * 4 + wave; r < N; r += (int64_t)gridDim.x * 4) {
+        int c = labels[r];
+        if (c < 0 || c >= C) c = 0;  // reported by cb_accumulate_kernel; keep the reads in bounds
+        const float* z = zhat + r * k;
+        const double* u = ucls + (int64_t)c * 128;
+        double a = 0.0;
+        if (lane < k) a = (double)z[lane] * u[lane];
+        if (lane + 64 < k) a += (double)z[lane + 64] * u[lane + 64];
+        for (int o = 32; o >= 1; o >>= 1) a += __shfl_xor(a, o);
+        if (lane == 0) {
+            if (a > 1.0) a = 1.0;
+            if (a < -1.0) a = -1.0;
+            float f = (float)a;
+            if (f == 0.f) f = 0.f;
+            alpha[r] = f;
+        }
+    }
+}
+
+// phase 0: histogram of byte shift/8 of the score keys whose higher bytes equal their class prefix
+// phase 1: the same over the row index, among the rows whose score key equals their class threshold
+__global__ __launch_bounds__(256) void cb_hist_kernel(const float* __restrict__ alpha, const int* __restrict__ labels,
+                                                      int64_t N, int C, int phase, int shift,
+                                                      const uint32_t* __restrict__ kc, const uint32_t* __restrict__ thr,
+                                                      const uint32_t* __restrict__ prefix, uint32_t* __restrict__ hist) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 256) {
+        const int c = labels[i];
+        if (c < 0 || c >= C || kc[c] == 0) continue;
+        uint32_t key = cb_key(alpha[i]);
+        if (phase == 1) {
+            if (key != thr[c]) continue;
+            key = (uint32_t)i;
+        }
+        const bool match = shift == 24 ? true : ((key >> (shift + 8)) == prefix[c]);
+        if (match) atomicAdd(&hist[(int64_t)c * 256 + ((key >> shift) & 255u)], 1u);
+    }
+}
+
+// one thread per class: walk the class's bins (from the top in phase 0: k-th largest score; from the bottom in phase 1:
+// k-th smallest index) until the remaining count is covered, extend the prefix, clear the bins
+__global__ __launch_bounds__(256) void cb_pick_kernel(uint32_t* __restrict__ hist, int C, int phase,
+                                                      const uint32_t* __restrict__ kc, uint32_t* __restrict__ prefix,
+                                                      uint32_t* __restrict__ remain) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    uint32_t* h = hist + (int64_t)c * 256;
+    if (kc[c]) {
+        const uint32_t want = remain[c];
+        uint32_t cum = 0;
+        int chosen = phase == 0 ? 0 : 255;
+        for (int t = 0; t < 256; ++t) {
+            const int b = phase == 0 ? 255 - t : t;
+            const uint32_t n = h[b];
+            if (cum + n >= want) { chosen = b; break; }
+            cum += n;
+        }
+        prefix[c] = (prefix[c] << 8) | (uint32_t)chosen;
+        remain[c] = want - cum;
+    }
+    for (int b = 0; b < 256; ++b) h[b] = 0;
+}
+
+// between the phases: the score prefix is the class threshold; the index select starts with `remain` ties to take
+__global__ __launch_bounds__(256) void cb_phase_kernel(int C, uint32_t* __restrict__ thr, uint32_t* __restrict__ prefix) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    thr[c] = prefix[c];
+    prefix[c] = 0;
+}
+
+// row i is kept when its class keeps anything and its key is above the class threshold, or on it with an index not
+// above the class's index threshold; per block of SELECT_BLOCK rows the number kept
+__global__ __launch_bounds__(256) void cb_count_kernel(const float* __restrict__ alpha, const int* __restrict__ labels,
+                                                       int64_t N, int C, const uint32_t* __restrict__ kc,
+                                                       const uint32_t* __restrict__ thr, const uint32_t* __restrict__ tidx,
+                                                       uint8_t* __restrict__ sel, uint32_t* __restrict__ blk) {
+    __shared__ uint32_t sg[256];
+    const int64_t base = (int64_t)blockIdx.x * SELECT_BLOCK + (int64_t)threadIdx.x * 8;
+    uint32_t g = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int64_t i = base + q;
+        if (i < N) {
+            const int c = labels[i];
+            bool keepit = false;
+            if (c >= 0 && c < C && kc[c]) {
+                const uint32_t key = cb_key(alpha[i]);
+                keepit = key > thr[c] || (key == thr[c] && (uint32_t)i <= tidx[c]);
+            }
+            sel[i] = keepit ? 1 : 0;
+            g += keepit;
+        }
+    }
+    sg[threadIdx.x] = g;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sg[threadIdx.x] += sg[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) blk[blockIdx.x] = sg[0];
+}
+
+// exclusive scan of the per-block counts, in place (single work-group, sequential over chunks of 256 blocks)
+__global__ __launch_bounds__(256) void cb_scan_kernel(uint32_t* __restrict__ blk, int nblk) {
+    __shared__ uint32_t sg[256];
+    uint32_t carry = 0;
+    for (int base = 0; base < nblk; base += 256) {
+        const int i = base + threadIdx.x;
+        const uint32_t g = i < nblk ? blk[i] : 0;
+        sg[threadIdx.x] = g;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {  // Hillis-Steele inclusive scan
+            uint32_t ag = 0;
+            if ((int)threadIdx.x >= o) ag = sg[threadIdx.x - o];
+            __syncthreads();
+            sg[threadIdx.x] += ag;
+            __syncthreads();
+        }
+        if (i < nblk) blk[i] = carry + sg[threadIdx.x] - g;
+        const uint32_t t = sg[255];
+        __syncthreads();
+        carry += t;
+    }
+}
+
+__global__ __launch_bounds__(256) void cb_emit_kernel(const uint8_t* __restrict__ sel, int64_t N,
+                                                      const uint32_t* __restrict__ blk, int64_t* __restrict__ out_idx) {
+    __shared__ uint32_t sg[256];
+    const int64_t base = (int64_t)blockIdx.x * SELECT_BLOCK + (int64_t)threadIdx.x * 8;
+    uint8_t f[8];
+    uint32_t g = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int64_t i = base + q;
+        f[q] = i < N ? sel[i] : 0;
+        g += f[q];
+    }
+    sg[threadIdx.x] = g;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+        uint32_t ag = 0;
+        if ((int)threadIdx.x >= o) ag = sg[threadIdx.x - o];
+        __syncthreads();
+        sg[threadIdx.x] += ag;
+        __syncthreads();
+    }
+    uint32_t slot = blk[blockIdx.x] + sg[threadIdx.x] - g;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        if (f[q]) out_idx[slot++] = base + q;
+}
+
+size_t cb_work_bytes(int C, int64_t N) {
+    const int64_t nblk = (N + SELECT_BLOCK - 1) / SELECT_BLOCK;
+    size_t b = 0;
+    b += (size_t)C * 4 * 6;             // counts, kc, prefix, remain, thr, (spare)
+    b += (size_t)C * 128 * 8 * 2;       // sums, ucls
+    b += (size_t)C * 256 * 4;           // hist
+    b += 64;                            // misc
+    b += (size_t)(nblk > 0 ? nblk : 1) * 4;  // blk
+    b += (size_t)(N > 0 ? N : 1);       // sel
+    return b + 4096;                    // alignment slack
+}
+
+CbWork cb_work_layout(void* base, int C, int64_t N) {
+    CbWork w{};
+    char* p = (char*)base;
+    auto take = [&](size_t bytes) {
+        char* q = p;
+        p += (bytes + 255) / 256 * 256;
+        return q;
+    };
+    w.sums = (long long*)take((size_t)C * 128 * 8);
+    w.ucls = (double*)take((size_t)C * 128 * 8);
+    w.counts = (uint32_t*)take((size_t)C * 4);
+    w.kc = (uint32_t*)take((size_t)C * 4);
+    w.prefix = (uint32_t*)take((size_t)C * 4);
+    w.remain = (uint32_t*)take((size_t)C * 4);
+    w.thr = (uint32_t*)take((size_t)C * 4);
+    w.hist = (uint32_t*)take((size_t)C * 256 * 4);
+    w.misc = (uint32_t*)take(64);
+    const int64_t nblk = (N + SELECT_BLOCK - 1) / SELECT_BLOCK;
+    w.blk = (uint32_t*)take((size_t)(nblk > 0 ? nblk : 1) * 4);
+    w.sel = (uint8_t*)take((size_t)(N > 0 ? N : 1));
+    return w;
+}
+
+// Stage 1: class counts, sums, centroids, k_c, scores. Afterwards misc[0] = total kept, misc[1] = bad label seen.
+hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int k, int C, double keep, float* alpha,
+                            const CbWork& w, hipStream_t st) {
+    const int64_t zi = (int64_t)C * 256;
+    hipLaunchKernelGGL(cb_zero_kernel, dim3((unsigned)((zi + 255) / 256)), dim3(256), 0, st, w.counts, w.sums, w.hist,
+                       w.misc, C);
+    if (N > 0) {
+        int64_t blocks = (N + 3) / 4;
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(cb_accumulate_kernel, dim3((unsigned)blocks), dim3(256), 0, st, zhat, labels, N, k, C, w.counts,
+                           w.sums, w.misc);
+    }
+    hipLaunchKernelGGL(cb_unit_kernel, dim3(C), dim3(128), 0, st, w.sums, w.counts, k, keep, w.ucls, w.kc, w.prefix,
+                       w.remain, w.misc);
+    if (N > 0) {
+        int64_t blocks = (N + 3) / 4;
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(cb_cosine_kernel, dim3((unsigned)blocks), dim3(256), 0, st, zhat, labels, N, k, C, w.ucls, alpha);
+    }
+    return hipGetLastError();
+}
+
+// Stage 2: thresholds per class, flags, compaction. out_idx receives misc[0] indices, ascending.
+hipError_t launch_cb_select(const float* alpha, const int* labels, int64_t N, int C, int64_t* out_idx, const CbWork& w,
+                            hipStream_t st) {
+    if (N <= 0) return hipSuccess;
+    int64_t hb = (N + 255) / 256;
+    if (hb > 2048) hb = 2048;
+    const unsigned cb = (unsigned)((C + 255) / 256);
+    for (int phase = 0; phase < 2; ++phase) {
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            hipLaunchKernelGGL(cb_hist_kernel, dim3((unsigned)hb), dim3(256), 0, st, alpha, labels, N, C, phase, shift, w.kc,
+                               w.thr, w.prefix, w.hist);
+            hipLaunchKernelGGL(cb_pick_kernel, dim3(cb), dim3(256), 0, st, w.hist, C, phase, w.kc, w.prefix, w.remain);
+        }
+        if (phase == 0) hipLaunchKernelGGL(cb_phase_kernel, dim3(cb), dim3(256), 0, st, C, w.thr, w.prefix);
+    }
+    const int64_t nblk = (N + SELECT_BLOCK - 1) / SELECT_BLOCK;
+    // after phase 1 `prefix` is the index threshold of every class
+    hipLaunchKernelGGL(cb_count_kernel, dim3((unsigned)nblk), dim3(256), 0, st, alpha, labels, N, C, w.kc, w.thr, w.prefix,
+                       w.sel, w.blk);
+    hipLaunchKernelGGL(cb_scan_kernel, dim3(1), dim3(256), 0, st, w.blk, (int)nblk);
+    hipLaunchKernelGGL(cb_emit_kernel, dim3((unsigned)nblk), dim3(256), 0, st, w.sel, N, w.blk, out_idx);
+    return hipGetLastError();
+}
+
+}  // namespace sage

@@ -225,6 +225,34 @@ def test_end_to_end_config1():
     assert np.abs(Vg.T @ Vg - o.V.T @ o.V).max() <= 1e-4  # same span
 
 
+def test_end_to_end_config1_sketch_weighted_projection():
+    """The paper's own projection z = S g (rows of the sketch a shrink would write) end to end on config 1."""
+    w = inputs.WORKLOADS[1]
+    G = inputs.generate_numpy(w)
+    o = Oracle(w.ell, w.D, 0)
+    for lo in range(0, w.N, w.batch):
+        o.update(G[lo:lo + w.batch])
+    o.basis(w.k, weighted=True)
+    for lo in range(0, w.N, w.batch):
+        o.score(G[lo:lo + w.batch])
+    oidx = o.select(w.keep)
+    B = _binding()
+    s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    Gd = to_dev(G, torch)
+    for lo in range(0, w.N, w.batch):
+        s.fd_update(Gd[lo:lo + w.batch])
+    s.fd_basis(w.k, weighted=True)
+    for lo in range(0, w.N, w.batch):
+        s.score(Gd[lo:lo + w.batch])
+    gidx = s.select(w.keep)
+    al = s.scores().cpu().numpy()
+    assert np.abs(al - o.alpha).max() <= SCORE_TOL
+    _check_selection(gidx.cpu().numpy(), oidx, o.alpha)
+    Sg = s.basis().cpu().numpy().astype(np.float64)
+    So = o.V
+    assert np.abs(Sg.T @ Sg - So.T @ So).max() <= 1e-4 * np.abs(So.T @ So).max()
+
+
 def test_end_to_end_reports_conditioning():
     """Slow power-law spectra make span(V_k) ill-conditioned; scores then agree only as far as the two sketches'
     top-k subspaces do. The check: the score gap is explained by the principal angle between the two bases."""
@@ -350,3 +378,73 @@ def test_score_store_grows():
     assert s.stats().n_scored == 80_000 and idx.numel() == 800
     al = s.scores()
     assert torch.equal(al[:40_000], al[40_000:])
+
+
+# ------------------------------------------------------------------------------------------ class-balanced variant
+@pytest.mark.parametrize("name,Cn", [("cfg1", 10), ("cfg2_small", 100), ("cfg5_small_bf16", 7), ("cfg5_k20_bf16_aligned", 1)])
+def test_class_balanced_selection_matches_oracle(name, Cn):
+    """CB-SAGE with the oracle's basis injected: class-wise scores to 1e-4, the selection exactly the class-wise top
+    k_c of the GPU's own scores, and equal to the oracle's outside a 1e-4 band round each class threshold."""
+    B = _binding()
+    w, G, o, _ = _oracle_run(name)
+    V = o.V.astype(np.float32)
+    rng = np.random.default_rng(len(name) + Cn)
+    labels = rng.integers(0, max(1, Cn - 1) if Cn > 2 else Cn, size=w.N).astype(np.int32)   # last class empty when Cn > 2
+    s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    s.set_basis(torch.from_numpy(V).cuda())
+    o2 = Oracle(w.ell, w.D, 1)
+    o2.set_basis(V.astype(np.float64))
+    Gd = to_dev(G, torch)
+    Ld = torch.from_numpy(labels).cuda()
+    for lo in range(0, w.N, w.batch):
+        s.score_labeled(Gd[lo:lo + w.batch], Ld[lo:lo + w.batch])
+        o2.score(G[lo:lo + w.batch])
+    gidx = s.select_cb(w.keep, Cn).cpu().numpy()
+    al = s.scores().cpu().numpy()
+    oal, oidx = o2.select_cb(w.keep, labels, Cn)
+    assert np.abs(al - oal).max() <= SCORE_TOL
+    assert gidx.tolist() == oracle.cb_select_from_alpha(al, labels, Cn, w.keep).tolist()
+    gi, oi = set(gidx.tolist()), set(oidx.tolist())
+    assert len(gi) == len(oi)
+    for c in range(Cn):
+        oc = [i for i in oi if labels[i] == c]
+        if not oc:
+            continue
+        tau = min(float(oal[i]) for i in oc)
+        for i in (gi ^ oi):
+            if labels[i] == c:
+                assert abs(float(oal[i]) - tau) <= SCORE_TOL
+    # the plain selection is still available on the same pass
+    pidx = s.select(w.keep).cpu().numpy()
+    assert pidx.tolist() == oracle.topm_f32(s.scores().cpu().numpy(), len(pidx)).tolist()
+
+
+def test_class_balanced_ties_empty_classes_and_errors():
+    B = _binding()
+    D, k, N, Cn = 64, 4, 600, 6
+    rng = np.random.default_rng(3)
+    V = np.ascontiguousarray(np.linalg.qr(rng.standard_normal((D, k)))[0].T.astype(np.float32))
+    G = rng.standard_normal((N, D)).astype(np.float32)
+    G[100:200] = G[100]          # 100 identical rows: equal scores inside their classes
+    G[300:320] = 0.0             # zero rows: zhat = 0, alpha = 0
+    labels = (np.arange(N) % 4).astype(np.int32)     # classes 4 and 5 stay empty
+    s = B.Sage(8, D)
+    s.set_basis(torch.from_numpy(V).cuda())
+    s.score_labeled(torch.from_numpy(G).cuda(), torch.from_numpy(labels).cuda())
+    for keep in (0.0, 0.13, 0.5, 1.0):
+        idx = s.select_cb(keep, Cn).cpu().numpy()
+        al = s.scores().cpu().numpy()
+        assert idx.tolist() == oracle.cb_select_from_alpha(al, labels, Cn, keep).tolist()
+        o = Oracle(8, D, 1)
+        o.set_basis(V.astype(np.float64))
+        o.score(G)
+        oal, _ = o.select_cb(keep, labels, Cn)
+        assert np.abs(al - oal).max() <= SCORE_TOL
+    # a label outside [0, n_classes) is refused; unlabeled rows in the pass are a state error
+    with pytest.raises(B.SageError) as e:
+        s.select_cb(0.5, 3)
+    assert e.value.code == B.SAGE_ERR_ARG
+    s.score(torch.from_numpy(G[:10]).cuda())
+    with pytest.raises(B.SageError) as e:
+        s.select_cb(0.5, Cn)
+    assert e.value.code == B.SAGE_ERR_STATE

@@ -369,3 +369,89 @@ def test_bf16_rows_are_widened_exactly():
     o1.score(h)
     o2.score(back)
     assert np.array_equal(o1.zhat, o2.zhat)
+
+
+# ---------------------------------------------------------------- sketch-weighted basis (the paper's z = S g)
+@pytest.mark.parametrize("mode", [0, 1])
+def test_weighted_basis_is_the_sketch_a_shrink_would_write(mode):
+    """Method, "Two-pass scoring": z = S g with S = Sigma' V^T. Pins: (1) against LAPACK, the rows are
+    sqrt(sigma_j^2 - sigma_ell^2) v_j^T of the buffer as it stands; (2) taken right after a shrink they are the
+    sketch rows themselves; (3) scores are then the plain definition on S g."""
+    rng = np.random.default_rng(11 + mode)
+    ell, D, k = 8, 40, 5
+    A = lowrank_rows(rng, 3 * ell + 5, D, 12, noise=0.05)   # buffer ends partly filled
+    o = Oracle(ell, D, mode)
+    o.update(A)
+    Bbuf = o.B.copy()
+    o.basis(k, weighted=True)
+    S = o.V
+    U, sv, Vt = np.linalg.svd(Bbuf, full_matrices=False)
+    delta = sv[ell - 1] ** 2
+    wgt = np.sqrt(np.maximum(sv[:k] ** 2 - delta, 0.0))
+    want = (wgt[:, None] * Vt[:k])
+    assert np.abs(S.T @ S - want.T @ want).max() <= 1e-10 * sv[0] ** 2          # sign-free comparison
+    assert np.abs(np.abs(np.sum(S * want, axis=1)) - wgt ** 2).max() <= 1e-10 * sv[0] ** 2
+    assert np.array_equal(o.B, Bbuf)                                             # the sketch is untouched
+    # (3) scores from the plain definition on S g
+    o.score(A)
+    idx = o.select(0.25)
+    Z = A.astype(np.float64) @ S.T
+    Zh = Z / np.linalg.norm(Z, axis=1, keepdims=True)
+    u = Zh.sum(0) / np.linalg.norm(Zh.sum(0))
+    al = np.clip(Zh @ u, -1, 1)
+    assert np.abs(o.alpha - al).max() <= 1e-12
+    assert idx.tolist() == sorted(np.lexsort((np.arange(len(al)), -al))[: len(idx)].tolist())
+    # (2) right after a shrink (exactly 2*ell + m*ell rows) the weighted basis is the sketch
+    o2 = Oracle(ell, D, mode)
+    o2.update(A[: 3 * ell])
+    assert o2.fill == ell
+    Bs = o2.B.copy()
+    o2.basis(k, weighted=True)
+    S2 = o2.V
+    for j in range(k):
+        sgn = np.sign(np.dot(S2[j], Bs[j])) or 1.0
+        assert np.abs(S2[j] - sgn * Bs[j]).max() <= 1e-9 * np.abs(Bs).max()
+
+
+# ---------------------------------------------------------------- class-balanced selection (CB-SAGE)
+def test_cb_selection_matches_per_class_plain_selection():
+    """Algorithm 1, "if class balance required". Pins: (1) with one class it is the plain selection; (2) class by class
+    it equals the plain (already pinned) scoring + selection run on that class's rows alone with the same basis;
+    (3) k_c = floor(keep*N_c + 0.5) rows per class exactly; (4) renaming the classes changes nothing."""
+    rng = np.random.default_rng(77)
+    ell, D, k, N, Cn = 8, 30, 4, 90, 5
+    A = lowrank_rows(rng, N, D, 6, noise=0.1)
+    A[17] = A[3]                     # ties inside a class
+    A[40] = 0.0                      # a zero row
+    labels = rng.integers(0, Cn - 1, size=N)    # class Cn-1 stays empty
+    labels[17] = labels[3]
+    o = Oracle(ell, D, 1)
+    o.update(A)
+    o.basis(k)
+    V = o.V.copy()
+    o.score(A)
+    plain_idx = o.select(0.3)
+    plain_alpha = o.alpha.copy()
+    # (1) one class
+    al1, idx1 = o.select_cb(0.3, np.zeros(N, dtype=np.int64), 1)
+    assert np.abs(al1 - plain_alpha).max() <= 1e-12 and idx1.tolist() == plain_idx.tolist()
+    # (2), (3) class by class through the plain path
+    al, idx = o.select_cb(0.3, labels, Cn)
+    got = set(idx.tolist())
+    for c in range(Cn):
+        rows = np.nonzero(labels == c)[0]
+        if rows.size == 0:
+            continue
+        oc = Oracle(ell, D, 1)
+        oc.set_basis(V)
+        oc.score(A[rows])
+        sub = oc.select(0.3)
+        assert np.abs(oc.alpha - al[rows]).max() <= 1e-12
+        assert sorted(rows[sub].tolist()) == sorted(i for i in got if labels[i] == c)
+        assert len(sub) == oracle.keep_count(0.3, rows.size)
+    assert idx.tolist() == sorted(idx.tolist())
+    assert (al <= 1).all() and (al >= -1).all()
+    # (4) renaming classes
+    perm = rng.permutation(Cn)
+    al2, idx2 = o.select_cb(0.3, perm[labels], Cn)
+    assert np.array_equal(al2, al) and idx2.tolist() == idx.tolist()
