@@ -111,9 +111,15 @@ def main():
 
     note("inputs resident")
 
+    # class labels for the class-balanced variant (CB-SAGE): the workload's class count where it is a last-layer shape
+    n_classes = {2: 10, 3: 100, 5: 1000}.get(args.workload, 10)
+    gl = torch.Generator(device="cuda")
+    gl.manual_seed(99)
+    labels = [torch.randint(0, n_classes, (b.shape[0],), generator=gl, device="cuda", dtype=torch.int32) for b in batches]
+
     def run_pass(s, timed):
         """W warm-up steps then K steps of the whole path; returns the event times of the K steps (ms)."""
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
         for b in range(W):
             s.fd_update(batches[b])
         s.fd_basis(k)
@@ -130,19 +136,23 @@ def main():
         s.fd_basis(k)
         ev[2].record()
         for b in range(W, W + K):
-            s.score(batches[b])
+            s.score_labeled(batches[b], labels[b])      # sage_score plus a 4-byte label per row
         ev[3].record()
         idx = s.select(w.keep)
         ev[4].record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        ev[5].record()
+        idx_cb = s.select_cb(w.keep, n_classes)         # the class-balanced selection of the same pass (not in `value`)
+        ev[6].record()
+        torch.cuda.synchronize()
         note("timed steps done")
-        ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(4)]
-        return ms, wall, idx
+        ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(4)] + [ev[5].elapsed_time(ev[6])]
+        return ms, wall, (idx, idx_cb)
 
     # ---- timed: exactly K steps (the events are recorded on the stream the library launches on)
     s = Sage(ell, D, dtype=w.dtype, max_rows=(W + K) * w.batch)
-    (ms_update, ms_basis, ms_score, ms_select), wall, idx = run_pass(s, True)
+    (ms_update, ms_basis, ms_score, ms_select, ms_select_cb), wall, (idx, idx_cb) = run_pass(s, True)
     total_ms = ms_update + ms_basis + ms_score + ms_select
     rows = K * w.batch
     value = rows / (total_ms * 1e-3)
@@ -232,6 +242,8 @@ def main():
         "score_frac_hbm_peak": sc_rows_s * score_bytes_row / PEAK_HBM,
         "score_with_basis_and_select_rows_per_s": sc_all_rows_s,
         "ms": {"update": ms_update, "basis": ms_basis, "score": ms_score, "select": ms_select, "wall": wall * 1e3},
+        "cb_sage": {"classes": n_classes, "select_cb_ms": ms_select_cb, "selected": int(idx_cb.numel()),
+                    "note": "class-balanced selection of the same scored pass; not part of value"},
         "selected": int(idx.numel()), "jacobi_sweeps_last": st.last_sweeps, "n_shrinks": int(st.n_shrinks),
         "roofline": roof, "kernels": kern,
     }
