@@ -46,43 +46,33 @@ __device__ __forceinline__ void atomic_max_pos_double(double* addr, double v) {
 
 // Rotation [[c, s], [-s, c]] that annihilates a_pq of the symmetric 2x2 [[app, apq], [apq, aqq]] (the one of
 // smaller angle): t = sign(a) apq / (|a| + sqrt(a^2 + apq^2)), a = (aqq - app)/2, c = 1/sqrt(1 + t^2), s = c t.
-__device__ __forceinline__ void rot_params(double app, double aqq, double apq, double& c, double& s) {
-    c = 1.0;
-    s = 0.0;
-    if (apq == 0.0) return;
-    double a = 0.5 * (aqq - app);
-    double den = fabs(a) + sqrt(a * a + apq * apq);
-    if (!(den > 0.0)) return;
-    double t = apq / den;
-    if (a < 0.0) t = -t;
-    c = 1.0 / sqrt(1.0 + t * t);
-    s = c * t;
-}
-
-// Same rotation from the hardware reciprocal / reciprocal-square-root approximations, each polished by two Newton
-// steps (the serial chain of a round starts here, so the IEEE division and square root are avoided). Also returns
-// t = s/c, which gives the rotated diagonal in closed form: a_pp - t a_pq and a_qq + t a_pq.
-__device__ __forceinline__ double rsqrt_newton(double x) {
-    double y = __builtin_amdgcn_rsq(x);
+// The angle is taken in single precision and the normalisation in double precision. The pivot solve only has to
+// produce an orthogonal Q that makes the pivot block nearly diagonal: the matrix itself is updated from Q in fp64 by
+// jac_apply_kernel, so an angle that is good to ~2^-22 leaves a pivot element that is ~1e-7 of what it was (instead
+// of 0), which the next sweep removes; c^2 + s^2 = 1 holds to fp64 rounding because c = 1/sqrt(1 + t^2) is polished
+// by two Newton steps in fp64 and s = c t. The inputs are first scaled by 2^-e with 2^e >= trace(C) >= every |c_pq|,
+// so they fit single precision; what underflows there is below 1e-19 trace and no longer matters (such a rotation
+// is still orthogonal, it just need not annihilate anything). Branch-free, so that the scheduler can fill the waits
+// of this serial chain with other work of the same wave. t is returned for the closed forms a_pp - t a_pq and
+// a_qq + t a_pq.
+__device__ __forceinline__ void rot_params_mixed(double app, double aqq, double apq, int e, double& c, double& s,
+                                                 double& t) {
+    const double a = 0.5 * (aqq - app);
+    const float af = (float)__builtin_amdgcn_ldexp(a, -e), pf = (float)__builtin_amdgcn_ldexp(apq, -e);
+    const float den = fabsf(af) + __builtin_amdgcn_sqrtf(af * af + pf * pf) + 1e-30f;
+    float tf = pf * __builtin_amdgcn_rcpf(den);  // pf = 0 (nothing to rotate, or negligible): the identity
+    if (a < 0.0) tf = -tf;
+    t = (double)tf;
+    const double x = __builtin_fma(t, t, 1.0);
+    double y = (double)__builtin_amdgcn_rsqf((float)x);
     y = y * (1.5 - 0.5 * x * y * y);
     y = y * (1.5 - 0.5 * x * y * y);
-    return y;
+    c = y;
+    s = y * t;
 }
-__device__ __forceinline__ void rot_params_fast(double app, double aqq, double apq, double& c, double& s, double& t) {
-    c = 1.0;
-    s = 0.0;
-    t = 0.0;
-    double a = 0.5 * (aqq - app);
-    double h = a * a + apq * apq;
-    if (apq == 0.0 || !(h > 1e-280) || !(h < 1e280)) return;  // nothing to rotate, or outside the safe range
-    double den = fabs(a) + h * rsqrt_newton(h);
-    double inv = __builtin_amdgcn_rcp(den);
-    inv = inv * (2.0 - den * inv);
-    inv = inv * (2.0 - den * inv);
-    t = apq * inv;
-    if (a < 0.0) t = -t;
-    c = rsqrt_newton(1.0 + t * t);
-    s = c * t;
+// exponent for rot_params_mixed from trace(C) = stat[0]
+__device__ __forceinline__ int scale_exponent(double trace) {
+    return (trace > 1e-280 && trace < 1e280) ? __builtin_amdgcn_frexp_exp(trace) : 0;
 }
 
 // Y = I, diag0 = diag(C), stat[0] = trace(C), stat[1..] = 0. grid = NP blocks of 256.
@@ -163,6 +153,7 @@ __global__ __launch_bounds__(256) void jac_diag_kernel(const double* __restrict_
     double* cs = Qm + 64 * LDA;  // 32 x 2
     const int tid = threadIdx.x;
     const int I = 2 * blockIdx.x, J = 2 * blockIdx.x + 1;
+    const int sexp = scale_exponent(stat[0]);
     load_pivot(C, NP, I, J, A, tid);
     for (int e = tid; e < 64 * 64; e += 256) Qm[(e >> 6) * LDA + (e & 63)] = ((e >> 6) == (e & 63)) ? 1.0 : 0.0;
     __syncthreads();
@@ -172,8 +163,8 @@ __global__ __launch_bounds__(256) void jac_diag_kernel(const double* __restrict_
             int p, q;
             rr_pair(32, t, tid & 15, p, q);
             if (tid >= 16) { p += 32; q += 32; }
-            double c, s;
-            rot_params(A[p * LDA + p], A[q * LDA + q], A[p * LDA + q], c, s);
+            double c, s, t;
+            rot_params_mixed(A[p * LDA + p], A[q * LDA + q], A[p * LDA + q], sexp, c, s, t);
             cs[2 * tid] = c;
             cs[2 * tid + 1] = s;
         }
@@ -217,107 +208,200 @@ __global__ __launch_bounds__(256) void jac_diag_kernel(const double* __restrict_
     for (int e = tid; e < 4096; e += 256) Qo[e] = Qm[(e >> 6) * LDA + (e & 63)];
 }
 
-// Steps 1..nb-1: work-group w holds blocks (I, J) as one 64x64 matrix and annihilates every pair (p in I, q in J) in
-// 32 rounds of 32 disjoint rotations. Index i = 4a + l of the first half (a < 8, l < 4) meets, in round
-// (sigma, tau), index 4((a + tau) % 8) + (l + sigma) % 4 of the second half: a Latin square, so every pair is met
-// once. A lives in LDS. Q lives in registers: a quad of lanes owns one row of Q, lane l of the quad holding the
-// first-half columns {4a + l} and the second-half columns {32 + 4a' + (l + sigma) % 4}; with this schedule a round
-// only rotates register pairs of one lane (static indices), and a change of sigma is a one-lane shift in the quad.
-__global__ __launch_bounds__(256) void jac_cross_kernel(const double* __restrict__ C, double* __restrict__ Qout,
+// Steps 1..nb-1: work-group w holds blocks (I, J) as one 64x64 matrix A (LDS, upper triangle kept current) and
+// annihilates every pair (p in I, q in J) in 32 rounds of 32 disjoint rotations. Rotation iota = 16 b + x keeps
+// p = iota and meets, in round r = 16 beta + rho, q = 32 + 16 (b ^ beta) + (x + rho) % 16: a Latin square, so every
+// pair is met once.
+//
+// A round updates, for every two rotations i < j, the 2x2 block rows {p_i, q_i} x columns {p_j, q_j}: 496 blocks,
+// one per thread of the 512. The block of rotations (iota, iota') with iota' = 16 b + (x + 1) % 16 holds the
+// element (p_iota, q_iota') that rotation iota annihilates in the next round, so the thread that has just updated it
+// goes on to compute the next rotation (the diagonal after this round's rotation is known in closed form) and
+// publishes it for the next round: one barrier per round. Those 32 blocks, and the 32 that play this part at the
+// change of beta, belong to wave 0, which has nothing else to do: the round's serial chain is one LDS round trip,
+// a block update and a rotation. The other 432 blocks are dealt in row-major order to waves 1..7, so that
+// consecutive lanes hold one i and consecutive j: their LDS accesses are rows or columns of A with distinct banks
+// (LDA is odd), and (c_i, s_i) is a broadcast.
+//
+// Q lives in registers: a thread owns 4 rows of column p_iota and of the column q that iota currently meets. A round
+// rotates those 4 register pairs with one (c, s); then the q columns move one lane down inside their 16 lanes (a
+// DPP row rotation), plus a swap of the two 16-lane halves at the change of beta.
+constexpr int cross_q(int iota, int r) { return 32 + ((((iota >> 4) ^ (r >> 4)) & 1) << 4) + ((iota + r) & 15); }
+
+struct CrossTable {
+    unsigned short e[512];  // [thread]: i | j << 5 | kind << 10 | valid << 12
+};
+// kind 1: the block's element (p_i, q_j) is the next pivot of rotation i; kind 2: (p_j, q_i) is that of rotation j
+constexpr CrossTable make_cross_table() {
+    CrossTable t{};
+    bool special[32][32] = {};
+    for (int half = 0; half < 2; ++half)  // half 0: ordinary rounds; half 1: the round before beta changes
+        for (int iota = 0; iota < 32; ++iota) {
+            const int b = iota >> 4, x = iota & 15;
+            const int other = ((half ? b ^ 1 : b) << 4) + ((x + 1) & 15);
+            const int i = iota < other ? iota : other, j = iota < other ? other : iota;
+            const int kind = iota < other ? 1 : 2;
+            t.e[32 * half + iota] = (unsigned short)(i | j << 5 | kind << 10 | 1 << 12);
+            special[i][j] = true;
+        }
+    int k = 64;
+    for (int i = 0; i < 32; ++i)
+        for (int j = i + 1; j < 32; ++j)
+            if (!special[i][j]) t.e[k++] = (unsigned short)(i | j << 5 | 1 << 12);
+    return t;  // k == 496: the last 16 threads have no block
+}
+__device__ const CrossTable cross_table = make_cross_table();
+
+__device__ __forceinline__ double dpp_row_ror15(double v) {  // lane l of a 16-lane row receives lane (l + 1) % 16
+    const long long u = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_mov_dpp((int)u, 0x12F, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_mov_dpp((int)(u >> 32), 0x12F, 0xF, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+__global__ __launch_bounds__(512) void jac_cross_kernel(const double* __restrict__ C, double* __restrict__ Qout,
                                                         double* __restrict__ stat, int NP, int sweep, int st,
                                                         double tol) {
-    if (sweep_done(stat, sweep, tol)) return;
     __shared__ double A[64 * LDA];
-    __shared__ double cs[2][64];
+    __shared__ __attribute__((aligned(16))) double cs[2][64];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nb = NP / 32;
     int I, J;
     block_pair(nb, st, blockIdx.x, I, J);
-    load_pivot(C, NP, I, J, A, tid);
-
-    const int qrow = wave * 16 + (lane >> 2), lq = lane & 3;
-    double qa[8], qb[8];
+    // the pivot block is requested before the convergence record is looked at: one memory round trip, not two
+    double v[8];
 #pragma unroll
-    for (int a = 0; a < 8; ++a) {
-        qa[a] = (qrow == 4 * a + lq) ? 1.0 : 0.0;
-        qb[a] = (qrow == 32 + 4 * a + lq) ? 1.0 : 0.0;
+    for (int u = 0; u < 8; ++u) {
+        const int e = u * 512 + tid;
+        const int r = e >> 6, c = e & 63;
+        const int gr = (r < 32 ? I * 32 + r : J * 32 + r - 32);
+        const int gc = (c < 32 ? I * 32 + c : J * 32 + c - 32);
+        v[u] = C[(int64_t)gr * NP + gc];
+    }
+    const unsigned ent = cross_table.e[tid];
+    const double trace = stat[0];
+    if (sweep_done(stat, sweep, tol)) return;
+    const int sexp = scale_exponent(trace);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int e = u * 512 + tid;
+        A[(e >> 6) * LDA + (e & 63)] = v[u];
+    }
+    const int i = ent & 31, j = (ent >> 5) & 31, kind = (ent >> 10) & 3;
+    const bool valid = ((ent >> 12) & 1) != 0;
+
+    const int iota = tid & 31, row0 = 4 * (tid >> 5);
+    double qp[4], qq[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        qp[k] = (row0 + k == iota) ? 1.0 : 0.0;
+        qq[k] = (row0 + k == 32 + iota) ? 1.0 : 0.0;
     }
     __syncthreads();
-
-    // the 496 pair-of-pairs (i < j) a round has to update are split statically: thread -> e = tid and e = 256 + tid
-    int bi[2], bj[2];
-    const bool second = (256 + tid) < 496;  // 16 threads have no second block
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        int e = u * 256 + tid, i = 0;
-        if (e >= 496) e = 0;
-        while (e >= 31 - i) { e -= 31 - i; ++i; }
-        bi[u] = i;
-        bj[u] = i + 1 + e;
+    if (tid < 32) {  // rotations of round 0: p = tid meets q = 32 + tid
+        const int p = tid, q = 32 + tid;
+        const double app = A[p * LDA + p], aqq = A[q * LDA + q], apq = A[p * LDA + q];
+        double c, s, t;
+        rot_params_mixed(app, aqq, apq, sexp, c, s, t);
+        cs[0][2 * tid] = c;
+        cs[0][2 * tid + 1] = s;
+        if (s != 0.0) {
+            A[p * LDA + p] = app - t * apq;
+            A[q * LDA + q] = aqq + t * apq;
+            A[p * LDA + q] = 0.0;
+        }
     }
+    // LDS offsets of this thread's block in round r; they are worked out before the barrier that opens the round
+    const int o00 = i * LDA + j;
+    int o01, o10, o11, od0, od1;
+    auto offsets = [&](int r) {
+        const int qi = cross_q(i, r), qj = cross_q(j, r);
+        o01 = i * LDA + qj;
+        o10 = j * LDA + qi;
+        o11 = qi < qj ? qi * LDA + qj : qj * LDA + qi;
+        const int rot = kind == 1 ? i : j, qn = kind == 1 ? qj : qi;  // wave 0: next round's rotation rot meets qn
+        od0 = rot * (LDA + 1);
+        od1 = qn * (LDA + 1);
+    };
+    offsets(0);
+    const int csn = 2 * (kind == 1 ? i : j);
+    __syncthreads();
 
-    for (int sigma = 0; sigma < 4; ++sigma) {
+    // Q <- Q R for this thread's column pair, then the q columns move on to the rotation that meets them next
+    auto q_update = [&](int r, double qc, double qs) {
 #pragma unroll
-        for (int tau = 0; tau < 8; ++tau) {
-            const int par = tau & 1;
-            if (tid < 32) {
-                // rotation of pair `tid`; its own 2x2 block has a closed form and nobody else touches it
-                int p = tid;
-                int q = 32 + ((((tid >> 2) + tau) & 7) << 2) + (((tid & 3) + sigma) & 3);
-                double app = A[p * LDA + p], aqq = A[q * LDA + q], apq = A[p * LDA + q];
-                double c, s, t;
-                rot_params_fast(app, aqq, apq, c, s, t);
-                cs[par][2 * tid] = c;
-                cs[par][2 * tid + 1] = s;
+        for (int k = 0; k < 4; ++k) {
+            const double x = qp[k], y = qq[k];
+            qp[k] = qc * x - qs * y;
+            qq[k] = qs * x + qc * y;
+        }
+        if (r < 31) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) qq[k] = dpp_row_ror15(qq[k]);
+            if (r == 15) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) qq[k] = __shfl_xor(qq[k], 16);
+            }
+        }
+    };
+
+    for (int r = 0; r < 32; ++r) {
+        const int par = r & 1;
+        if (wave == 0) {
+            // the serial chain of the round: block update, then next round's rotation from the fresh pivot
+            const double ci = cs[par][2 * i], si = cs[par][2 * i + 1], cj = cs[par][2 * j], sj = cs[par][2 * j + 1];
+            const double x00 = A[o00], x01 = A[o01], x10 = A[o10], x11 = A[o11];
+            const double app = A[od0], aqq = A[od1];
+            const double qc = cs[par][2 * iota], qs = cs[par][2 * iota + 1];
+            const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
+            const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
+            double z01 = sj * y00 + cj * y01, z10 = cj * y10 - sj * y11;
+            const double z00 = cj * y00 - sj * y01, z11 = sj * y10 + cj * y11;
+            const bool act = r != 31 && ((r == 15) == (lane >= 32));  // lanes 0..31: ordinary rounds; 32..63: beta changes
+            const double apq = kind == 1 ? z01 : z10;
+            double c, s, t;
+            rot_params_mixed(app, aqq, apq, sexp, c, s, t);
+            if (act) {
+                cs[par ^ 1][csn] = c;
+                cs[par ^ 1][csn + 1] = s;
                 if (s != 0.0) {
-                    A[p * LDA + p] = app - t * apq;
-                    A[q * LDA + q] = aqq + t * apq;
-                    A[p * LDA + q] = 0.0;
-                    A[q * LDA + p] = 0.0;
+                    A[od0] = app - t * apq;
+                    A[od1] = aqq + t * apq;
+                    if (kind == 1) z01 = 0.0;
+                    else z10 = 0.0;
                 }
             }
-            __syncthreads();
-            // 2x2 blocks of A for pairs i < j: X <- R_i^T X R_j, written to (i, j) and mirrored to (j, i)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                if (u == 1 && !second) continue;
-                const int i = bi[u], j = bj[u];
-                int pi = i, qi = 32 + ((((i >> 2) + tau) & 7) << 2) + (((i & 3) + sigma) & 3);
-                int pj = j, qj = 32 + ((((j >> 2) + tau) & 7) << 2) + (((j & 3) + sigma) & 3);
-                double ci = cs[par][2 * i], si = cs[par][2 * i + 1], cj = cs[par][2 * j], sj = cs[par][2 * j + 1];
-                // only the upper triangle is kept current: (qi, pj) lives at (pj, qi), (qi, qj) at (min, max)
-                const int o00 = pi * LDA + pj, o01 = pi * LDA + qj, o10 = pj * LDA + qi;
-                const int o11 = qi < qj ? qi * LDA + qj : qj * LDA + qi;
-                double x00 = A[o00], x01 = A[o01], x10 = A[o10], x11 = A[o11];
-                double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
-                double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
+            A[o00] = z00;
+            A[o01] = z01;
+            A[o10] = z10;
+            A[o11] = z11;
+            q_update(r, qc, qs);
+        } else {
+            // the other waves have time to spare: their Q work goes first, which keeps their LDS traffic out of the
+            // way of wave 0's reads right after the barrier
+            const double qc = cs[par][2 * iota], qs = cs[par][2 * iota + 1];
+            q_update(r, qc, qs);
+            __builtin_amdgcn_sched_barrier(0);
+            const double ci = cs[par][2 * i], si = cs[par][2 * i + 1], cj = cs[par][2 * j], sj = cs[par][2 * j + 1];
+            const double x00 = A[o00], x01 = A[o01], x10 = A[o10], x11 = A[o11];
+            const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
+            const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
+            if (valid) {
                 A[o00] = cj * y00 - sj * y01;
                 A[o01] = sj * y00 + cj * y01;
                 A[o10] = cj * y10 - sj * y11;
                 A[o11] = sj * y10 + cj * y11;
             }
-            // Q <- Q R: register pairs (qa[a], qb[(a + tau) % 8]) of pair index i = 4a + lq
-#pragma unroll
-            for (int a = 0; a < 8; ++a) {
-                const int i = 4 * a + lq;
-                double c = cs[par][2 * i], s = cs[par][2 * i + 1];
-                double x = qa[a], y = qb[(a + tau) & 7];
-                qa[a] = c * x - s * y;
-                qb[(a + tau) & 7] = s * x + c * y;
-            }
-            __syncthreads();
         }
-        if (sigma < 3) {
-            const int src = (lane & ~3) | ((lane + 1) & 3);
-#pragma unroll
-            for (int a = 0; a < 8; ++a) qb[a] = __shfl(qb[a], src);
-        }
+        offsets(r + 1 < 32 ? r + 1 : 31);
+        __syncthreads();
     }
-    double* Qo = Qout + (int64_t)blockIdx.x * 4096 + qrow * 64;
+    double* Qo = Qout + (int64_t)blockIdx.x * 4096 + row0 * 64;
+    const int qlast = cross_q(iota, 31);
 #pragma unroll
-    for (int a = 0; a < 8; ++a) {
-        Qo[4 * a + lq] = qa[a];
-        Qo[32 + 4 * a + ((lq + 3) & 3)] = qb[a];
+    for (int k = 0; k < 4; ++k) {
+        Qo[k * 64 + iota] = qp[k];
+        Qo[k * 64 + qlast] = qq[k];
     }
 }
 
@@ -541,7 +625,7 @@ hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipS
             if (s == 0)
                 hipLaunchKernelGGL(jac_diag_kernel, dim3(np), dim3(256), DIAG_LDS, st, Cb[cur], w.Q, w.stat, NP, sweep, tol);
             else
-                hipLaunchKernelGGL(jac_cross_kernel, dim3(np), dim3(256), 0, st, Cb[cur], w.Q, w.stat, NP, sweep, s, tol);
+                hipLaunchKernelGGL(jac_cross_kernel, dim3(np), dim3(512), 0, st, Cb[cur], w.Q, w.stat, NP, sweep, s, tol);
             hipLaunchKernelGGL(jac_apply_kernel, dim3(4 * np * np), dim3(256), APPLY_LDS, st, Cb[cur], Cb[cur ^ 1], Yb[cur],
                                Yb[cur ^ 1], w.Q, w.stat, NP, sweep, s, tol);
         }
