@@ -425,6 +425,7 @@ __global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict
                                                         const double* __restrict__ Q, const double* __restrict__ stat,
                                                         int NP, int sweep, int st, double tol) {
     if (sweep_done(stat, sweep, tol)) return;
+    __builtin_amdgcn_s_setprio(3);  // short and on the critical path: goes before the Gram waves it shares SIMDs with
     extern __shared__ double sm[];
     double* X = sm;                // 64 x LDX
     double* Qb = sm + 64 * LDX;    // 64 x LDQB (32 columns), later T = X Q_b[:, h]
@@ -601,7 +602,11 @@ __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restr
     }
 }
 
-static const size_t DIAG_LDS = (size_t)(2 * 64 * LDA + 64) * sizeof(double);
+// Dynamic LDS that the two pivot kernels never touch: with it a work-group does not fit on a CU that already holds a
+// work-group of the Gram kernel running on the side stream (64 KB), so it goes to one of the CUs that launch leaves
+// free. Sharing a SIMD with matrix-core waves stretched single pivot solves several times over.
+static const size_t CROSS_PAD_LDS = 100 * 1024;
+static const size_t DIAG_LDS = (size_t)(2 * 64 * LDA + 64) * sizeof(double) + 36 * 1024;  // padded like CROSS_PAD_LDS
 static const size_t APPLY_LDS = (size_t)(64 * LDX + 64 * LDQB + 64 * LDQ) * sizeof(double);
 
 hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st) {
@@ -609,6 +614,7 @@ hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipS
     if (!attr) {
         (void)hipFuncSetAttribute((const void*)jac_diag_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)DIAG_LDS);
         (void)hipFuncSetAttribute((const void*)jac_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)APPLY_LDS);
+        (void)hipFuncSetAttribute((const void*)jac_cross_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CROSS_PAD_LDS);
         attr = true;
     }
     if (max_sweeps > MAX_SWEEPS) max_sweeps = MAX_SWEEPS;
@@ -625,7 +631,7 @@ hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipS
             if (s == 0)
                 hipLaunchKernelGGL(jac_diag_kernel, dim3(np), dim3(256), DIAG_LDS, st, Cb[cur], w.Q, w.stat, NP, sweep, tol);
             else
-                hipLaunchKernelGGL(jac_cross_kernel, dim3(np), dim3(512), 0, st, Cb[cur], w.Q, w.stat, NP, sweep, s, tol);
+                hipLaunchKernelGGL(jac_cross_kernel, dim3(np), dim3(512), CROSS_PAD_LDS, st, Cb[cur], w.Q, w.stat, NP, sweep, s, tol);
             hipLaunchKernelGGL(jac_apply_kernel, dim3(4 * np * np), dim3(256), APPLY_LDS, st, Cb[cur], Cb[cur ^ 1], Yb[cur],
                                Yb[cur ^ 1], w.Q, w.stat, NP, sweep, s, tol);
         }
