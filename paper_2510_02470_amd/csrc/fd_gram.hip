@@ -293,6 +293,133 @@ __global__ __launch_bounds__(256, 2) void gram_cross8_kernel(const float* __rest
     }
 }
 
+// The (new rows) x (new rows) triangle for NP = 512: 256 rows, i.e. 8 row blocks of 32 and 36 blocks (bi >= bj) of
+// 32 x 32. Only the new rows are staged (16 KB per slab). The 36 blocks are dealt to the 4 waves, 9 each, so that a
+// wave needs at most 6 operand rows-blocks per k-step: three 3 x 3 rectangles
+//   rows {5,6,7} x {0,1,2},   rows {5,6,7} x {3,4,5},   rows {2,3,4} x {0,1,2},
+// and the three 2 x 2 triangles on the diagonal that are left, {0,1}, {3,4}, {6,7} (on a diagonal block both
+// operands are the same registers). No idle accumulators, 12 LDS reads per 72 matrix-core instructions. One
+// work-group per column range; partial tiles in the layout of gram_kernel's mode 2 (the upper 32 x 32 block of a
+// diagonal tile is not written and never read).
+template <int W>
+struct New8Map;
+template <>
+struct New8Map<0> {
+    static constexpr int rows[6] = {5, 6, 7, 0, 1, 2};
+    static constexpr int pa[9] = {0, 0, 0, 1, 1, 1, 2, 2, 2}, pb[9] = {3, 4, 5, 3, 4, 5, 3, 4, 5};
+};
+template <>
+struct New8Map<1> {
+    static constexpr int rows[6] = {5, 6, 7, 3, 4, 4};
+    static constexpr int pa[9] = {0, 0, 0, 1, 1, 1, 2, 2, 2}, pb[9] = {3, 4, 0, 3, 4, 0, 3, 4, 0};
+};
+template <>
+struct New8Map<2> {
+    static constexpr int rows[6] = {2, 3, 4, 0, 1, 1};
+    static constexpr int pa[9] = {0, 0, 0, 1, 1, 1, 2, 2, 2}, pb[9] = {3, 4, 0, 3, 4, 0, 3, 4, 0};
+};
+template <>
+struct New8Map<3> {
+    static constexpr int rows[6] = {0, 1, 3, 4, 6, 7};
+    static constexpr int pa[9] = {0, 1, 1, 2, 3, 3, 4, 5, 5}, pb[9] = {0, 0, 1, 2, 2, 3, 4, 4, 5};
+};
+
+template <int W>
+__device__ __forceinline__ void gram_new8_wave(const f32x4* __restrict__ Nv, int nfill, float* __restrict__ partial,
+                                               int group, int64_t s0, int64_t s1, int64_t trips, f32x4* lds) {
+    using M = New8Map<W>;
+    constexpr int LP = 256, STAGE = LP * 4;
+    const int tid = threadIdx.x & 255, lane = tid & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    f32x16 acc[9];
+#pragma unroll
+    for (int q = 0; q < 9; ++q)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+
+    int src[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int ps = it * 256 + tid;
+        const int row = ps >> 2;
+        const int p = (ps & 3) ^ ((row >> 2) & 3);
+        src[it] = row >= nfill ? -1 : row * 4 + p;
+    }
+    f32x4 pre[4];
+    auto fetch = [&](int64_t sl) {  // a slab beyond the range reads as zero
+        const f32x4* base = Nv + sl * STAGE;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) pre[it] = (src[it] >= 0 && sl < s1) ? base[src[it]] : f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    fetch(s0);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) lds[it * 256 + tid] = pre[it];
+    __syncthreads();
+
+    for (int64_t t = 0; t < trips; ++t) {
+        const int cur = (int)(t & 1);
+        const bool more = (t + 1 < trips);
+        if (more) fetch(s0 + t + 1);
+        const f32x4* st = lds + cur * STAGE;
+        f32x4 op[2][6];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int p = 2 * j + h;
+#pragma unroll
+            for (int o = 0; o < 6; ++o) {
+                const int r = M::rows[o] * 32 + l32;
+                op[j][o] = st[r * 4 + (p ^ ((r >> 2) & 3))];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above: the scheduler would sink each next to its use
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int q = 0; q < 9; ++q) acc[q] = mfma32(op[j][M::pa[q]][c], op[j][M::pb[q]][c], acc[q]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+            f32x4* nx = lds + (cur ^ 1) * STAGE;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) nx[it * 256 + tid] = pre[it];
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int q = 0; q < 9; ++q) {
+        const int bi = M::rows[M::pa[q]], bj = M::rows[M::pb[q]];
+        const int ti = bi >> 1, tj = bj >> 1;
+        float* out = partial + ((int64_t)group * 10 + ti * (ti + 1) / 2 + tj) * 4096 + (bi & 1) * 2048 + (bj & 1) * 32;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int r = 8 * (e >> 2) + 4 * h + (e & 3);
+            out[r * 64 + l32] = acc[q][e];
+        }
+    }
+}
+
+// One work-group (4 waves, 32 KB of LDS) per column range, two per CU. Used when the launch has the chip to itself.
+__global__ __launch_bounds__(256, 2) void gram_new8_kernel(const float* __restrict__ nw, int nfill,
+                                                           float* __restrict__ partial, int64_t slabs_total,
+                                                           int64_t slabs_per_group) {
+    extern __shared__ f32x4 lds[];
+    const int group = blockIdx.x;
+    int64_t s0 = (int64_t)group * slabs_per_group;
+    int64_t s1 = s0 + slabs_per_group;
+    if (s1 > slabs_total) s1 = slabs_total;
+    if (s0 > s1) s0 = s1;
+    const f32x4* Nv = reinterpret_cast<const f32x4*>(nw);
+    switch (threadIdx.x >> 6) {  // wave-uniform
+        case 0: gram_new8_wave<0>(Nv, nfill, partial, group, s0, s1, s1 - s0, lds); break;
+        case 1: gram_new8_wave<1>(Nv, nfill, partial, group, s0, s1, s1 - s0, lds); break;
+        case 2: gram_new8_wave<2>(Nv, nfill, partial, group, s0, s1, s1 - s0, lds); break;
+        default: gram_new8_wave<3>(Nv, nfill, partial, group, s0, s1, s1 - s0, lds); break;
+    }
+}
+
 // C (NP x NP, fp64, both triangles) = sum over groups of the partial tiles, in group order. With q = P/2:
 // known_top: tiles with ti < q are not summed, their block is diag(known) (the top rows are the orthogonal rows the
 // last shrink wrote, whose squared norms it recorded). Otherwise tile (ti, tj) comes from source A when its mode
@@ -347,6 +474,7 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(GramSrc a, GramSrc b, 
 // kernel needs more registers than remain on a CU that holds one of them.
 GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_per_cu) {
     GramPlan p;
+    const bool side = wg_per_cu == 1;
     const int P = d.NP / 64, q = P / 2;
     p.mode = mode;
     p.t0 = 0;
@@ -360,7 +488,11 @@ GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_pe
     }
     p.wg_per_group = (p.tiles + 5) / 6;
     if (mode == 1 && P == 8) p.wg_per_group = 2;  // gram_cross8_kernel: 8 wave tiles of 128 x 64
-    const int cus = wg_per_cu == 1 && num_cu > 32 ? num_cu - 16 : num_cu;
+    // gram_new8_kernel (the whole triangle in one work-group) when the launch has the chip to itself. Beside the
+    // eigensolve the slower gram_kernel is the better neighbour: measured on one box, the eigensolve lost more time to
+    // the denser kernel than the side stream gained (21.7 k rows/s against 22.8 k for the whole update at config 5).
+    if (mode == 2 && P == 8 && !side) p.wg_per_group = 1;
+    const int cus = side && num_cu > 32 ? num_cu - 16 : num_cu;
     int g = (wg_per_cu * cus / p.wg_per_group) / 8 * 8;
     if (g < 8) g = 8;
     // keep at least 4 slabs per group so that tiny problems do not drown in partial tiles
@@ -385,6 +517,15 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
             attr8 = true;
         }
         hipLaunchKernelGGL(gram_cross8_kernel, grid, dim3(256), lds, st, top, nw, nfill, partial, d.S, p.slabs_per_group);
+        return hipGetLastError();
+    }
+    if (p.mode == 2 && d.NP == 512 && p.wg_per_group == 1) {
+        static bool attrn = false;
+        if (!attrn) {
+            (void)hipFuncSetAttribute((const void*)gram_new8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+            attrn = true;
+        }
+        hipLaunchKernelGGL(gram_new8_kernel, grid, dim3(256), 32768, st, nw, nfill, partial, d.S, p.slabs_per_group);
         return hipGetLastError();
     }
     switch (d.NP / 64) {
