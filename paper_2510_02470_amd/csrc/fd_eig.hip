@@ -2,12 +2,12 @@
 // LDS, and the coefficient matrices built from it.
 //
 // The shrink step (Method, FD paragraph) needs sigma_j^2 = lambda_j and, for the rebuild, the left singular
-// vectors y_j of the buffer:  sigma_j v_j^T = y_j^T B.  The matrix is cut into 32x32 blocks. One sweep is:
-//   step 0        every work-group takes two diagonal blocks and annihilates all pairs inside each block,
-//   step 1..nb-1  round-robin over block pairs (I, J): annihilate every pair (p in I, q in J),
-// so each off-diagonal element is rotated exactly once per sweep. A step is two kernels: a solve kernel runs the
-// rotations of each 64x64 pivot sub-matrix in LDS and emits its accumulated 64x64 rotation Q_w; `apply`
-// updates C <- Q^T C Q and Y <- Y Q with Q = blockdiag(Q_w) as 64x64x64 products on the fp64 matrix cores.
+// vectors y_j of the buffer:  sigma_j v_j^T = y_j^T B.  The matrix is cut into 32x32 blocks. One sweep is nb - 1 steps;
+// step st pairs the blocks round-robin (I, J) and annihilates every pair (p in I, q in J); step 1, whose pairs cover
+// every block once, first annihilates the pairs inside I and inside J. So each off-diagonal element is rotated
+// exactly once per sweep. A step is two kernels: `pivot` runs the rotations of each 64x64 pivot sub-matrix in LDS
+// and emits its accumulated 64x64 rotation Q_w; `apply` updates C <- Q^T C Q and Y <- Y Q with Q = blockdiag(Q_w) as
+// 64x64x64 products on the fp64 matrix cores (ping-pong between two copies of C and Y).
 #include "sage_internal.h"
 
 namespace sage {
@@ -25,16 +25,12 @@ __device__ __forceinline__ void rr_pair(int n, int t, int i, int& p, int& q) {
 
 // block pair (I, J) of work-group w at step `st` of a sweep over nb blocks
 __device__ __forceinline__ void block_pair(int nb, int st, int w, int& I, int& J) {
-    if (st == 0) {
-        I = 2 * w;
-        J = 2 * w + 1;
-    } else {
-        rr_pair(nb, st - 1, w, I, J);
-    }
+    rr_pair(nb, st - 1, w, I, J);  // st = 1 .. nb - 1
 }
 
-// stat[1 + s] = largest off-diagonal |c_pq| / trace(C) measured (jac_measure_kernel) just before sweep s. The solve
-// is finished, and sweep s and all later ones do nothing, once that is <= tol.
+// stat[1 + s] = largest off-diagonal |c_pq| / trace(C) of the matrix sweep s starts from (written by
+// jac_measure_kernel for s = 0, by the last jac_apply_kernel of sweep s - 1 otherwise). The solve is finished, and
+// sweep s and all later ones do nothing, once that is <= tol.
 __device__ __forceinline__ bool sweep_done(const double* stat, int sweep, double tol) {
     return stat[1 + sweep] <= tol;
 }
@@ -102,29 +98,9 @@ __global__ __launch_bounds__(256) void jac_init_kernel(const double* __restrict_
     }
 }
 
-// all 16 global loads of a thread are issued before the first LDS store, so their latencies overlap
-__device__ __forceinline__ void load_pivot(const double* __restrict__ C, int NP, int I, int J, double* A, int tid) {
-    double v[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        int e = u * 256 + tid;
-        int r = e >> 6, c = e & 63;
-        int gr = (r < 32 ? I * 32 + r : J * 32 + r - 32);
-        int gc = (c < 32 ? I * 32 + c : J * 32 + c - 32);
-        v[u] = C[(int64_t)gr * NP + gc];
-    }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        int e = u * 256 + tid;
-        A[(e >> 6) * LDA + (e & 63)] = v[u];
-    }
-}
-
-// Before sweep `sweep`: stat[1 + sweep] = max off-diagonal |c_pq| / trace. One block per 16 matrix rows.
-// Once a measurement is <= tol the later ones simply repeat it (the matrix no longer changes).
-__global__ __launch_bounds__(256) void jac_measure_kernel(const double* __restrict__ C, double* __restrict__ stat, int NP,
-                                                          int sweep, double tol) {
-    if (sweep > 0 && stat[sweep] <= tol) return;  // stat[1 + sweep] stays 0 <= tol
+// stat[1] = max off-diagonal |c_pq| / trace of the matrix as given (the record before sweep 0; the later records are
+// written by the last jac_apply_kernel of each sweep). One block per 16 matrix rows.
+__global__ __launch_bounds__(256) void jac_measure_kernel(const double* __restrict__ C, double* __restrict__ stat, int NP) {
     __shared__ double red[4];
     double mx = 0.0;
     for (int rr = 0; rr < 16; ++rr) {
@@ -138,74 +114,26 @@ __global__ __launch_bounds__(256) void jac_measure_kernel(const double* __restri
     double tr = stat[0];
     if (threadIdx.x == 0 && tr > 0.0) {
         mx = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
-        if (mx > 0.0) atomic_max_pos_double(&stat[1 + sweep], mx / tr);
+        if (mx > 0.0) atomic_max_pos_double(&stat[1], mx / tr);
     }
 }
 
-// Step 0 of a sweep: work-group w holds diagonal blocks 2w and 2w+1 as one 64x64 matrix and annihilates every pair
-// inside each block (31 rounds of 16 + 16 disjoint rotations, round-robin inside a block). Q accumulates in LDS.
-__global__ __launch_bounds__(256) void jac_diag_kernel(const double* __restrict__ C, double* __restrict__ Qout,
-                                                       double* __restrict__ stat, int NP, int sweep, double tol) {
-    if (sweep_done(stat, sweep, tol)) return;
-    extern __shared__ double sm[];
-    double* A = sm;              // 64 x LDA
-    double* Qm = sm + 64 * LDA;  // 64 x LDA
-    double* cs = Qm + 64 * LDA;  // 32 x 2
-    const int tid = threadIdx.x;
-    const int I = 2 * blockIdx.x, J = 2 * blockIdx.x + 1;
-    const int sexp = scale_exponent(stat[0]);
-    load_pivot(C, NP, I, J, A, tid);
-    for (int e = tid; e < 64 * 64; e += 256) Qm[(e >> 6) * LDA + (e & 63)] = ((e >> 6) == (e & 63)) ? 1.0 : 0.0;
-    __syncthreads();
-
-    for (int t = 0; t < 31; ++t) {
-        if (tid < 32) {
-            int p, q;
-            rr_pair(32, t, tid & 15, p, q);
-            if (tid >= 16) { p += 32; q += 32; }
-            double c, s, t;
-            rot_params_mixed(A[p * LDA + p], A[q * LDA + q], A[p * LDA + q], sexp, c, s, t);
-            cs[2 * tid] = c;
-            cs[2 * tid + 1] = s;
-        }
-        __syncthreads();
-        // 2x2 blocks: X <- R_i^T X R_j,  R = [[c, s], [-s, c]]
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            int b = it * 256 + tid;
-            int i = b >> 5, j = b & 31;
-            int pi, qi, pj, qj;
-            rr_pair(32, t, i & 15, pi, qi);
-            if (i >= 16) { pi += 32; qi += 32; }
-            rr_pair(32, t, j & 15, pj, qj);
-            if (j >= 16) { pj += 32; qj += 32; }
-            double ci = cs[2 * i], si = cs[2 * i + 1], cj = cs[2 * j], sj = cs[2 * j + 1];
-            double x00 = A[pi * LDA + pj], x01 = A[pi * LDA + qj], x10 = A[qi * LDA + pj], x11 = A[qi * LDA + qj];
-            double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
-            double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
-            double z00 = cj * y00 - sj * y01, z01 = sj * y00 + cj * y01;
-            double z10 = cj * y10 - sj * y11, z11 = sj * y10 + cj * y11;
-            if (i == j && si != 0.0) { z01 = 0.0; z10 = 0.0; }
-            A[pi * LDA + pj] = z00; A[pi * LDA + qj] = z01;
-            A[qi * LDA + pj] = z10; A[qi * LDA + qj] = z11;
-        }
-        // Q <- Q R_j
-#pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            int b = it * 256 + tid;
-            int r = b >> 5, j = b & 31;
-            int pj, qj;
-            rr_pair(32, t, j & 15, pj, qj);
-            if (j >= 16) { pj += 32; qj += 32; }
-            double cj = cs[2 * j], sj = cs[2 * j + 1];
-            double a = Qm[r * LDA + pj], bq = Qm[r * LDA + qj];
-            Qm[r * LDA + pj] = cj * a - sj * bq;
-            Qm[r * LDA + qj] = sj * a + cj * bq;
-        }
-        __syncthreads();
+// After the last sweep: a sweep is nb - 1 steps, an odd number, so after an odd number of executed sweeps the result
+// sits in the second copies of C and Y; bring it to the first. The number of executed sweeps is the first record
+// <= tol, or all that were launched.
+__global__ __launch_bounds__(256) void jac_finish_kernel(double* __restrict__ C, const double* __restrict__ C2,
+                                                         double* __restrict__ Y, const double* __restrict__ Y2,
+                                                         const double* __restrict__ stat, int NP, double tol) {
+    const int launched = (int)stat[MAX_SWEEPS + 3];
+    int executed = launched;
+    for (int s = 0; s < launched; ++s)
+        if (stat[1 + s] <= tol) { executed = s; break; }
+    if (!(executed & 1)) return;
+    const int row = blockIdx.x;
+    for (int c = threadIdx.x; c < NP; c += 256) {
+        C[(int64_t)row * NP + c] = C2[(int64_t)row * NP + c];
+        Y[(int64_t)row * NP + c] = Y2[(int64_t)row * NP + c];
     }
-    double* Qo = Qout + (int64_t)blockIdx.x * 4096;
-    for (int e = tid; e < 4096; e += 256) Qo[e] = Qm[(e >> 6) * LDA + (e & 63)];
 }
 
 // Steps 1..nb-1: work-group w holds blocks (I, J) as one 64x64 matrix A (LDS, upper triangle kept current) and
@@ -259,11 +187,14 @@ __device__ __forceinline__ double dpp_row_ror15(double v) {  // lane l of a 16-l
     return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
 
-__global__ __launch_bounds__(512) void jac_cross_kernel(const double* __restrict__ C, double* __restrict__ Qout,
+__global__ __launch_bounds__(512) void jac_pivot_kernel(const double* __restrict__ C, double* __restrict__ Qout,
                                                         double* __restrict__ stat, int NP, int sweep, int st,
                                                         double tol) {
-    __shared__ double A[64 * LDA];
+    extern __shared__ double dyn[];  // two copies of the pivot matrix, 64 x LDA each (the launch asks for more: see launch_eig)
     __shared__ __attribute__((aligned(16))) double cs[2][64];
+    double* const A = dyn;             // the pair phase works in place here
+    double* const A1 = dyn + 64 * LDA; // the within-block phase goes back and forth between A1 and A
+    const bool within = st == 1;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nb = NP / 32;
     int I, J;
@@ -282,10 +213,13 @@ __global__ __launch_bounds__(512) void jac_cross_kernel(const double* __restrict
     const double trace = stat[0];
     if (sweep_done(stat, sweep, tol)) return;
     const int sexp = scale_exponent(trace);
+    {
+        double* const Ain = within ? A1 : A;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int e = u * 512 + tid;
-        A[(e >> 6) * LDA + (e & 63)] = v[u];
+        for (int u = 0; u < 8; ++u) {
+            const int e = u * 512 + tid;
+            Ain[(e >> 6) * LDA + (e & 63)] = v[u];
+        }
     }
     const int i = ent & 31, j = (ent >> 5) & 31, kind = (ent >> 10) & 3;
     const bool valid = ((ent >> 12) & 1) != 0;
@@ -298,6 +232,104 @@ __global__ __launch_bounds__(512) void jac_cross_kernel(const double* __restrict
         qq[k] = (row0 + k == 32 + iota) ? 1.0 : 0.0;
     }
     __syncthreads();
+
+    if (within) {
+        // ---- pairs inside block I and inside block J: 31 rounds, round t pairs index x with x ^ t (same block).
+        // Rotation rho = 16 * block + r: its p is r with a zero inserted at the top bit of t, q = p ^ t. The same
+        // 496 blocks of rotation pairs as below, one per thread, but read from one copy of the matrix and written
+        // to the other, so that lane rho of wave 0 can, in the same round, work out the element its rotation
+        // annihilates next (it recomputes that one element of whatever block holds it), the rotation, and the
+        // diagonal after it. Lane rho also writes this round's pivot (0 once rotated) and the two diagonal entries:
+        // every entry of the upper triangle is written exactly once per round. Q columns stay with their lanes:
+        // lane iota owns columns iota and 32 + iota and fetches the partner columns from lane iota ^ t.
+        if (tid < 32) {  // rotations of round 1
+            const int p = 32 * (tid >> 4) + 2 * (tid & 15), q = p + 1;
+            const double app = A1[p * LDA + p], aqq = A1[q * LDA + q], apq = A1[p * LDA + q];
+            double c, s, t;
+            rot_params_mixed(app, aqq, apq, sexp, c, s, t);
+            cs[1][2 * tid] = c;
+            cs[1][2 * tid + 1] = s;
+            A1[p * LDA + p] = app - t * apq;
+            A1[q * LDA + q] = aqq + t * apq;
+        }
+        __syncthreads();
+        for (int t = 1; t < 32; ++t) {
+            const int par = t & 1;
+            const double* const R = par ? A1 : A;
+            double* const W = par ? A : A1;
+            const int hb = 31 - __builtin_clz(t);
+            const int lowm = (1 << hb) - 1;
+            auto p_of = [&](int rho) { return 32 * (rho >> 4) + ((((rho & 15) >> hb) << (hb + 1)) | (rho & lowm)); };
+            auto up = [&](int r, int c) { return r < c ? r * LDA + c : c * LDA + r; };
+            if (tid < 32) {
+                const int rho = tid;
+                const int p = p_of(rho), q = p ^ t;
+                const double s_cur = cs[par][2 * rho + 1];
+                const double piv = R[p * LDA + q];
+                if (t < 31) {
+                    const int t2 = t + 1, hb2 = 31 - __builtin_clz(t2);
+                    const int p2 = 32 * (rho >> 4) + ((((rho & 15) >> hb2) << (hb2 + 1)) | (rho & ((1 << hb2) - 1)));
+                    const int q2 = p2 ^ t2;
+                    // rotations of this round that hold p2 and q2
+                    auto rot_of = [&](int x) {
+                        const int y = x & 31, m = y < (y ^ t) ? y : (y ^ t);
+                        return 16 * (x >> 5) + (((m >> (hb + 1)) << hb) | (m & lowm));
+                    };
+                    const int ri = rot_of(p2), rj = rot_of(q2);
+                    const int Pi = p_of(ri), Qi = Pi ^ t, Pj = p_of(rj), Qj = Pj ^ t;
+                    const double ci = cs[par][2 * ri], si = cs[par][2 * ri + 1];
+                    const double cj = cs[par][2 * rj], sj = cs[par][2 * rj + 1];
+                    const double x00 = R[up(Pi, Pj)], x01 = R[up(Pi, Qj)], x10 = R[up(Qi, Pj)], x11 = R[up(Qi, Qj)];
+                    const double app = R[p2 * LDA + p2], aqq = R[q2 * LDA + q2];
+                    const bool urow = p2 != Pi, vcol = q2 != Pj;
+                    const double y0 = urow ? si * x00 + ci * x10 : ci * x00 - si * x10;
+                    const double y1 = urow ? si * x01 + ci * x11 : ci * x01 - si * x11;
+                    const double z = vcol ? sj * y0 + cj * y1 : cj * y0 - sj * y1;
+                    double c, s, tt;
+                    rot_params_mixed(app, aqq, z, sexp, c, s, tt);
+                    cs[par ^ 1][2 * rho] = c;
+                    cs[par ^ 1][2 * rho + 1] = s;
+                    W[p2 * LDA + p2] = app - tt * z;
+                    W[q2 * LDA + q2] = aqq + tt * z;
+                } else {
+                    W[p * LDA + p] = R[p * LDA + p];
+                    W[q * LDA + q] = R[q * LDA + q];
+                }
+                W[p * LDA + q] = s_cur != 0.0 ? 0.0 : piv;
+            }
+            {   // this thread's block of rotations (i, j)
+                const int Pi = p_of(i), Qi = Pi ^ t, Pj = p_of(j), Qj = Pj ^ t;
+                const int o00 = up(Pi, Pj), o01 = up(Pi, Qj), o10 = up(Qi, Pj), o11 = up(Qi, Qj);
+                const double ci = cs[par][2 * i], si = cs[par][2 * i + 1], cj = cs[par][2 * j], sj = cs[par][2 * j + 1];
+                const double x00 = R[o00], x01 = R[o01], x10 = R[o10], x11 = R[o11];
+                const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
+                const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
+                if (valid) {
+                    W[o00] = cj * y00 - sj * y01;
+                    W[o01] = sj * y00 + cj * y01;
+                    W[o10] = cj * y10 - sj * y11;
+                    W[o11] = sj * y10 + cj * y11;
+                }
+            }
+            {   // Q: columns iota (block I) and 32 + iota (block J) against those of lane iota ^ t
+                const int mate = iota ^ t, m = iota < mate ? iota : mate;
+                const int rr = ((m >> (hb + 1)) << hb) | (m & lowm);
+                const double c0 = cs[par][2 * rr], s0 = cs[par][2 * rr + 1];
+                const double c1 = cs[par][2 * (16 + rr)], s1 = cs[par][2 * (16 + rr) + 1];
+                const bool first = iota < mate;  // this lane holds the pair's p
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const double op = __shfl_xor(qp[k], t), oq = __shfl_xor(qq[k], t);
+                    qp[k] = first ? c0 * qp[k] - s0 * op : s0 * op + c0 * qp[k];
+                    qq[k] = first ? c1 * qq[k] - s1 * oq : s1 * oq + c1 * qq[k];
+                }
+            }
+            __syncthreads();
+        }
+        // 31 rounds from A1 end in A
+    }
+
+    // ---- pairs (p in I, q in J)
     if (tid < 32) {  // rotations of round 0: p = tid meets q = 32 + tid
         const int p = tid, q = 32 + tid;
         const double app = A[p * LDA + p], aqq = A[q * LDA + q], apq = A[p * LDA + q];
@@ -422,7 +454,7 @@ __device__ __forceinline__ f64x4 mfma64(double a, double b, f64x4 acc) {
 // the two halves of a tile never race. A wave owns 16 rows of the 64x32 result (2 accumulator tiles).
 __global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict__ Cin, double* __restrict__ Cout,
                                                         const double* __restrict__ Yin, double* __restrict__ Yout,
-                                                        const double* __restrict__ Q, const double* __restrict__ stat,
+                                                        const double* __restrict__ Q, double* __restrict__ stat,
                                                         int NP, int sweep, int st, double tol) {
     if (sweep_done(stat, sweep, tol)) return;
     __builtin_amdgcn_s_setprio(3);  // short and on the critical path: goes before the Gram waves it shares SIMDs with
@@ -497,12 +529,24 @@ __global__ __launch_bounds__(256) void jac_apply_kernel(const double* __restrict
         }
     }
     const int gcb = (half == 0 ? Ib : Jb) * 32;
+    double mx = 0.0;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         int r = i0 + 4 * v + lk;
         int gr = isY ? (a * 64 + r) : (r < 32 ? Ia * 32 + r : Ja * 32 + r - 32);
 #pragma unroll
-        for (int jt = 0; jt < 2; ++jt) Mout[(int64_t)gr * NP + gcb + jt * 16 + l16] = acc[jt][v];
+        for (int jt = 0; jt < 2; ++jt) {
+            const int gc = gcb + jt * 16 + l16;
+            Mout[(int64_t)gr * NP + gc] = acc[jt][v];
+            if (gr != gc) mx = fmax(mx, fabs(acc[jt][v]));
+        }
+    }
+    // The last step of a sweep leaves the matrix the next sweep starts from: its largest off-diagonal entry is the
+    // record that sweep (and eig_sort_kernel, after the last one) looks at.
+    if (!isY && st == nb - 1) {
+        for (int o = 32; o >= 1; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
+        const double tr = stat[0];
+        if (lane == 0 && tr > 0.0 && mx > 0.0) atomic_max_pos_double(&stat[2 + sweep], mx / tr);
     }
 }
 
@@ -602,42 +646,38 @@ __global__ __launch_bounds__(256) void basis_coeffs_kernel(const double* __restr
     }
 }
 
-// Dynamic LDS that the two pivot kernels never touch: with it a work-group does not fit on a CU that already holds a
-// work-group of the Gram kernel running on the side stream (64 KB), so it goes to one of the CUs that launch leaves
-// free. Sharing a SIMD with matrix-core waves stretched single pivot solves several times over.
+// The pivot kernel uses 66.5 KB of this (two copies of the pivot matrix); the rest is there so that a work-group does
+// not fit on a CU that already holds a work-group of the Gram kernel running on the side stream (64 KB), so it goes
+// to one of the CUs that launch leaves free. Sharing a SIMD with matrix-core waves stretched single pivot solves
+// several times over.
 static const size_t CROSS_PAD_LDS = 100 * 1024;
-static const size_t DIAG_LDS = (size_t)(2 * 64 * LDA + 64) * sizeof(double) + 36 * 1024;  // padded like CROSS_PAD_LDS
 static const size_t APPLY_LDS = (size_t)(64 * LDX + 64 * LDQB + 64 * LDQ) * sizeof(double);
 
 hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st) {
     static bool attr = false;
     if (!attr) {
-        (void)hipFuncSetAttribute((const void*)jac_diag_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)DIAG_LDS);
         (void)hipFuncSetAttribute((const void*)jac_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)APPLY_LDS);
-        (void)hipFuncSetAttribute((const void*)jac_cross_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CROSS_PAD_LDS);
+        (void)hipFuncSetAttribute((const void*)jac_pivot_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CROSS_PAD_LDS);
         attr = true;
     }
     if (max_sweeps > MAX_SWEEPS) max_sweeps = MAX_SWEEPS;
     if (max_sweeps < 1) max_sweeps = 1;
     hipLaunchKernelGGL(jac_init_kernel, dim3(NP), dim3(256), 0, st, w.C, w.Y, w.diag0, w.stat, NP, max_sweeps);
+    hipLaunchKernelGGL(jac_measure_kernel, dim3(NP / 16), dim3(256), 0, st, w.C, w.stat, NP);
     const int np = NP / 64, nb = NP / 32;
-    // nb is even, so every sweep starts and ends on buffer 0: that is where the result is, whenever it converged
+    // Executed sweeps are the first ones, so sweep number `sweep` starts on copy (sweep * (nb - 1)) & 1 = sweep & 1
     double* Cb[2] = {w.C, w.C2};
     double* Yb[2] = {w.Y, w.Y2};
+    int cur = 0;
     for (int sweep = 0; sweep < max_sweeps; ++sweep) {
-        hipLaunchKernelGGL(jac_measure_kernel, dim3(NP / 16), dim3(256), 0, st, w.C, w.stat, NP, sweep, tol);
-        for (int s = 0; s < nb; ++s) {
-            const int cur = s & 1;
-            if (s == 0)
-                hipLaunchKernelGGL(jac_diag_kernel, dim3(np), dim3(256), DIAG_LDS, st, Cb[cur], w.Q, w.stat, NP, sweep, tol);
-            else
-                hipLaunchKernelGGL(jac_cross_kernel, dim3(np), dim3(512), CROSS_PAD_LDS, st, Cb[cur], w.Q, w.stat, NP, sweep, s, tol);
+        for (int s = 1; s < nb; ++s) {
+            hipLaunchKernelGGL(jac_pivot_kernel, dim3(np), dim3(512), CROSS_PAD_LDS, st, Cb[cur], w.Q, w.stat, NP, sweep, s, tol);
             hipLaunchKernelGGL(jac_apply_kernel, dim3(4 * np * np), dim3(256), APPLY_LDS, st, Cb[cur], Cb[cur ^ 1], Yb[cur],
                                Yb[cur ^ 1], w.Q, w.stat, NP, sweep, s, tol);
+            cur ^= 1;
         }
     }
-    // what the last launched sweep left: eig_sort_kernel tells a converged solve from one that ran out of sweeps
-    hipLaunchKernelGGL(jac_measure_kernel, dim3(NP / 16), dim3(256), 0, st, w.C, w.stat, NP, max_sweeps, tol);
+    hipLaunchKernelGGL(jac_finish_kernel, dim3(NP), dim3(256), 0, st, w.C, w.C2, w.Y, w.Y2, w.stat, NP, tol);
     return hipGetLastError();
 }
 
