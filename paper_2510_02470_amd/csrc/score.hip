@@ -148,51 +148,66 @@ __global__ __launch_bounds__(256) void project_kernel(const T* __restrict__ G, i
 }
 
 // Sum of the split-K partial projections, normalisation and consensus partial sums.
-// One wave per row (4 rows per work-group): lane j holds coordinates j and j + 64 and adds the splits in order, sixteen
-// independent loads at a time. Writes zhat (R x k, fp32) and cons_partial[block][128] (fp64 sums of the block's
-// zhat, the four rows added in wave order). All in fp64, fixed order: the result does not depend on timing.
+// A work-group of 1024 threads takes 4 rows, four waves per row: wave (row, quarter) adds a quarter of the splits
+// in order, lane j holding coordinates 2j and 2j + 1, with all its loads (up to 32 at a time) in flight together;
+// the quarter sums are added in quarter order by the row's first wave, which normalises. Writes zhat (R x k, fp32)
+// and cons_partial[block][128] (fp64 sums of the block's zhat, the four rows added in row order). All in fp64, fixed
+// order: the result does not depend on timing.
 constexpr int FIN_ROWS = 4;
-__global__ __launch_bounds__(256) void score_finalize_kernel(const float* __restrict__ partial, int64_t R, int KP, int k,
-                                                             int splits, float* __restrict__ zhat,
-                                                             double* __restrict__ cons_partial) {
-    __shared__ double cs[4][128];
+__global__ __launch_bounds__(1024) void score_finalize_kernel(const float* __restrict__ partial, int64_t R, int KP, int k,
+                                                              int splits, float* __restrict__ zhat,
+                                                              double* __restrict__ cons_partial) {
+    __shared__ double red[FIN_ROWS][4][128];
+    __shared__ double cs[FIN_ROWS][128];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const bool on0 = lane < KP, on1 = lane + 64 < KP;
-    const int64_t r = (int64_t)blockIdx.x * FIN_ROWS + wave;
-    float h0 = 0.f, h1 = 0.f;
-    if (r < R) {
-        double z0 = 0.0, z1 = 0.0;
-        const float* p0 = partial + r * KP + lane;
-        const int64_t sstride = R * KP;
-        for (int s = 0; s < splits; s += 16) {
-            float v0[16], v1[16];
+    const int rr = wave >> 2, quarter = wave & 3;
+    const int64_t r = (int64_t)blockIdx.x * FIN_ROWS + rr;
+    const bool on = 2 * lane < KP;  // KP is a multiple of 32
+    double z0 = 0.0, z1 = 0.0;
+    if (r < R && on) {
+        const int per = (splits + 3) / 4;
+        const int sa = quarter * per, sb = sa + per < splits ? sa + per : splits;
+        const float2* p0 = reinterpret_cast<const float2*>(partial + r * KP) + lane;
+        const int64_t sstride = R * KP / 2;  // in float2
+        for (int s = sa; s < sb; s += 32) {
+            float2 v[32];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int ss = s + u < splits ? s + u : splits - 1;  // repeats are not added
-                v0[u] = on0 ? p0[ss * sstride] : 0.f;
-                v1[u] = on1 ? p0[ss * sstride + 64] : 0.f;
+            for (int u = 0; u < 32; ++u) {
+                const int ss = s + u < sb ? s + u : sb - 1;  // repeats are not added
+                v[u] = p0[ss * sstride];
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (s + u < splits) {
-                    z0 += (double)v0[u];
-                    z1 += (double)v1[u];
+            for (int u = 0; u < 32; ++u)
+                if (s + u < sb) {
+                    z0 += (double)v[u].x;
+                    z1 += (double)v[u].y;
                 }
         }
-        if (lane >= k) z0 = 0.0;
-        if (lane + 64 >= k) z1 = 0.0;
-        double q2 = z0 * z0 + z1 * z1;
-        for (int o = 32; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
-        const double nrm = sqrt(q2);
-        if (nrm > 0.0) {
-            h0 = (float)(z0 / nrm);
-            h1 = (float)(z1 / nrm);
-        }
-        if (lane < k) zhat[r * k + lane] = h0;
-        if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
     }
-    cs[wave][lane] = (double)h0;
-    cs[wave][lane + 64] = (double)h1;
+    red[rr][quarter][2 * lane] = z0;
+    red[rr][quarter][2 * lane + 1] = z1;
+    __syncthreads();
+    if (quarter == 0) {
+        float h0 = 0.f, h1 = 0.f;
+        if (r < R) {
+            // lane j now holds coordinates j and j + 64
+            double a0 = ((red[rr][0][lane] + red[rr][1][lane]) + red[rr][2][lane]) + red[rr][3][lane];
+            double a1 = ((red[rr][0][lane + 64] + red[rr][1][lane + 64]) + red[rr][2][lane + 64]) + red[rr][3][lane + 64];
+            if (lane >= k) a0 = 0.0;
+            if (lane + 64 >= k) a1 = 0.0;
+            double q2 = a0 * a0 + a1 * a1;
+            for (int o = 32; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
+            const double nrm = sqrt(q2);
+            if (nrm > 0.0) {
+                h0 = (float)(a0 / nrm);
+                h1 = (float)(a1 / nrm);
+            }
+            if (lane < k) zhat[r * k + lane] = h0;
+            if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
+        }
+        cs[rr][lane] = (double)h0;
+        cs[rr][lane + 64] = (double)h1;
+    }
     __syncthreads();
     if (tid < 128)
         cons_partial[(int64_t)blockIdx.x * 128 + tid] = ((cs[0][tid] + cs[1][tid]) + cs[2][tid]) + cs[3][tid];
@@ -267,7 +282,7 @@ hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk
 hipError_t launch_score_finalize(const float* partial, int64_t R, int KP, int k, int splits, float* zhat_out,
                                  double* cons_partial, double* ssum, hipStream_t st) {
     int nblocks = (int)((R + FIN_ROWS - 1) / FIN_ROWS);
-    hipLaunchKernelGGL(score_finalize_kernel, dim3(nblocks), dim3(256), 0, st, partial, R, KP, k, splits, zhat_out,
+    hipLaunchKernelGGL(score_finalize_kernel, dim3(nblocks), dim3(1024), 0, st, partial, R, KP, k, splits, zhat_out,
                        cons_partial);
     hipLaunchKernelGGL(consensus_add_kernel, dim3(1), dim3(1024), 0, st, cons_partial, nblocks, k, ssum);
     return hipGetLastError();
