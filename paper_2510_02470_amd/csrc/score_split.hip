@@ -121,14 +121,15 @@ __device__ __forceinline__ void split8(const u32x4& x0, const u32x4& x1, u32x4& 
 // w, w + 8, w + 16, ... of the work-group's 512: 8 * pitch is a multiple of 128 because the pitch is a multiple of 16)
 // and walks them in line-aligned windows: with phi = (row address mod 128) / (bytes of 8 columns), window m of the
 // wave is the 128 bytes that start 8*phi columns before column m*KC. Its basis operand is then the last phi pieces
-// of image m-1 followed by the first PPR-phi pieces of image m, so LDS keeps a ring of three images (m-1, m, and
-// m+1 on its way in). The first and the last window of a split reach into the neighbouring splits; those pieces
-// of the row operand are zeroed.
+// of image m-1 followed by the first PPR-phi pieces of image m, so LDS keeps a ring of four images: m-1 and m in
+// use, m+1 and m+2 on their way in (an image requested only one window ahead arrived late: with the memory system
+// saturated a load takes about two windows). The first and the last window of a split reach into the neighbouring
+// splits; those pieces of the row operand are zeroed.
 //
 // Work-group = 512 threads = 8 waves (two per SIMD), one per CU, 512 batch rows x KP basis columns; a wave owns 64
 // rows (2 accumulator row tiles) x KP columns. Row operands go straight from global memory to registers, the pieces
-// of window m+2 being requested as soon as the matrix cores are done with the same pieces of window m; images are
-// streamed with direct global->LDS loads.
+// of window m+2 being requested at the start of window m; images are streamed with direct global->LDS loads, also
+// two windows ahead.
 template <typename T>
 struct RowOp {
     u32x4 v[4];  // bf16 rows: v[j] = k-step j; fp32 rows: v[2j], v[2j+1] = k-step j
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
     constexpr int PB = 8 * (int)sizeof(T);  // bytes of a piece in a row: 16 or 32
     constexpr int IMG = 2 * KP * PPR;  // 16-byte pieces per image
     constexpr int KS = KC / 16;        // matrix-core k-steps per window
-    extern __shared__ u32x4 lds[];     // 3 * IMG
+    extern __shared__ u32x4 lds[];     // 4 * IMG
 
     const int id = blockIdx.x;
     const int xcd = id & 7, y = id >> 3;
@@ -215,21 +216,24 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + q * 512),
                                              (__attribute__((address_space(3))) void*)(lds + slot * IMG + q * 512 + wave * 64),
                                              16, 0, 0);
-        if constexpr (IMG % 512 != 0) {  // IMG = 256 (KP = 32, fp32 rows): half a round
-            if (wave < 4)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
-                                                 (__attribute__((address_space(3))) void*)(lds + slot * IMG + wave * 64), 16,
-                                                 0, 0);
+        if constexpr (IMG % 512 != 0) {  // IMG = 256 (KP = 32, fp32 rows): half a round; waves 4..7 repeat it, so that
+                                         // every wave has the same number of loads in flight (the wait below counts)
+            const u32x4* src2 = img + image_of(c) * IMG + (tid & 255);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src2),
+                                             (__attribute__((address_space(3))) void*)(lds + slot * IMG + (wave & 3) * 64), 16,
+                                             0, 0);
         }
     };
+    constexpr int VL = (IMG + 511) / 512;  // image loads per wave and window
 
     // One window. Step s = (k-step j, column tile ct) in order; the basis operand of step s + 1 is fetched from LDS
     // before the matrix-core instructions of step s are issued, and the scheduler may not move anything across a
-    // step (left alone it hoists a whole window of LDS reads and spills). sp / sc / sn: ring slots of images m-1, m
-    // and m+1. a: row operand of this window; afar: buffer that receives window m+2.
-    auto visit = [&](RowOp<T> (&a)[2], RowOp<T> (&afar)[2], int64_t i, int sp, int sc, int sn) {
-        const int64_t m = c0 + i;
-        stage(m + 1, sn);
+    // step (left alone it hoists a whole window of LDS reads and spills). The ring has four slots, image c in slot
+    // c mod 4: m-1 and m are read, m+1 has landed or is landing, m+2 is requested now. a: row operand of this window;
+    // afar: buffer that receives window m+2.
+    auto visit = [&](RowOp<T> (&a)[2], RowOp<T> (&afar)[2], int64_t m) {
+        const int sp = (int)((m - 1) & 3), sc = (int)(m & 3);
+        stage(m + 2, (int)((m + 2) & 3));
         // all 8 row loads of window m+2 together: the four pieces of a line are asked for back to back, while the
         // line is still on its way or fresh in the vector cache
         const int64_t m2 = m + 2 > c1 ? c1 : m + 2;  // beyond the last window: repeat it (never used)
@@ -237,8 +241,8 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int x = 0; x < 4; ++x) load_piece(afar[t], t, m2, x);
-        if (i == 0 || i == nv - 1) {
-            const bool first = i == 0, last = i == nv - 1;
+        if (m == c0 || m == c1) {
+            const bool first = m == c0, last = m == c1;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -282,39 +286,51 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        // 8 row loads were issued after this window's image loads: once at most 8 loads are outstanding the next
-        // image (and every older load) has landed. A bare barrier: __syncthreads() carries a release fence, which on
-        // this target drains every outstanding load and would throw the prefetch distance away. The LDS reads of this
-        // window have all been consumed by matrix-core instructions above.
+        // This window requested VL image loads (image m+2) and 8 row loads (window m+2): once at most 8 + VL loads are
+        // outstanding, image m+1 and the rows of window m+1 (and every older load) have landed; both were requested a
+        // whole window earlier. A bare barrier: __syncthreads() carries a release fence, which on this target drains
+        // every outstanding load and would throw the prefetch distance away. The LDS reads of this window have all
+        // been consumed by matrix-core instructions above.
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8); expcnt, lgkmcnt not waited for
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (8 + VL));  // vmcnt(8 + VL); expcnt, lgkmcnt not waited for
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // The windows of a split are walked from a start that differs from split to split and wrap around: work-groups
+    // that all start at the first window of their split march over memory in lock step, a regular pattern that left
+    // some memory channels idle (5.1 TB/s for the row stream alone against 6.2 TB/s with rotated starts). The two row
+    // tiles of a split keep the same start, so that they still share the basis images through L2. A run of
+    // consecutive windows needs the ring primed with the images around its first window, so the walk is two runs.
     RowOp<T> a0[2], a1[2], a2[2];
-    if (nv > 0) {
-        stage(c0 - 1, 0);
-        stage(c0, 1);
+    auto run = [&](int64_t ms, int64_t len) {
+        stage(ms - 1, (int)((ms - 1) & 3));
+        stage(ms, (int)(ms & 3));
+        stage(ms + 1, (int)((ms + 1) & 3));
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                load_piece(a0[t], t, c0, x);
-                load_piece(a1[t], t, c0 + 1, x);
+                load_piece(a0[t], t, ms, x);
+                load_piece(a1[t], t, ms + 1, x);
             }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        // three windows per trip: the row buffers and the ring slots return to their roles
+        // three windows per trip: the row buffers return to their roles
         int64_t i = 0;
-        for (; i + 2 < nv; i += 3) {
-            visit(a0, a2, i, 0, 1, 2);
-            visit(a1, a0, i + 1, 1, 2, 0);
-            visit(a2, a1, i + 2, 2, 0, 1);
+        for (; i + 2 < len; i += 3) {
+            visit(a0, a2, ms + i);
+            visit(a1, a0, ms + i + 1);
+            visit(a2, a1, ms + i + 2);
         }
-        if (i < nv) visit(a0, a2, i, 0, 1, 2);
-        if (i + 1 < nv) visit(a1, a0, i + 1, 1, 2, 0);
+        if (i < len) visit(a0, a2, ms + i);
+        if (i + 1 < len) visit(a1, a0, ms + i + 1);
+    };
+    if (nv > 0) {
+        const int64_t rot = nv >= 8 ? (int64_t)(((unsigned)split * 37u) % (unsigned)(nv - 4)) + 2 : 0;  // 2 .. nv - 3
+        run(c0 + rot, nv - rot);
+        if (rot > 0) run(c0, rot);
     }
 
     float* out = partial + (int64_t)split * R * KP;
@@ -357,7 +373,7 @@ template <int NT, typename T>
 static hipError_t launch_split_t(const T* G, int64_t R, const void* img, float* partial, const ScorePlan& p,
                                  const Dims& d, hipStream_t st) {
     constexpr int KC = 128 / (int)sizeof(T);
-    constexpr size_t LDS = (size_t)3 * 2 * NT * 32 * (KC / 8) * 16;
+    constexpr size_t LDS = (size_t)4 * 2 * NT * 32 * (KC / 8) * 16;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void*)project_split_kernel<NT, T>, hipFuncAttributeMaxDynamicSharedMemorySize,
