@@ -179,7 +179,7 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
         lbase[t] = (unsigned)((r - row0) * S) + 128u - back;
     }
     // piece x of window m for row tile t
-    auto load_piece = [&](RowOp<T>& a, int t, int64_t m, int x) {
+    auto load_piece = [&](RowOp<T>& a, int t, int64_t m, int x) __attribute__((always_inline)) {
         const int xoff = sizeof(T) == 2 ? 32 * x : 64 * (x >> 1) + 16 * (x & 1);
         const unsigned lo = lbase[t] + back, hi = lo + (unsigned)S - 16u;
         unsigned o = lbase[t] + (unsigned)(m * 128) + (unsigned)xoff;
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
     auto image_of = [&](int64_t c) {  // images outside the matrix repeat the nearest one (finite data, never counted)
         return c < 0 ? (int64_t)0 : (c > chunks_total - 1 ? chunks_total - 1 : c);
     };
-    auto stage = [&](int64_t c, int slot) {
+    auto stage = [&](int64_t c, int slot) __attribute__((always_inline)) {
         const u32x4* src = img + image_of(c) * IMG + tid;
 #pragma unroll
         for (int q = 0; q < IMG / 512; ++q)
@@ -231,16 +231,15 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
     // step (left alone it hoists a whole window of LDS reads and spills). The ring has four slots, image c in slot
     // c mod 4: m-1 and m are read, m+1 has landed or is landing, m+2 is requested now. a: row operand of this window;
     // afar: buffer that receives window m+2.
-    auto visit = [&](RowOp<T> (&a)[2], RowOp<T> (&afar)[2], int64_t m) {
+    auto visit = [&](RowOp<T> (&a)[2], RowOp<T> (&afar)[2], int64_t m) __attribute__((always_inline)) {
         const int sp = (int)((m - 1) & 3), sc = (int)(m & 3);
         stage(m + 2, (int)((m + 2) & 3));
-        // all 8 row loads of window m+2 together: the four pieces of a line are asked for back to back, while the
-        // line is still on its way or fresh in the vector cache
+        // The row loads of window m+2 go out in two bursts, row tile 0 now and row tile 1 half way through the window
+        // (measured: 12% faster than one burst of 8). Within a burst the four pieces of a line are asked for back to
+        // back, while the line is still on its way or fresh in the vector cache.
         const int64_t m2 = m + 2 > c1 ? c1 : m + 2;  // beyond the last window: repeat it (never used)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) load_piece(afar[t], t, m2, x);
+        for (int x = 0; x < 4; ++x) load_piece(afar[0], 0, m2, x);
         if (m == c0 || m == c1) {
             const bool first = m == c0, last = m == c1;
 #pragma unroll
@@ -275,6 +274,10 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
                 const int j2 = (s + 1) / (2 * NT), ct2 = (s + 1) % (2 * NT);
                 b[(s + 1) % 2] = lds[baddr[j2] + ct2 * 32 * PPR];
             }
+            if (s == STEPS / 2) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) load_piece(afar[1], 1, m2, x);
+            }
             const u32x4 bb = b[s % 2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) acc[t][ct % NT] = mfma_bf16(ahi[t], bb, acc[t][ct % NT]);
@@ -304,7 +307,9 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
     // tiles of a split keep the same start, so that they still share the basis images through L2. A run of
     // consecutive windows needs the ring primed with the images around its first window, so the walk is two runs.
     RowOp<T> a0[2], a1[2], a2[2];
-    auto run = [&](int64_t ms, int64_t len) {
+    // (always_inline: called twice, the compiler otherwise makes the fp32-row instance a real function with the
+    // accumulators in scratch memory)
+    auto run = [&](int64_t ms, int64_t len) __attribute__((always_inline)) {
         stage(ms - 1, (int)((ms - 1) & 3));
         stage(ms, (int)(ms & 3));
         stage(ms + 1, (int)((ms + 1) & 3));
