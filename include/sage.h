@@ -152,6 +152,18 @@ void sage_destroy(sage_ctx* ctx);
 int sage_sync(sage_ctx* ctx);
 
 /*
+ * Merge another sketch into this one (Method, FD paragraph: the sketch is the Frequent Directions sketch, which is
+ * mergeable -- feeding the rows of one sketch to another as if they were data gives a sketch of the two streams
+ * together whose covariance error is at most the sum of the two sum_delta plus what this context's later shrinks add).
+ * B_other: DEVICE, rows x D fp32 row-major (e.g. the first `fill` rows of sage_fd_sketch_export's output of the other
+ * context: all the rows its buffer holds), whatever this context's row type is; rows >= 0. The rows go through the
+ * same insert / shrink cycle as sage_fd_update's; sage_stats counts them like data rows (rows_seen, frob2 = their
+ * squared norms). Asynchronous on
+ * the context stream like sage_fd_update; invalidates the basis. The building block for sharding a stream by rows.
+ */
+int sage_fd_merge(sage_ctx* ctx, const float* B_other, int64_t rows);
+
+/*
  * Copy the sketch buffer to B_out as a plain row-major (2*ell) x D fp32 matrix (the library keeps it in a
  * column-slab layout internally). B_out: DEVICE, 2*ell*D floats. Rows >= fill are zero. Waits for the stream.
  */

@@ -181,7 +181,7 @@ int decompose(sage_ctx* c, double tol, bool full) {
 // next / next_rows: what is left of the running update call after this buffer. If a whole further cycle of rows is
 // there, they are stored in the other new half and their own Gram block is formed on the side stream while the
 // eigensolve runs on the context stream (neither needs its result, and the eigensolve leaves most of the chip idle).
-int shrink(sage_ctx* c, const void* next, int64_t next_rows) {
+int shrink(sage_ctx* c, const void* next, int64_t next_rows, int next_dtype) {
     const int LP = c->d.LP, ell = c->d.ell;
     if (c->new_block_ready || (c->top_shrunk && c->gp_cross.tiles > 0)) {
         // The top x top block is known. The new x new block came from the side stream, or is formed here when there
@@ -209,7 +209,7 @@ int shrink(sage_ctx* c, const void* next, int64_t next_rows) {
         const int o = c->cur ^ 1;
         HIPCHK(hipEventRecord(c->ev_mark, c->st));
         HIPCHK(hipStreamWaitEvent(c->st2, c->ev_mark, 0));
-        HIPCHK(launch_insert(next, c->dtype, ell, 0, c->nw[o], LP, c->d, c->st2));
+        HIPCHK(launch_insert(next, next_dtype, ell, 0, c->nw[o], LP, c->d, c->st2));
         HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], c->gp_new, c->d, c->st2));
         HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
     }
@@ -235,7 +235,7 @@ int shrink(sage_ctx* c, const void* next, int64_t next_rows) {
 int flush_pending(sage_ctx* c) {
     if (!c->pending_shrink) return SAGE_OK;
     c->pending_shrink = false;
-    return shrink(c, nullptr, 0);
+    return shrink(c, nullptr, 0, c->dtype);
 }
 
 void reset_scoring(sage_ctx* c) {
@@ -453,18 +453,19 @@ int sage_sync(sage_ctx* c) {
     return SAGE_OK;
 }
 
-int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
+// Rows of type `dtype` (the context's own for sage_fd_update, fp32 for sage_fd_merge) go through the insert / shrink cycle.
+static int update_rows(sage_ctx* c, const void* G_batch, int dtype, int64_t rows) {
     if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
     if (rows == 0) return SAGE_OK;
     c->has_basis = false;
     const char* g = (const char*)G_batch;
-    const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
+    const size_t esz = dtype == SAGE_BF16 ? 2 : 4;
     const int ell = c->d.ell, LP = c->d.LP;
     if (c->pending_shrink) {
         // the buffer filled up exactly at the end of the previous call: with this call's rows at hand the shrink can
         // look ahead
         c->pending_shrink = false;
-        int rc = shrink(c, g, rows);
+        int rc = shrink(c, g, rows, dtype);
         if (rc != SAGE_OK) return rc;
     }
     while (rows > 0) {
@@ -472,7 +473,7 @@ int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
         if (c->fill_top < ell) {
             // first fill of the buffer: rows go into the top half
             take = (int)((int64_t)(ell - c->fill_top) < rows ? (ell - c->fill_top) : rows);
-            RUN(K_INSERT, launch_insert(g, c->dtype, take, c->fill_top, c->top, LP, c->d, c->st));
+            RUN(K_INSERT, launch_insert(g, dtype, take, c->fill_top, c->top, LP, c->d, c->st));
             c->fill_top += take;
         } else if (c->pre_stored) {
             // the previous shrink of this call has had these ell rows stored already (side stream)
@@ -481,7 +482,7 @@ int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
             c->fill_new = ell;
         } else {
             take = (int)((int64_t)(ell - c->fill_new) < rows ? (ell - c->fill_new) : rows);
-            RUN(K_INSERT, launch_insert(g, c->dtype, take, c->fill_new, c->nw[c->cur], LP, c->d, c->st));
+            RUN(K_INSERT, launch_insert(g, dtype, take, c->fill_new, c->nw[c->cur], LP, c->d, c->st));
             c->fill_new += take;
         }
         c->rows_seen += take;
@@ -496,13 +497,19 @@ int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
                 c->pending_shrink = true;
                 if (c->new_block_ready) HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
             } else {
-                int rc = shrink(c, g, rows);
+                int rc = shrink(c, g, rows, dtype);
                 if (rc != SAGE_OK) return rc;
             }
         }
     }
     return SAGE_OK;
 }
+
+int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
+    return update_rows(c, G_batch, c ? c->dtype : SAGE_F32, rows);
+}
+
+int sage_fd_merge(sage_ctx* c, const float* B_other, int64_t rows) { return update_rows(c, B_other, SAGE_F32, rows); }
 
 static int basis_impl(sage_ctx* c, int k, bool weighted);
 

@@ -170,6 +170,40 @@ def test_long_stream_error_does_not_accumulate(ell, D, cycles, batch):
     assert ev.min() >= -1e-5 * fro and ev.max() <= st.sum_delta + 1e-5 * fro
 
 
+@pytest.mark.parametrize("name", ["cfg1", "cfg5_small_bf16"])
+def test_merge_matches_oracle(name):
+    """sage_fd_merge: the second half of a stream is sketched by a second context and its sketch rows (fp32) are fed to
+    the first; the oracle does the same with its own two sketches. Covariance parity and the added FD bound."""
+    B = _binding()
+    w, G, _, _ = _oracle_run(name)
+    half = (w.N // 2 // 7) * 7 + 3  # ragged split point
+    A64 = (inputs.bf16_bits_to_f32(G) if G.dtype == np.uint16 else G).astype(np.float64)
+    fro = (A64 ** 2).sum()
+    o1, o2 = Oracle(w.ell, w.D, 1), Oracle(w.ell, w.D, 1)
+    s1, s2 = B.Sage(w.ell, w.D, dtype=w.dtype), B.Sage(w.ell, w.D, dtype=w.dtype)
+    Gd = to_dev(G, torch)
+    for lo in range(0, half, w.batch):
+        hi = min(half, lo + w.batch)
+        o1.update(G[lo:hi])
+        s1.fd_update(Gd[lo:hi])
+    for lo in range(half, w.N, w.batch):
+        hi = min(w.N, lo + w.batch)
+        o2.update(G[lo:hi])
+        s2.fd_update(Gd[lo:hi])
+    assert s2.stats().fill == o2.fill
+    o1.update(o2.B[:o2.fill].astype(np.float32))  # every row the buffer holds, not only the first ell
+    s1.fd_merge(s2.sketch()[:o2.fill].contiguous())
+    Bg = s1.sketch().cpu().numpy()
+    st1, st2 = s1.stats(), s2.stats()
+    assert st1.n_shrinks == o1.n_shrinks and st1.fill == o1.fill
+    assert cov_diff_spec_norm(Bg, o1.B) / fro <= COV_TOL
+    assert abs(st1.sum_delta - o1.sum_delta) <= 1e-5 * fro
+    if w.D <= 5200:
+        diff = A64.T @ A64 - Bg.astype(np.float64).T @ Bg.astype(np.float64)
+        ev = np.linalg.eigvalsh(diff)
+        assert ev.min() >= -1e-5 * fro and ev.max() <= st1.sum_delta + st2.sum_delta + 1e-5 * fro
+
+
 def test_sketch_is_deterministic():
     w = inputs.WORKLOADS[1].scaled(N=700)
     G = inputs.generate_numpy(w)

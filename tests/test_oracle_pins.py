@@ -455,3 +455,26 @@ def test_cb_selection_matches_per_class_plain_selection():
     perm = rng.permutation(Cn)
     al2, idx2 = o.select_cb(0.3, perm[labels], Cn)
     assert np.array_equal(al2, al) and idx2.tolist() == idx.tolist()
+
+
+def test_sketches_merge_with_added_bounds():
+    """Mergeability (a property of Frequent Directions, the sketch the Method section uses): feeding the rows of the
+    sketch of A2 to the sketch of A1 as data gives B with 0 <= A^T A - B^T B and
+    ||A^T A - B^T B||_2 <= sum_delta(merged context) + sum_delta(second sketch), A = [A1; A2]."""
+    rng = np.random.default_rng(23)
+    ell, D = 8, 40
+    A1 = lowrank_rows(rng, 120, D, 12, noise=0.2)
+    A2 = lowrank_rows(rng, 95, D, 12, noise=0.2)
+    o1, o2 = Oracle(ell, D, 0), Oracle(ell, D, 0)
+    o1.update(A1)
+    o2.update(A2)
+    B2 = o2.B[:o2.fill].astype(np.float32)  # what a merge sends: fp32 rows
+    o1.update(B2)
+    A = np.vstack([A1, A2]).astype(np.float64)
+    diff = A.T @ A - o1.B.T @ o1.B
+    ev = np.linalg.eigvalsh(diff)
+    fro = (A ** 2).sum()
+    assert ev.min() >= -1e-6 * fro  # fp32 rounding of the rows sent
+    assert ev.max() <= o1.sum_delta + o2.sum_delta + 1e-6 * fro
+    assert o1.sum_delta + o2.sum_delta <= fro / ell + 1e-6 * fro
+
