@@ -143,6 +143,19 @@ int sage_select(sage_ctx* ctx, double keep_rate, int64_t* out_idx, int64_t cap, 
 int sage_score_labeled(sage_ctx* ctx, const void* G_batch, const int32_t* labels, int64_t rows);
 int sage_select_cb(sage_ctx* ctx, double keep_rate, int n_classes, int64_t* out_idx, int64_t cap, int64_t* out_m);
 
+/*
+ * Scoring without the N x k store of zhat (Abstract: O(l D) memory, no explicit N x l store). With
+ * store_zhat = 0, sage_score only accumulates the consensus sum (rows are counted, nothing per row is kept), and a
+ * further pass over the same rows in the same order, sage_rescore, recomputes zhat_i and writes alpha_i =
+ * clamp(<zhat_i, u>, -1, 1) (4 bytes per row); sage_select then selects from those. The scores are bit-equal to the
+ * stored run's. store_zhat = 1 (the default) is the two-pass run. Either call resets the scoring pass.
+ * In the store-free run: sage_score after the first sage_rescore, sage_rescore of more rows than were scored,
+ * sage_select before every row has been rescored, sage_score_labeled / sage_select_cb and sage_zhat_export return
+ * SAGE_ERR_STATE. G_batch: DEVICE, as for sage_score. Asynchronous on the context stream.
+ */
+int sage_set_score_store(sage_ctx* ctx, int store_zhat);
+int sage_rescore(sage_ctx* ctx, const void* G_batch, int64_t rows);
+
 /* Release the context and everything it owns (waits for its stream). NULL is allowed. */
 void sage_destroy(sage_ctx* ctx);
 

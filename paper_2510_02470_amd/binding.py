@@ -17,7 +17,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 
 # every symbol include/sage.h declares
 EXPORTS = (
-    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
+    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix",
     "sage_profile_enable", "sage_copy_probe",
@@ -53,6 +53,8 @@ def lib():
     L.sage_fd_create_ex.argtypes = [C.POINTER(vp), i32, i64, i32, i64, vp]
     L.sage_fd_update.argtypes = [vp, vp, i64]
     L.sage_fd_merge.argtypes = [vp, vp, i64]
+    L.sage_set_score_store.argtypes = [vp, i32]
+    L.sage_rescore.argtypes = [vp, vp, i64]
     L.sage_fd_basis.argtypes = [vp, i32]
     L.sage_fd_basis_weighted.argtypes = [vp, i32]
     L.sage_score.argtypes = [vp, vp, i64]
@@ -131,6 +133,13 @@ class Sage:
     def fd_update(self, G):
         G = self._rows(G)
         _check(self.L.sage_fd_update(self.h, _ptr(G), G.shape[0]), "sage_fd_update")
+
+    def set_score_store(self, store_zhat=True):
+        _check(self.L.sage_set_score_store(self.h, 1 if store_zhat else 0), "sage_set_score_store")
+
+    def rescore(self, G):
+        G = self._rows(G)
+        _check(self.L.sage_rescore(self.h, _ptr(G), G.shape[0]), "sage_rescore")
 
     def fd_merge(self, B_other):
         """Feed the rows of another sketch (fp32 device tensor, rows x D) to this one."""

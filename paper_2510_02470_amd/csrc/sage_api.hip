@@ -69,6 +69,8 @@ struct sage_ctx {
     int proj_mode = SAGE_PROJ_AUTO;
     float* zhat = nullptr;
     int64_t cap_rows = 0, n_scored = 0;
+    bool store_zhat = true;   // false: zhat is not kept; alpha comes from a second pass over the rows (sage_rescore)
+    int64_t n_rescored = 0;
     int* labels = nullptr;       // class label of every scored row (sage_score_labeled), same capacity as zhat
     int64_t n_labeled = 0;       // rows of the current pass that came with a label
     void* cb_work = nullptr;     // work space of the class-balanced selection
@@ -240,6 +242,7 @@ int flush_pending(sage_ctx* c) {
 
 void reset_scoring(sage_ctx* c) {
     c->n_scored = 0;
+    c->n_rescored = 0;
     c->n_labeled = 0;
     c->alpha_n = 0;
 }
@@ -247,9 +250,6 @@ void reset_scoring(sage_ctx* c) {
 int ensure_score_buffers(sage_ctx* c) {
     if (!c->ssum) ALLOC(c->ssum, 128 * sizeof(double));
     if (!c->cons_partial) ALLOC(c->cons_partial, (size_t)(SCORE_CHUNK / 4) * 128 * sizeof(double));  // one per 4 rows
-    if (!c->zhat) {
-        ALLOC(c->zhat, (size_t)c->cap_rows * 128 * sizeof(float));
-    }
     HIPCHK(hipMemsetAsync(c->ssum, 0, 128 * sizeof(double), c->st));
     return SAGE_OK;
 }
@@ -563,6 +563,21 @@ int sage_set_basis(sage_ctx* c, const float* Vt, int k) {
     return ensure_score_buffers(c);
 }
 
+// split-K partial projections of one launch
+static int ensure_partial(sage_ctx* c, size_t need) {
+    if (need <= c->proj_partial_floats) return SAGE_OK;
+    if (c->proj_partial) {
+        HIPCHK(hipStreamSynchronize(c->st));
+        (void)hipFree(c->proj_partial);
+        c->proj_partial = nullptr;
+        c->proj_partial_floats = 0;
+    }
+    size_t want = (size_t)512 * 128 * 128 > need ? (size_t)512 * 128 * 128 : need;
+    ALLOC(c->proj_partial, want * sizeof(float));
+    c->proj_partial_floats = want;
+    return SAGE_OK;
+}
+
 static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64_t rows);
 
 int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) { return score_impl(c, G_batch, nullptr, rows); }
@@ -576,7 +591,9 @@ static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64
     if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     if (rows == 0) return SAGE_OK;
-    if (c->n_scored + rows > c->cap_rows) {
+    if (!c->store_zhat && (labels || c->n_rescored > 0)) return SAGE_ERR_STATE;  // no labels without zhat; pass 2 is over
+    if (c->store_zhat && !c->zhat) ALLOC(c->zhat, (size_t)c->cap_rows * 128 * sizeof(float));
+    if (c->store_zhat && c->n_scored + rows > c->cap_rows) {
         if (c->fixed_cap) return SAGE_ERR_CAPACITY;
         int64_t ncap = c->cap_rows;
         while (ncap < c->n_scored + rows) ncap *= 2;
@@ -615,29 +632,84 @@ static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64
         int64_t R = rows < SCORE_CHUNK ? rows : SCORE_CHUNK;
         const bool split = c->img_ok && split_path_ok(g, c->dtype, c->d);
         ScorePlan p = split ? score_split_plan(R, c->dtype, c->d, c->num_cu) : score_plan(R, c->d, c->num_cu);
-        size_t need = (size_t)p.splits * R * c->KP;
-        if (need > c->proj_partial_floats) {
-            if (c->proj_partial) {
-                HIPCHK(hipStreamSynchronize(c->st));
-                (void)hipFree(c->proj_partial);
-                c->proj_partial = nullptr;
-                c->proj_partial_floats = 0;
-            }
-            size_t want = (size_t)512 * 128 * 128 > need ? (size_t)512 * 128 * 128 : need;
-            ALLOC(c->proj_partial, want * sizeof(float));
-            c->proj_partial_floats = want;
+        {
+            int rcp = ensure_partial(c, (size_t)p.splits * R * c->KP);
+            if (rcp != SAGE_OK) return rcp;
         }
         if (split)
             RUN(K_PROJECT, launch_project_split(g, c->dtype, R, c->Vimg, c->KP, c->proj_partial, p, c->d, c->st));
         else
             RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
         RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, p.splits,
-                                             c->zhat + (size_t)c->n_scored * c->k, c->cons_partial, c->ssum, c->st));
+                                             c->store_zhat ? c->zhat + (size_t)c->n_scored * c->k : nullptr,
+                                             c->cons_partial, c->ssum, c->store_zhat ? 0 : 1, nullptr, c->st));
         c->n_scored += R;
         g += (size_t)R * c->d.D * esz;
         rows -= R;
     }
     c->alpha_n = 0;
+    return SAGE_OK;
+}
+
+// alpha capacity for N rows (and the selection work space that goes with it)
+static int ensure_alpha(sage_ctx* c, int64_t N) {
+    if (N <= c->alpha_cap) return SAGE_OK;
+    float* na = nullptr;
+    int64_t ncap = N > c->cap_rows ? N : c->cap_rows;
+    ALLOC(na, (size_t)ncap * sizeof(float));
+    if (c->alpha) {
+        // keep what a running rescoring pass has written
+        if (hipMemcpyAsync(na, c->alpha, (size_t)c->alpha_cap * sizeof(float), hipMemcpyDeviceToDevice, c->st) != hipSuccess ||
+            hipStreamSynchronize(c->st) != hipSuccess) {
+            (void)hipFree(na);
+            return SAGE_ERR_HIP;
+        }
+        (void)hipFree(c->alpha);
+    }
+    c->alpha = na;
+    free_select_work(c->sw);
+    int rc = alloc_select_work(c->sw, ncap);
+    if (rc != SAGE_OK) return rc;
+    c->alpha_cap = ncap;
+    return SAGE_OK;
+}
+
+int sage_set_score_store(sage_ctx* c, int store_zhat) {
+    if (!c) return SAGE_ERR_ARG;
+    c->store_zhat = store_zhat != 0;
+    reset_scoring(c);
+    if (c->ssum) HIPCHK(hipMemsetAsync(c->ssum, 0, 128 * sizeof(double), c->st));
+    return SAGE_OK;
+}
+
+int sage_rescore(sage_ctx* c, const void* G_batch, int64_t rows) {
+    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    if (!c->has_basis || c->store_zhat) return SAGE_ERR_STATE;
+    if (c->n_rescored + rows > c->n_scored) return SAGE_ERR_STATE;  // more rows than the first pass saw
+    if (rows == 0) return SAGE_OK;
+    int rc = ensure_alpha(c, c->n_scored);
+    if (rc != SAGE_OK) return rc;
+    const char* g = (const char*)G_batch;
+    const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
+    while (rows > 0) {
+        int64_t R = rows < SCORE_CHUNK ? rows : SCORE_CHUNK;
+        const bool split = c->img_ok && split_path_ok(g, c->dtype, c->d);
+        ScorePlan p = split ? score_split_plan(R, c->dtype, c->d, c->num_cu) : score_plan(R, c->d, c->num_cu);
+        {
+            int rcp = ensure_partial(c, (size_t)p.splits * R * c->KP);
+            if (rcp != SAGE_OK) return rcp;
+        }
+        if (split)
+            RUN(K_PROJECT, launch_project_split(g, c->dtype, R, c->Vimg, c->KP, c->proj_partial, p, c->d, c->st));
+        else
+            RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
+        RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, p.splits, nullptr, c->cons_partial, c->ssum,
+                                             2, c->alpha + c->n_rescored, c->st));
+        c->n_rescored += R;
+        g += (size_t)R * c->d.D * esz;
+        rows -= R;
+    }
+    c->alpha_n = c->n_rescored == c->n_scored ? c->n_scored : 0;
     return SAGE_OK;
 }
 
@@ -649,20 +721,12 @@ int sage_select(sage_ctx* c, double keep_rate, int64_t* out_idx, int64_t cap, in
     *out_m = m;
     if (m > cap) return SAGE_ERR_CAPACITY;
     if (m > 0 && !out_idx) return SAGE_ERR_ARG;
-    if (N > c->alpha_cap) {
-        if (c->alpha) {
-            HIPCHK(hipStreamSynchronize(c->st));
-            (void)hipFree(c->alpha);
-            c->alpha = nullptr;
-        }
-        free_select_work(c->sw);
-        int64_t ncap = N > c->cap_rows ? N : c->cap_rows;
-        ALLOC(c->alpha, (size_t)ncap * sizeof(float));
-        int rc = alloc_select_work(c->sw, ncap);
+    if (!c->store_zhat && c->n_rescored != N) return SAGE_ERR_STATE;  // the rescoring pass is not complete
+    {
+        int rc = ensure_alpha(c, N);
         if (rc != SAGE_OK) return rc;
-        c->alpha_cap = ncap;
     }
-    RUN(K_SELECT, launch_cosine(c->zhat, N, c->k, c->ssum, c->alpha, c->st));
+    if (c->store_zhat) RUN(K_SELECT, launch_cosine(c->zhat, N, c->k, c->ssum, c->alpha, c->st));
     c->alpha_n = N;
     RUN(K_SELECT, launch_topm(c->alpha, N, m, out_idx, c->sw, c->st));
     HIPCHK(hipStreamSynchronize(c->st));
@@ -674,20 +738,11 @@ int sage_select_cb(sage_ctx* c, double keep_rate, int n_classes, int64_t* out_id
         return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     const int64_t N = c->n_scored;
-    if (c->n_labeled != N) return SAGE_ERR_STATE;  // every row of the pass must have come with a label
+    if (!c->store_zhat || c->n_labeled != N) return SAGE_ERR_STATE;  // needs zhat, and a label for every row of the pass
     *out_m = 0;
-    if (N > c->alpha_cap) {
-        if (c->alpha) {
-            HIPCHK(hipStreamSynchronize(c->st));
-            (void)hipFree(c->alpha);
-            c->alpha = nullptr;
-        }
-        free_select_work(c->sw);
-        int64_t ncap = N > c->cap_rows ? N : c->cap_rows;
-        ALLOC(c->alpha, (size_t)ncap * sizeof(float));
-        int rc = alloc_select_work(c->sw, ncap);
+    {
+        int rc = ensure_alpha(c, N);
         if (rc != SAGE_OK) return rc;
-        c->alpha_cap = ncap;
     }
     const size_t need = cb_work_bytes(n_classes, N);
     if (need > c->cb_work_bytes) {
@@ -773,7 +828,7 @@ int sage_scores_export(sage_ctx* c, float* alpha_out) {
 
 int sage_zhat_export(sage_ctx* c, float* zhat_out) {
     if (!c || (!zhat_out && c->n_scored > 0)) return SAGE_ERR_ARG;
-    if (!c->has_basis) return SAGE_ERR_STATE;
+    if (!c->has_basis || !c->store_zhat) return SAGE_ERR_STATE;
     if (c->n_scored > 0)
         HIPCHK(hipMemcpyAsync(zhat_out, c->zhat, (size_t)c->n_scored * c->k * sizeof(float), hipMemcpyDeviceToDevice,
                               c->st));

@@ -125,7 +125,7 @@ ScorePlan score_plan(int64_t R, const Dims& d, int num_cu);
 hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk, int KP, float* partial,
                           const ScorePlan& p, const Dims& d, hipStream_t st);
 hipError_t launch_score_finalize(const float* partial, int64_t R, int KP, int k, int splits, float* zhat_out,
-                                 double* cons_partial, double* ssum, hipStream_t st);
+                                 double* cons_partial, double* ssum, int mode, float* alpha_out, hipStream_t st);
 
 // score_split.hip: the same projection on the bf16 matrix cores with the basis split as hi + lo (bf16 each).
 // The basis is kept as per-chunk LDS images built once per basis by launch_basis_split (from the fp32 slabs).

@@ -154,12 +154,36 @@ __global__ __launch_bounds__(256) void project_kernel(const T* __restrict__ G, i
 // and cons_partial[block][128] (fp64 sums of the block's zhat, the four rows added in row order). All in fp64, fixed
 // order: the result does not depend on timing.
 constexpr int FIN_ROWS = 4;
+// mode 0: as above. mode 1: consensus partial sums only, zhat is not kept (first scoring pass of a run that does not
+// store zhat). mode 2: the second such pass: alpha_i = clamp(<zhat_i, u>, -1, 1) straight from the recomputed zhat_i,
+// with u = ssum / ||ssum|| rebuilt by every work-group and the arithmetic of cosine_kernel (same lanes, same order),
+// so that the scores are bit-equal to those of the run that stores zhat.
 __global__ __launch_bounds__(1024) void score_finalize_kernel(const float* __restrict__ partial, int64_t R, int KP, int k,
                                                               int splits, float* __restrict__ zhat,
-                                                              double* __restrict__ cons_partial) {
+                                                              double* __restrict__ cons_partial, int mode,
+                                                              const double* __restrict__ ssum,
+                                                              float* __restrict__ alpha) {
     __shared__ double red[FIN_ROWS][4][128];
     __shared__ double cs[FIN_ROWS][128];
+    __shared__ double u[128];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (mode == 2) {  // work-group uniform
+        double* tree = &red[0][0][0];
+        if (tid < 128) {
+            const double sv = tid < k ? ssum[tid] : 0.0;
+            u[tid] = sv;
+            tree[tid] = sv * sv;
+        }
+        __syncthreads();
+        for (int w = 64; w >= 1; w >>= 1) {  // fixed-shape tree, as in cosine_kernel
+            if (tid < w) tree[tid] += tree[tid + w];
+            __syncthreads();
+        }
+        const double nrm = sqrt(tree[0]);
+        __syncthreads();
+        if (tid < 128) u[tid] = nrm > 0.0 ? u[tid] / nrm : 0.0;
+        __syncthreads();
+    }
     const int rr = wave >> 2, quarter = wave & 3;
     const int64_t r = (int64_t)blockIdx.x * FIN_ROWS + rr;
     const bool on = 2 * lane < KP;  // KP is a multiple of 32
@@ -202,14 +226,28 @@ __global__ __launch_bounds__(1024) void score_finalize_kernel(const float* __res
                 h0 = (float)(a0 / nrm);
                 h1 = (float)(a1 / nrm);
             }
-            if (lane < k) zhat[r * k + lane] = h0;
-            if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
+            if (mode == 0) {
+                if (lane < k) zhat[r * k + lane] = h0;
+                if (lane + 64 < k) zhat[r * k + lane + 64] = h1;
+            } else if (mode == 2) {
+                double a = 0.0;
+                if (lane < k) a = (double)h0 * u[lane];
+                if (lane + 64 < k) a += (double)h1 * u[lane + 64];
+                for (int o = 32; o >= 1; o >>= 1) a += __shfl_xor(a, o);
+                if (lane == 0) {
+                    if (a > 1.0) a = 1.0;
+                    if (a < -1.0) a = -1.0;
+                    float f = (float)a;
+                    if (f == 0.f) f = 0.f;  // -0 -> +0
+                    alpha[r] = f;
+                }
+            }
         }
         cs[rr][lane] = (double)h0;
         cs[rr][lane + 64] = (double)h1;
     }
     __syncthreads();
-    if (tid < 128)
+    if (mode != 2 && tid < 128)
         cons_partial[(int64_t)blockIdx.x * 128 + tid] = ((cs[0][tid] + cs[1][tid]) + cs[2][tid]) + cs[3][tid];
 }
 
@@ -280,11 +318,11 @@ hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk
 }
 
 hipError_t launch_score_finalize(const float* partial, int64_t R, int KP, int k, int splits, float* zhat_out,
-                                 double* cons_partial, double* ssum, hipStream_t st) {
+                                 double* cons_partial, double* ssum, int mode, float* alpha_out, hipStream_t st) {
     int nblocks = (int)((R + FIN_ROWS - 1) / FIN_ROWS);
     hipLaunchKernelGGL(score_finalize_kernel, dim3(nblocks), dim3(1024), 0, st, partial, R, KP, k, splits, zhat_out,
-                       cons_partial);
-    hipLaunchKernelGGL(consensus_add_kernel, dim3(1), dim3(1024), 0, st, cons_partial, nblocks, k, ssum);
+                       cons_partial, mode, ssum, alpha_out);
+    if (mode != 2) hipLaunchKernelGGL(consensus_add_kernel, dim3(1), dim3(1024), 0, st, cons_partial, nblocks, k, ssum);
     return hipGetLastError();
 }
 

@@ -301,6 +301,38 @@ def test_end_to_end_reports_conditioning():
     assert err <= max(SCORE_TOL, 20.0 * sin_max), (err, sin_max)
 
 
+@pytest.mark.parametrize("name", ["cfg1_ragged", "cfg5_k64_bf16_aligned"])
+def test_store_free_scoring_is_bit_equal(name):
+    """sage_set_score_store(0): the first scoring pass keeps only the consensus sum, sage_rescore recomputes zhat and
+    writes alpha. Scores and selection must equal the stored run's bit for bit, hence match the oracle like it does."""
+    B = _binding()
+    w, G, o, oidx = _oracle_run(name)
+    s, gidx = run_gpu(w, G)                      # stored run
+    al = s.scores().cpu().numpy()
+    Gd = to_dev(G, torch)
+    s.set_score_store(False)                     # same context, same basis: only the scoring pass restarts
+    for lo in range(0, w.N, w.batch):
+        s.score(Gd[lo:lo + w.batch])
+    with pytest.raises(B.SageError):             # nothing rescored yet
+        s.select(w.keep)
+    with pytest.raises(B.SageError):
+        s.zhat()
+    for lo in range(0, w.N, 97):                 # a different batching on purpose
+        s.rescore(Gd[lo:lo + 97])
+    with pytest.raises(B.SageError):             # the pass is complete
+        s.rescore(Gd[:1])
+    with pytest.raises(B.SageError):
+        s.score(Gd[:1])
+    idx2 = s.select(w.keep)
+    al2 = s.scores().cpu().numpy()
+    assert np.array_equal(al2.view(np.uint32), al.view(np.uint32))
+    assert idx2.cpu().tolist() == gidx.cpu().tolist()
+    s.set_score_store(True)                      # back to the stored run
+    for lo in range(0, w.N, w.batch):
+        s.score(Gd[lo:lo + w.batch])
+    assert s.select(w.keep).cpu().tolist() == gidx.cpu().tolist()
+
+
 # ------------------------------------------------------------------------------------------ selection
 @pytest.mark.parametrize("N,m", [(1, 1), (5, 0), (5, 5), (2048, 205), (2049, 1), (100_000, 10_000), (1_000_003, 9_999),
                                  (300_000, 299_999)])
