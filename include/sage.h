@@ -241,6 +241,19 @@ int sage_probe_gram_eig(sage_ctx* ctx, double* C_out, int eig, double* Y_out, do
 int sage_probe_eig_matrix(sage_ctx* ctx, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out);
 
 /*
+ * The shrink's eigensolve route (Method, FD paragraph: the SVD of the buffer, here through its Gram matrix): with
+ * on != 0 the positive semi-definite Gram matrix is first put through one Cholesky step (C + eps I = L L^T with the
+ * diagonal sorted, Jacobi on L^T L, eigenvectors L W (Lambda + eps I)^{-1/2}), which saves two Jacobi sweeps of seven at
+ * n = 512; with on = 0 (the default) Jacobi runs on the Gram matrix itself. On an MI355X the factorisation costs about
+ * what the two sweeps save once the side stream's work is counted, so it is off unless asked for. The basis of
+ * sage_fd_basis always takes the plain route. ell >= 32 only (on is ignored below that).
+ * sage_probe_eig_psd: that route on a given positive semi-definite n_pad x n_pad matrix (DEVICE, row-major), shrink
+ * tolerance; outputs as sage_probe_eig_matrix (eigenvector columns of eigenvalues near 0 are not meaningful).
+ */
+int sage_set_eig_precondition(sage_ctx* ctx, int on);
+int sage_probe_eig_psd(sage_ctx* ctx, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out);
+
+/*
  * A plain device-to-device copy kernel of `bytes` bytes (16 bytes per work-item; bytes and both DEVICE pointers
  * multiples of 16), asynchronous on hip_stream. Harnesses run it under a profiler to learn what the memory-traffic
  * counters report for a known amount of traffic (bytes read, bytes written), and scale the readings of the path's

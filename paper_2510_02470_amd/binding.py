@@ -19,7 +19,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 EXPORTS = (
     "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
-    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix",
+    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix", "sage_probe_eig_psd", "sage_set_eig_precondition",
     "sage_profile_enable", "sage_copy_probe",
     "sage_profile_read", "sage_strerror",
 )
@@ -75,6 +75,8 @@ def lib():
     L.sage_topm.argtypes = [vp, i64, i64, vp, vp]
     L.sage_probe_gram_eig.argtypes = [vp, vp, i32, vp, vp, C.POINTER(i32)]
     L.sage_probe_eig_matrix.argtypes = [vp, vp, vp, vp, vp]
+    L.sage_probe_eig_psd.argtypes = [vp, vp, vp, vp, vp]
+    L.sage_set_eig_precondition.argtypes = [vp, i32]
     L.sage_copy_probe.argtypes = [vp, vp, i64, vp]
     L.sage_profile_enable.argtypes = [vp, i32]
     L.sage_profile_read.argtypes = [vp, i32, C.POINTER(dbl), C.POINTER(i64)]
@@ -239,6 +241,18 @@ class Sage:
         stat = self.torch.empty((18,), dtype=self.torch.float64, device="cuda")
         _check(self.L.sage_probe_eig_matrix(self.h, _ptr(Cm), _ptr(Y), _ptr(lam), _ptr(stat)), "sage_probe_eig_matrix")
         return Y, lam, stat
+
+    def probe_eig_psd(self, Cm):
+        n = Cm.shape[0]
+        assert Cm.is_cuda and Cm.dtype == self.torch.float64 and Cm.is_contiguous()
+        Y = self.torch.empty((n, n), dtype=self.torch.float64, device="cuda")
+        lam = self.torch.empty((n,), dtype=self.torch.float64, device="cuda")
+        stat = self.torch.empty((18,), dtype=self.torch.float64, device="cuda")
+        _check(self.L.sage_probe_eig_psd(self.h, _ptr(Cm), _ptr(Y), _ptr(lam), _ptr(stat)), "sage_probe_eig_psd")
+        return Y, lam, stat
+
+    def set_eig_precondition(self, on=True):
+        _check(self.L.sage_set_eig_precondition(self.h, 1 if on else 0), "sage_set_eig_precondition")
 
     def profile_enable(self, on=True):
         _check(self.L.sage_profile_enable(self.h, 1 if on else 0), "sage_profile_enable")

@@ -69,6 +69,7 @@ struct sage_ctx {
     int proj_mode = SAGE_PROJ_AUTO;
     float* zhat = nullptr;
     int64_t cap_rows = 0, n_scored = 0;
+    bool precond = false;     // shrink: eigensolve through one Cholesky step (fd_chol.hip)
     bool store_zhat = true;   // false: zhat is not kept; alpha comes from a second pass over the rows (sage_rescore)
     int64_t n_rescored = 0;
     int* labels = nullptr;       // class label of every scored row (sage_score_labeled), same capacity as zhat
@@ -216,7 +217,10 @@ int shrink(sage_ctx* c, const void* next, int64_t next_rows, int next_dtype) {
         HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
     }
     poll_sweeps(c);
-    RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweep_cap, c->st));
+    if (c->precond)
+        RUN(K_EIG, launch_eig_precond(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweep_cap, c->st));
+    else
+        RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweep_cap, c->st));
     RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, LP, ell, c->cnt_top, c->fill_top, LP + c->cnt_new, LP + c->fill_new,
                                       c->Mt, c->acc, JACOBI_TOL_SHRINK, c->st));
     RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], ell, c->Mt, c->top, LP, LP, c->d, c->st));
@@ -406,6 +410,11 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     CALLOC(c->ew.pos, (size_t)NP * sizeof(int));
     CALLOC(c->ew.lam, (size_t)NP * sizeof(double));
     CALLOC(c->ew.known, (size_t)NP * sizeof(double));
+    CALLOC(c->ew.L, (size_t)NP * NP * sizeof(double));
+    CALLOC(c->ew.Ld, (size_t)NP * 64 * sizeof(double));
+    CALLOC(c->ew.perm, (size_t)NP * sizeof(int));
+    CALLOC(c->ew.scal, 8 * sizeof(double));
+    c->precond = false;  // see sage_set_eig_precondition
     CALLOC(c->Mt, (size_t)NP * c->d.LP * sizeof(float));
     CALLOC(c->acc, 8 * sizeof(double));
 #undef CALLOC
@@ -431,7 +440,7 @@ void sage_destroy(sage_ctx* c) {
     if (c->st2) (void)hipStreamSynchronize(c->st2);
     void* ptrs[] = {c->top,     c->nw[0],    c->nw[1],  c->gram_partial, c->gram_partial_new[0], c->gram_partial_new[1],
                     c->ew.C,    c->ew.Y,     c->ew.C2,  c->ew.Y2,        c->ew.Q,    c->ew.diag0, c->ew.stat,
-                    c->ew.pos,  c->ew.lam,   c->ew.known, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
+                    c->ew.pos,  c->ew.lam,   c->ew.known, c->ew.L, c->ew.Ld, c->ew.perm, c->ew.scal, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
                     c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -910,6 +919,27 @@ int sage_probe_eig_matrix(sage_ctx* c, const double* C_in, double* Y_out, double
     if (sweep_stat_out)
         HIPCHK(hipMemcpyAsync(sweep_stat_out, c->ew.stat, 18 * sizeof(double), hipMemcpyDeviceToDevice, c->st));
     HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_probe_eig_psd(sage_ctx* c, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out) {
+    if (!c || !C_in) return SAGE_ERR_ARG;
+    const int NP = c->d.NP;
+    HIPCHK(hipMemcpyAsync(c->ew.C, C_in, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    HIPCHK(launch_eig_precond(c->ew, NP, JACOBI_TOL_SHRINK, MAX_SWEEPS, c->st));
+    if (Y_out) HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    if (lam_out)
+        HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double), NP,
+                                hipMemcpyDeviceToDevice, c->st));
+    if (sweep_stat_out)
+        HIPCHK(hipMemcpyAsync(sweep_stat_out, c->ew.stat, 18 * sizeof(double), hipMemcpyDeviceToDevice, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_set_eig_precondition(sage_ctx* c, int on) {
+    if (!c) return SAGE_ERR_ARG;
+    c->precond = on != 0 && c->d.NP >= 64;
     return SAGE_OK;
 }
 

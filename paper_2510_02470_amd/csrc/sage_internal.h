@@ -81,6 +81,10 @@ struct EigWork {
     int* pos;       // NP: pos[rank] = column of Y holding the rank-th largest eigenvalue
     double* lam;    // NP: eigenvalues sorted descending
     double* known;  // NP: squared norms of the rows the last shrink wrote (lambda_j - delta, 0 from row ell-1 on)
+    double* L;      // NP x NP: Cholesky factor (launch_eig_precond)
+    double* Ld;     // NP x 64: its diagonal blocks while the factorisation runs
+    int* perm;      // NP: diagonal order of the factorisation
+    double* scal;   // [0] the diagonal shift of the factorisation
 };
 constexpr int MAX_SWEEPS = 14;
 // Stopping rule: a sweep records the largest |c_pq| / trace(C) it met before rotating; the solve ends after the
@@ -92,6 +96,8 @@ constexpr double JACOBI_TOL_BASIS = 1e-9;
 // kernels then holds the sweeps that were needed, or max_sweeps + SWEEPS_NOT_CONVERGED when they did not suffice.
 constexpr int SWEEPS_NOT_CONVERGED = 100;
 hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st);
+// fd_chol.hip: the same for a positive semi-definite matrix, through one Cholesky step (fewer sweeps)
+hipError_t launch_eig_precond(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st);
 // scalars on device: acc[0] sum_delta, acc[1] frob2, acc[2] last_delta, acc[3] sweeps used (as double)
 // frob2 += diag0 over matrix indices [ra0, ra1) and [rb0, rb1) (the rows not yet counted in ||A||_F^2)
 hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int ra0, int ra1, int rb0, int rb1, float* Mt,

@@ -95,6 +95,46 @@ def test_eigensolve_on_given_matrices():
     assert torch.equal(Y, torch.eye(n, dtype=torch.float64, device="cuda")) and not lam.any()
 
 
+@pytest.mark.parametrize("ell", [64, 256])
+def test_preconditioned_eigensolve_on_gram_matrices(ell):
+    """The shrink's route (one Cholesky step, Jacobi on L^T L, back-transformation) on positive semi-definite matrices:
+    the eigenvalues, and the matrix the shrink builds from the decomposition, S = sum_j max(lambda_j - delta, 0) y_j y_j^T,
+    against numpy's LAPACK eigh. Rank-deficient input, zero rows and a plain Gram matrix."""
+    B = _binding()
+    s = B.Sage(ell, 64)
+    n = 2 * ell
+    rng = np.random.default_rng(17 + ell)
+
+    def shrunk(lam, Y):
+        o = np.argsort(-lam)
+        lam, Y = lam[o], Y[:, o]
+        w2 = np.maximum(lam - lam[ell - 1], 0.0)
+        return (Y * w2) @ Y.T
+
+    cases = {}
+    A = rng.standard_normal((n, 3 * n)) * (np.arange(1, n + 1)[:, None] ** -0.5)
+    cases["gram"] = A @ A.T
+    A2 = rng.standard_normal((n, n // 4)) @ rng.standard_normal((n // 4, 2 * n))   # rank n/4
+    cases["rank_deficient"] = A2 @ A2.T
+    A3 = A.copy()
+    A3[ell - 1] = 0.0
+    A3[n - 5:] = 0.0                                                              # zero rows, as after a shrink
+    cases["zero_rows"] = A3 @ A3.T
+    for name, Cm in cases.items():
+        Cm = (Cm + Cm.T) / 2
+        tr = np.trace(Cm)
+        Y, lam, stat = s.probe_eig_psd(torch.from_numpy(Cm).cuda())
+        Y, lam, stat = Y.cpu().numpy(), lam.cpu().numpy(), stat.cpu().numpy()
+        le, Ye = np.linalg.eigh(Cm)
+        assert np.abs(np.sort(lam)[::-1] - le[::-1]).max() <= 1e-6 * tr, name
+        assert np.abs(np.linalg.eigvalsh(shrunk(lam, Y) - shrunk(le, Ye))).max() <= 1e-6 * tr, name
+        used = next(i for i in range(15) if stat[1 + i] <= 1e-7)
+        assert used <= 9, (name, used)
+    Z = torch.zeros((n, n), dtype=torch.float64, device="cuda")
+    Y, lam, stat = s.probe_eig_psd(Z)
+    assert np.abs(lam.cpu().numpy()).max() <= 1e-12 and torch.isfinite(Y).all()
+
+
 # ------------------------------------------------------------------------------------------ sketch parity
 def _small_workloads():
     W = inputs.WORKLOADS
@@ -202,6 +242,25 @@ def test_merge_matches_oracle(name):
         diff = A64.T @ A64 - Bg.astype(np.float64).T @ Bg.astype(np.float64)
         ev = np.linalg.eigvalsh(diff)
         assert ev.min() >= -1e-5 * fro and ev.max() <= st1.sum_delta + st2.sum_delta + 1e-5 * fro
+
+
+@pytest.mark.parametrize("name", ["cfg2_small", "cfg5_small_bf16"])
+def test_sketch_with_preconditioned_eigensolve(name):
+    """The same covariance parity with the shrink's eigensolve routed through the Cholesky step."""
+    B = _binding()
+    w, G, o, _ = _oracle_run(name)
+    s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    s.set_eig_precondition(True)
+    Gd = to_dev(G, torch)
+    for lo in range(0, w.N, w.batch):
+        s.fd_update(Gd[lo:lo + w.batch])
+    Bg = s.sketch().cpu().numpy()
+    A64 = (inputs.bf16_bits_to_f32(G) if G.dtype == np.uint16 else G).astype(np.float64)
+    fro = (A64 ** 2).sum()
+    st = s.stats()
+    assert st.n_shrinks == o.n_shrinks and st.fill == o.fill and st.last_sweeps < 100
+    assert cov_diff_spec_norm(Bg, o.B) / fro <= COV_TOL
+    assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro
 
 
 def test_sketch_is_deterministic():
