@@ -173,6 +173,15 @@ void post_sweeps(sage_ctx* c) {
 // (lambda_j - delta), so their block is not recomputed.
 int decompose(sage_ctx* c, double tol, bool full) {
     const bool skip = !full && c->top_shrunk && c->gp_skip.t0 > 0;
+    if (skip && c->fill_new == 0) {
+        // Only the rows the last shrink wrote are there: the Gram matrix is diag(known), nothing to compute and
+        // nothing to rotate (one sweep is launched; it finds the matrix diagonal and returns).
+        GramPlan none = c->gp_skip;
+        none.tiles = 0;
+        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, none, nullptr, nullptr, c->ew.C, true, c->ew.known, c->d, c->st));
+        RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, 1, c->st));
+        return SAGE_OK;
+    }
     const GramPlan& gp = skip ? c->gp_skip : c->gp;
     RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, gp, c->d, c->st));
     RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
