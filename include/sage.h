@@ -177,6 +177,31 @@ int sage_sync(sage_ctx* ctx);
 int sage_fd_merge(sage_ctx* ctx, const float* B_other, int64_t rows);
 
 /*
+ * Rows given by their two factors (Method, definition of g_i as the per-example gradient, taken for a linear last
+ * layer with n_classes x n_features weights followed by n_classes biases and a loss on its logits: the gradient is the
+ * outer product of the logit error e_i = dL/dlogits with [h_i; 1], h_i the layer's input). Row i of the batch is
+ *     g_i[c * n_features + t] = e_i[c] * h_i[t],     g_i[n_classes * n_features + c] = e_i[c],
+ * with every product rounded as a stored row of the context's type would hold it (fp32: the fp32 product; bf16: the
+ * exact product rounded to nearest even), so that each call below computes exactly what its row-major counterpart
+ * (sage_fd_update, sage_score / sage_score_labeled, sage_rescore) computes on those rows -- the sketch bit for bit,
+ * projections up to the order of fp32 summation -- while the D-long rows are never stored or read: the update writes
+ * them straight into the sketch buffer, the scoring pass forms them in registers.
+ * E: DEVICE, rows x n_classes row-major; H: DEVICE, rows x n_features row-major (16-byte aligned); both of the
+ * context's row type; n_classes * (n_features + 1) must equal D (SAGE_ERR_ARG otherwise). labels: DEVICE, rows int32,
+ * or NULL. The in-register projection needs n_features to be a multiple of 128 bytes of the row type (64 bf16, 32
+ * fp32 values); for other shapes the rows are written to a staging buffer of rows x D values, at most 2048 rows at a
+ * time, and projected from there (in the store-free run the scores of such shapes equal the stored run's bit for bit
+ * only when both passes cut the stream into the same batches: the order of summation follows a row's place in the
+ * staging buffer). Asynchronous on the context stream; state rules and errors as for the row-major calls.
+ */
+int sage_fd_update_outer(sage_ctx* ctx, const void* E, const void* H, int64_t rows, int64_t n_classes,
+                         int64_t n_features);
+int sage_score_outer(sage_ctx* ctx, const void* E, const void* H, const int32_t* labels, int64_t rows,
+                     int64_t n_classes, int64_t n_features);
+int sage_rescore_outer(sage_ctx* ctx, const void* E, const void* H, int64_t rows, int64_t n_classes,
+                       int64_t n_features);
+
+/*
  * Copy the sketch buffer to B_out as a plain row-major (2*ell) x D fp32 matrix (the library keeps it in a
  * column-slab layout internally). B_out: DEVICE, 2*ell*D floats. Rows >= fill are zero. Waits for the stream.
  */

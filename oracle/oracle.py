@@ -1,7 +1,8 @@
 """ctypes front end of ``sage_oracle.c`` (fp64 CPU oracle; test infrastructure only).
 
 Every function here only marshals arguments; the arithmetic lives in the C file, which cites the passages of
-the paper (arxiv 2510.02470) it follows.
+the paper (arxiv 2510.02470) it follows. The one exception is ``last_layer_rows``, which writes out the rows that
+the factored entry points of the library are defined on (plain numpy, a few lines).
 """
 import ctypes as C
 import os
@@ -277,3 +278,34 @@ def cb_scores_and_selection(zhat, labels, n_classes, keep_rate):
 
 def keep_count(keep_rate, N):
     return int(_load().orc_keep_count(float(keep_rate), int(N)))
+
+
+def _round_to_bf16(x):
+    """float64 values rounded to the nearest bf16 value (8 significant bits), ties to even; normal range only."""
+    m, ex = np.frexp(np.asarray(x, dtype=np.float64))
+    return np.ldexp(np.rint(np.ldexp(m, 8)), ex - 8)
+
+
+def last_layer_rows(E, H):
+    """The rows behind a batch given by factors (Method, definition of g_i, for a linear last layer of C x dh weights
+    followed by C biases with a loss on the logits): g_i = [vec(e_i h_i^T) ; e_i], i.e. column c*dh + t is
+    e_i[c] * h_i[t] and column C*dh + c is e_i[c], each value as a stored row of the factors' type holds it
+    (float32: the product rounded to float32; bf16 bit patterns: the exact product rounded to bf16).
+    E: N x C, H: N x dh, both float32 or both uint16 (bf16 bits). Returns N x C*(dh+1) of the same type."""
+    E = np.ascontiguousarray(E)
+    H = np.ascontiguousarray(H)
+    assert E.dtype == H.dtype and E.ndim == 2 and H.ndim == 2 and E.shape[0] == H.shape[0]
+    bf = E.dtype == np.uint16
+    if bf:
+        e = (E.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        h = (H.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    else:
+        assert E.dtype == np.float32
+        e, h = E.astype(np.float64), H.astype(np.float64)
+    N, Cn = e.shape
+    W = e[:, :, None] * h[:, None, :]          # N x C x dh, exact in float64 for both types
+    rows = np.concatenate([W.reshape(N, -1), e], axis=1)
+    if bf:
+        r32 = _round_to_bf16(rows).astype(np.float32)  # exact: bf16 values
+        return (r32.view(np.uint32) >> 16).astype(np.uint16)
+    return rows.astype(np.float32)

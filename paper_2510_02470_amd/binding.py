@@ -17,7 +17,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 
 # every symbol include/sage.h declares
 EXPORTS = (
-    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
+    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix", "sage_probe_eig_psd", "sage_set_eig_precondition",
     "sage_profile_enable", "sage_copy_probe",
@@ -53,6 +53,9 @@ def lib():
     L.sage_fd_create_ex.argtypes = [C.POINTER(vp), i32, i64, i32, i64, vp]
     L.sage_fd_update.argtypes = [vp, vp, i64]
     L.sage_fd_merge.argtypes = [vp, vp, i64]
+    L.sage_fd_update_outer.argtypes = [vp, vp, vp, i64, i64, i64]
+    L.sage_score_outer.argtypes = [vp, vp, vp, vp, i64, i64, i64]
+    L.sage_rescore_outer.argtypes = [vp, vp, vp, i64, i64, i64]
     L.sage_set_score_store.argtypes = [vp, i32]
     L.sage_rescore.argtypes = [vp, vp, i64]
     L.sage_fd_basis.argtypes = [vp, i32]
@@ -147,6 +150,28 @@ class Sage:
         """Feed the rows of another sketch (fp32 device tensor, rows x D) to this one."""
         assert B_other.is_cuda and B_other.is_contiguous() and B_other.dtype == self.torch.float32 and B_other.shape[1] == self.D
         _check(self.L.sage_fd_merge(self.h, _ptr(B_other), B_other.shape[0]), "sage_fd_merge")
+
+    def _factors(self, E, H):
+        for t in (E, H):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype and t.dim() == 2
+        assert E.shape[0] == H.shape[0]
+        return E.shape[0], E.shape[1], H.shape[1]
+
+    def fd_update_outer(self, E, H):
+        """Rows e_i (x) [h_i; 1] given by their factors (E: rows x classes, H: rows x features)."""
+        rows, ncls, nfeat = self._factors(E, H)
+        _check(self.L.sage_fd_update_outer(self.h, _ptr(E), _ptr(H), rows, ncls, nfeat), "sage_fd_update_outer")
+
+    def score_outer(self, E, H, labels=None):
+        rows, ncls, nfeat = self._factors(E, H)
+        if labels is not None:
+            assert labels.is_cuda and labels.is_contiguous() and labels.dtype == self.torch.int32
+            assert labels.numel() == rows
+        _check(self.L.sage_score_outer(self.h, _ptr(E), _ptr(H), _ptr(labels), rows, ncls, nfeat), "sage_score_outer")
+
+    def rescore_outer(self, E, H):
+        rows, ncls, nfeat = self._factors(E, H)
+        _check(self.L.sage_rescore_outer(self.h, _ptr(E), _ptr(H), rows, ncls, nfeat), "sage_rescore_outer")
 
     def fd_basis(self, k, weighted=False):
         if weighted:

@@ -40,6 +40,78 @@ hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float
     return hipGetLastError();
 }
 
+// Factored rows (a linear last layer: column c*dh + t of row r is e_rc * h_rt, column C*dh + c is e_rc; Method,
+// definition of g_i). The value a caller would have stored in a row of type T: the fp32 product, for bf16 rows
+// rounded to nearest even (the product of two bf16 values is exact in fp32).
+template <typename T>
+__device__ __forceinline__ float outer_value(const T* __restrict__ e, const T* __restrict__ h, int64_t col, int64_t main,
+                                             int64_t dh, int64_t D) {
+    if (col >= D) return 0.f;
+    if constexpr (sizeof(T) == 2) {
+        if (col >= main) return bf16_to_f32(e[col - main]);
+        const float x = bf16_to_f32(e[col / dh]) * bf16_to_f32(h[col % dh]);
+        return (float)(__bf16)x;
+    } else {
+        if (col >= main) return e[col - main];
+        return e[col / dh] * h[col % dh];
+    }
+}
+
+// Same grid as insert_kernel: one thread writes 4 columns of one row into the slab layout.
+template <typename T>
+__global__ __launch_bounds__(256) void insert_outer_kernel(const T* __restrict__ E, const T* __restrict__ H, int64_t C,
+                                                           int64_t dh, int row0, float* __restrict__ B, int NP, int64_t D,
+                                                           int64_t S) {
+    int64_t piece = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (piece >= S * 4) return;
+    const int64_t r = blockIdx.y, d0 = piece * 4, main = C * dh;
+    const T* e = E + r * C;
+    const T* h = H + r * dh;
+    float v[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = outer_value(e, h, d0 + c, main, dh, D);
+    float4* dst = reinterpret_cast<float4*>(B + blk_off(d0, row0 + (int)r, NP));
+    *dst = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+hipError_t launch_insert_outer(const void* E, const void* H, int dtype, int64_t C, int64_t dh, int64_t rows, int row0,
+                               float* half, int half_rows, const Dims& d, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    dim3 grid((unsigned)((d.S * 4 + 255) / 256), (unsigned)rows);
+    if (dtype == SAGE_BF16)
+        hipLaunchKernelGGL(insert_outer_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)E, (const uint16_t*)H, C,
+                           dh, row0, half, half_rows, d.D, d.S);
+    else
+        hipLaunchKernelGGL(insert_outer_kernel<float>, grid, dim3(256), 0, st, (const float*)E, (const float*)H, C, dh, row0,
+                           half, half_rows, d.D, d.S);
+    return hipGetLastError();
+}
+
+// The same rows written out row-major in their own type (for shapes the factored projection does not take).
+template <typename T>
+__global__ __launch_bounds__(256) void expand_outer_kernel(const T* __restrict__ E, const T* __restrict__ H, int64_t C,
+                                                           int64_t dh, T* __restrict__ out, int64_t D) {
+    const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (col >= D) return;
+    const int64_t r = blockIdx.y;
+    const float x = outer_value(E + r * C, H + r * dh, col, C * dh, dh, D);
+    if constexpr (sizeof(T) == 2) out[r * D + col] = (uint16_t)(__float_as_uint(x) >> 16);  // x is a bf16 value already
+    else out[r * D + col] = x;
+}
+
+hipError_t launch_expand_outer(const void* E, const void* H, int dtype, int64_t C, int64_t dh, int64_t rows, void* out,
+                               const Dims& d, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    dim3 grid((unsigned)((d.D + 255) / 256), (unsigned)rows);
+    if (dtype == SAGE_BF16)
+        hipLaunchKernelGGL(expand_outer_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)E, (const uint16_t*)H, C,
+                           dh, (uint16_t*)out, d.D);
+    else
+        hipLaunchKernelGGL(expand_outer_kernel<float>, grid, dim3(256), 0, st, (const float*)E, (const float*)H, C, dh,
+                           (float*)out, d.D);
+    return hipGetLastError();
+}
+
 // slab layout (NPsrc rows) -> row-major nrows x D
 __global__ __launch_bounds__(256) void export_kernel(const float* __restrict__ Bblk, int NPsrc, float* __restrict__ out,
                                                      int64_t D) {

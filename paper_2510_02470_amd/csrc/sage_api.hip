@@ -65,7 +65,10 @@ struct sage_ctx {
     int Vblk_KP = 0;
     void* Vimg = nullptr;      // bf16 hi/lo chunk images of the basis (score_split.hip); built when the rows allow it
     size_t Vimg_bytes = 0;
-    bool img_ok = false;
+    bool img_ok = false;       // ... and usable for row-major batches of this D
+    bool img_built = false;    // the images hold the current basis
+    void* stage = nullptr;     // factored rows written out, for shapes the factored projection does not take
+    size_t stage_bytes = 0;
     int proj_mode = SAGE_PROJ_AUTO;
     float* zhat = nullptr;
     int64_t cap_rows = 0, n_scored = 0;
@@ -137,6 +140,32 @@ int pad_pow2_32(int v) {
 
 bool use_side(const sage_ctx* c) { return c->st2 != nullptr; }
 
+// Where rows come from: a row-major batch, or the two factors of last-layer gradient rows (sage_fd_update_outer).
+struct RowSrc {
+    const void* G = nullptr;  // rows x D, or
+    const void* E = nullptr;  // rows x C logit errors and
+    const void* H = nullptr;  // rows x dh features
+    int64_t C = 0, dh = 0;
+    int dtype = SAGE_F32;
+    bool outer() const { return G == nullptr; }
+    RowSrc after(int64_t rows, int64_t D) const {
+        const size_t esz = dtype == SAGE_BF16 ? 2 : 4;
+        RowSrc r = *this;
+        if (outer()) {
+            r.E = (const char*)E + (size_t)rows * C * esz;
+            r.H = (const char*)H + (size_t)rows * dh * esz;
+        } else {
+            r.G = (const char*)G + (size_t)rows * D * esz;
+        }
+        return r;
+    }
+};
+
+hipError_t insert_rows(const RowSrc& s, int64_t rows, int row0, float* half, int half_rows, const Dims& d, hipStream_t st) {
+    if (s.outer()) return launch_insert_outer(s.E, s.H, s.dtype, s.C, s.dh, rows, row0, half, half_rows, d, st);
+    return launch_insert(s.G, s.dtype, rows, row0, half, half_rows, d, st);
+}
+
 constexpr int SWEEP_RING = 4;
 
 // Pick up the sweep counts that have arrived and set the number of sweeps to launch next.
@@ -193,7 +222,7 @@ int decompose(sage_ctx* c, double tol, bool full) {
 // next / next_rows: what is left of the running update call after this buffer. If a whole further cycle of rows is
 // there, they are stored in the other new half and their own Gram block is formed on the side stream while the
 // eigensolve runs on the context stream (neither needs its result, and the eigensolve leaves most of the chip idle).
-int shrink(sage_ctx* c, const void* next, int64_t next_rows, int next_dtype) {
+int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
     const int LP = c->d.LP, ell = c->d.ell;
     if (c->new_block_ready || (c->top_shrunk && c->gp_cross.tiles > 0)) {
         // The top x top block is known. The new x new block came from the side stream, or is formed here when there
@@ -215,13 +244,13 @@ int shrink(sage_ctx* c, const void* next, int64_t next_rows, int next_dtype) {
         RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
     }
     c->new_block_ready = false;
-    const bool ahead = use_side(c) && !c->prof && next_rows >= ell;
+    const bool ahead = use_side(c) && !c->prof && next && next_rows >= ell;
     if (ahead) {
         // The other half was last read by the rebuild before last, which precedes the mark on the context stream.
         const int o = c->cur ^ 1;
         HIPCHK(hipEventRecord(c->ev_mark, c->st));
         HIPCHK(hipStreamWaitEvent(c->st2, c->ev_mark, 0));
-        HIPCHK(launch_insert(next, next_dtype, ell, 0, c->nw[o], LP, c->d, c->st2));
+        HIPCHK(insert_rows(*next, ell, 0, c->nw[o], LP, c->d, c->st2));
         HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], c->gp_new, c->d, c->st2));
         HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
     }
@@ -250,7 +279,7 @@ int shrink(sage_ctx* c, const void* next, int64_t next_rows, int next_dtype) {
 int flush_pending(sage_ctx* c) {
     if (!c->pending_shrink) return SAGE_OK;
     c->pending_shrink = false;
-    return shrink(c, nullptr, 0, c->dtype);
+    return shrink(c, nullptr, 0);
 }
 
 void reset_scoring(sage_ctx* c) {
@@ -279,11 +308,9 @@ int ensure_vblk(sage_ctx* c, int KP) {
     return SAGE_OK;
 }
 
-// After Vblk holds a new basis: build the bf16 hi/lo images when the split projection can be used for this D.
-int finish_basis(sage_ctx* c) {
-    c->img_ok = false;
-    if (c->proj_mode == SAGE_PROJ_F32) return SAGE_OK;
-    if (!split_path_ok(nullptr, c->dtype, c->d)) return SAGE_OK;  // nullptr is "aligned": only D is judged here
+// The bf16 hi/lo images of the basis in Vblk (score_split.hip).
+int ensure_images(sage_ctx* c) {
+    if (c->img_built) return SAGE_OK;
     const size_t need = basis_image_bytes(c->KP, c->dtype, c->d);
     if (need > c->Vimg_bytes) {
         if (c->Vimg) {
@@ -296,6 +323,19 @@ int finish_basis(sage_ctx* c) {
         c->Vimg_bytes = need;
     }
     RUN(K_REBUILD, launch_basis_split(c->Vblk, c->KP, c->dtype, c->Vimg, c->d, c->st));
+    c->img_built = true;
+    return SAGE_OK;
+}
+
+// After Vblk holds a new basis: build the images when the split projection can be used for row-major batches of
+// this D (factored rows build them on first use otherwise).
+int finish_basis(sage_ctx* c) {
+    c->img_ok = false;
+    c->img_built = false;
+    if (c->proj_mode == SAGE_PROJ_F32) return SAGE_OK;
+    if (!split_path_ok(nullptr, c->dtype, c->d)) return SAGE_OK;  // nullptr is "aligned": only D is judged here
+    int rc = ensure_images(c);
+    if (rc != SAGE_OK) return rc;
     c->img_ok = true;
     return SAGE_OK;
 }
@@ -450,7 +490,7 @@ void sage_destroy(sage_ctx* c) {
     void* ptrs[] = {c->top,     c->nw[0],    c->nw[1],  c->gram_partial, c->gram_partial_new[0], c->gram_partial_new[1],
                     c->ew.C,    c->ew.Y,     c->ew.C2,  c->ew.Y2,        c->ew.Q,    c->ew.diag0, c->ew.stat,
                     c->ew.pos,  c->ew.lam,   c->ew.known, c->ew.L, c->ew.Ld, c->ew.perm, c->ew.scal, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
-                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work};
+                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work, c->stage};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (c->st2) (void)hipStreamDestroy(c->st2);
@@ -472,18 +512,16 @@ int sage_sync(sage_ctx* c) {
 }
 
 // Rows of type `dtype` (the context's own for sage_fd_update, fp32 for sage_fd_merge) go through the insert / shrink cycle.
-static int update_rows(sage_ctx* c, const void* G_batch, int dtype, int64_t rows) {
-    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+static int update_rows(sage_ctx* c, RowSrc g, int64_t rows) {
+    if (!c || rows < 0) return SAGE_ERR_ARG;
     if (rows == 0) return SAGE_OK;
     c->has_basis = false;
-    const char* g = (const char*)G_batch;
-    const size_t esz = dtype == SAGE_BF16 ? 2 : 4;
     const int ell = c->d.ell, LP = c->d.LP;
     if (c->pending_shrink) {
         // the buffer filled up exactly at the end of the previous call: with this call's rows at hand the shrink can
         // look ahead
         c->pending_shrink = false;
-        int rc = shrink(c, g, rows, dtype);
+        int rc = shrink(c, &g, rows);
         if (rc != SAGE_OK) return rc;
     }
     while (rows > 0) {
@@ -491,7 +529,7 @@ static int update_rows(sage_ctx* c, const void* G_batch, int dtype, int64_t rows
         if (c->fill_top < ell) {
             // first fill of the buffer: rows go into the top half
             take = (int)((int64_t)(ell - c->fill_top) < rows ? (ell - c->fill_top) : rows);
-            RUN(K_INSERT, launch_insert(g, dtype, take, c->fill_top, c->top, LP, c->d, c->st));
+            RUN(K_INSERT, insert_rows(g, take, c->fill_top, c->top, LP, c->d, c->st));
             c->fill_top += take;
         } else if (c->pre_stored) {
             // the previous shrink of this call has had these ell rows stored already (side stream)
@@ -500,11 +538,11 @@ static int update_rows(sage_ctx* c, const void* G_batch, int dtype, int64_t rows
             c->fill_new = ell;
         } else {
             take = (int)((int64_t)(ell - c->fill_new) < rows ? (ell - c->fill_new) : rows);
-            RUN(K_INSERT, launch_insert(g, dtype, take, c->fill_new, c->nw[c->cur], LP, c->d, c->st));
+            RUN(K_INSERT, insert_rows(g, take, c->fill_new, c->nw[c->cur], LP, c->d, c->st));
             c->fill_new += take;
         }
         c->rows_seen += take;
-        g += (size_t)take * c->d.D * esz;
+        g = g.after(take, c->d.D);
         rows -= take;
         if (c->fill_new == ell) {
             if (rows == 0 && use_side(c) && c->top_shrunk && !c->prof) {
@@ -515,7 +553,7 @@ static int update_rows(sage_ctx* c, const void* G_batch, int dtype, int64_t rows
                 c->pending_shrink = true;
                 if (c->new_block_ready) HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
             } else {
-                int rc = shrink(c, g, rows, dtype);
+                int rc = shrink(c, &g, rows);
                 if (rc != SAGE_OK) return rc;
             }
         }
@@ -523,11 +561,41 @@ static int update_rows(sage_ctx* c, const void* G_batch, int dtype, int64_t rows
     return SAGE_OK;
 }
 
-int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
-    return update_rows(c, G_batch, c ? c->dtype : SAGE_F32, rows);
+static RowSrc dense_src(const void* G, int dtype) {
+    RowSrc s;
+    s.G = G;
+    s.dtype = dtype;
+    return s;
 }
 
-int sage_fd_merge(sage_ctx* c, const float* B_other, int64_t rows) { return update_rows(c, B_other, SAGE_F32, rows); }
+// factored rows must tile the context's row exactly: D = C * (dh + 1)
+static bool outer_src(const sage_ctx* c, const void* E, const void* H, int64_t C, int64_t dh, RowSrc& s) {
+    if (!E || !H || C < 1 || dh < 1 || dh > ((int64_t)1 << 40) / C || C * (dh + 1) != c->d.D) return false;
+    s.E = E;
+    s.H = H;
+    s.C = C;
+    s.dh = dh;
+    s.dtype = c->dtype;
+    return true;
+}
+
+int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
+    if (!c || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    return update_rows(c, dense_src(G_batch, c->dtype), rows);
+}
+
+int sage_fd_update_outer(sage_ctx* c, const void* E, const void* H, int64_t rows, int64_t n_classes, int64_t n_features) {
+    if (!c || rows < 0) return SAGE_ERR_ARG;
+    if (rows == 0) return SAGE_OK;
+    RowSrc s;
+    if (!outer_src(c, E, H, n_classes, n_features, s)) return SAGE_ERR_ARG;
+    return update_rows(c, s, rows);
+}
+
+int sage_fd_merge(sage_ctx* c, const float* B_other, int64_t rows) {
+    if (!c || (rows > 0 && !B_other)) return SAGE_ERR_ARG;
+    return update_rows(c, dense_src(B_other, SAGE_F32), rows);
+}
 
 static int basis_impl(sage_ctx* c, int k, bool weighted);
 
@@ -596,17 +664,72 @@ static int ensure_partial(sage_ctx* c, size_t need) {
     return SAGE_OK;
 }
 
-static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64_t rows);
-
-int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) { return score_impl(c, G_batch, nullptr, rows); }
-
-int sage_score_labeled(sage_ctx* c, const void* G_batch, const int32_t* labels, int64_t rows) {
-    if (rows > 0 && !labels) return SAGE_ERR_ARG;
-    return score_impl(c, G_batch, labels, rows);
+// The projection partials of R rows (R <= SCORE_CHUNK) in proj_partial; *slots = partial slots to sum.
+static int project_rows(sage_ctx* c, const RowSrc& src, int64_t R, int* slots) {
+    const void* g = src.G;
+    if (src.outer()) {
+        if (c->proj_mode != SAGE_PROJ_F32 && outer_path_ok(src.E, src.H, src.dtype, src.C, src.dh)) {
+            int rc = ensure_images(c);
+            if (rc != SAGE_OK) return rc;
+            ScorePlan p = score_outer_plan(R, src.dtype, src.C, src.dh, c->num_cu);
+            rc = ensure_partial(c, (size_t)(p.splits + 1) * R * c->KP);
+            if (rc != SAGE_OK) return rc;
+            RUN(K_PROJECT, launch_project_outer(src.E, src.H, src.dtype, R, src.C, src.dh, c->Vimg, c->Vblk, c->KP,
+                                                c->proj_partial, p, c->st));
+            *slots = p.splits + 1;
+            return SAGE_OK;
+        }
+        // any other shape: write the rows out and project them like a row-major batch
+        const size_t need = (size_t)R * c->d.D * (src.dtype == SAGE_BF16 ? 2 : 4);
+        if (need > c->stage_bytes) {
+            if (c->stage) {
+                HIPCHK(hipStreamSynchronize(c->st));
+                (void)hipFree(c->stage);
+                c->stage = nullptr;
+                c->stage_bytes = 0;
+            }
+            ALLOC(c->stage, need);
+            c->stage_bytes = need;
+        }
+        RUN(K_INSERT, launch_expand_outer(src.E, src.H, src.dtype, src.C, src.dh, R, c->stage, c->d, c->st));
+        g = c->stage;
+    }
+    const bool split = c->img_ok && split_path_ok(g, c->dtype, c->d);
+    ScorePlan p = split ? score_split_plan(R, c->dtype, c->d, c->num_cu) : score_plan(R, c->d, c->num_cu);
+    int rc = ensure_partial(c, (size_t)p.splits * R * c->KP);
+    if (rc != SAGE_OK) return rc;
+    if (split)
+        RUN(K_PROJECT, launch_project_split(g, c->dtype, R, c->Vimg, c->KP, c->proj_partial, p, c->d, c->st));
+    else
+        RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
+    *slots = p.splits;
+    return SAGE_OK;
 }
 
-static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64_t rows) {
-    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+static int score_impl(sage_ctx* c, RowSrc g, const int* labels, int64_t rows);
+
+int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) {
+    if (!c || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    return score_impl(c, dense_src(G_batch, c->dtype), nullptr, rows);
+}
+
+int sage_score_labeled(sage_ctx* c, const void* G_batch, const int32_t* labels, int64_t rows) {
+    if (!c || (rows > 0 && (!labels || !G_batch))) return SAGE_ERR_ARG;
+    return score_impl(c, dense_src(G_batch, c->dtype), labels, rows);
+}
+
+int sage_score_outer(sage_ctx* c, const void* E, const void* H, const int32_t* labels, int64_t rows, int64_t n_classes,
+                     int64_t n_features) {
+    if (!c || rows < 0) return SAGE_ERR_ARG;
+    if (!c->has_basis) return SAGE_ERR_STATE;
+    if (rows == 0) return SAGE_OK;
+    RowSrc s;
+    if (!outer_src(c, E, H, n_classes, n_features, s)) return SAGE_ERR_ARG;
+    return score_impl(c, s, labels, rows);
+}
+
+static int score_impl(sage_ctx* c, RowSrc g, const int* labels, int64_t rows) {
+    if (!c || rows < 0) return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     if (rows == 0) return SAGE_OK;
     if (!c->store_zhat && (labels || c->n_rescored > 0)) return SAGE_ERR_STATE;  // no labels without zhat; pass 2 is over
@@ -644,25 +767,16 @@ static int score_impl(sage_ctx* c, const void* G_batch, const int* labels, int64
         HIPCHK(hipMemcpyAsync(c->labels + c->n_scored, labels, (size_t)rows * sizeof(int), hipMemcpyDeviceToDevice, c->st));
         if (c->n_labeled == c->n_scored) c->n_labeled += rows;  // stays behind for good once an unlabeled batch came
     }
-    const char* g = (const char*)G_batch;
-    const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
     while (rows > 0) {
         int64_t R = rows < SCORE_CHUNK ? rows : SCORE_CHUNK;
-        const bool split = c->img_ok && split_path_ok(g, c->dtype, c->d);
-        ScorePlan p = split ? score_split_plan(R, c->dtype, c->d, c->num_cu) : score_plan(R, c->d, c->num_cu);
-        {
-            int rcp = ensure_partial(c, (size_t)p.splits * R * c->KP);
-            if (rcp != SAGE_OK) return rcp;
-        }
-        if (split)
-            RUN(K_PROJECT, launch_project_split(g, c->dtype, R, c->Vimg, c->KP, c->proj_partial, p, c->d, c->st));
-        else
-            RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
-        RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, p.splits,
+        int slots = 0;
+        int rcp = project_rows(c, g, R, &slots);
+        if (rcp != SAGE_OK) return rcp;
+        RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, slots,
                                              c->store_zhat ? c->zhat + (size_t)c->n_scored * c->k : nullptr,
                                              c->cons_partial, c->ssum, c->store_zhat ? 0 : 1, nullptr, c->st));
         c->n_scored += R;
-        g += (size_t)R * c->d.D * esz;
+        g = g.after(R, c->d.D);
         rows -= R;
     }
     c->alpha_n = 0;
@@ -700,35 +814,38 @@ int sage_set_score_store(sage_ctx* c, int store_zhat) {
     return SAGE_OK;
 }
 
-int sage_rescore(sage_ctx* c, const void* G_batch, int64_t rows) {
-    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+static int rescore_impl(sage_ctx* c, RowSrc g, int64_t rows) {
     if (!c->has_basis || c->store_zhat) return SAGE_ERR_STATE;
     if (c->n_rescored + rows > c->n_scored) return SAGE_ERR_STATE;  // more rows than the first pass saw
     if (rows == 0) return SAGE_OK;
     int rc = ensure_alpha(c, c->n_scored);
     if (rc != SAGE_OK) return rc;
-    const char* g = (const char*)G_batch;
-    const size_t esz = c->dtype == SAGE_BF16 ? 2 : 4;
     while (rows > 0) {
         int64_t R = rows < SCORE_CHUNK ? rows : SCORE_CHUNK;
-        const bool split = c->img_ok && split_path_ok(g, c->dtype, c->d);
-        ScorePlan p = split ? score_split_plan(R, c->dtype, c->d, c->num_cu) : score_plan(R, c->d, c->num_cu);
-        {
-            int rcp = ensure_partial(c, (size_t)p.splits * R * c->KP);
-            if (rcp != SAGE_OK) return rcp;
-        }
-        if (split)
-            RUN(K_PROJECT, launch_project_split(g, c->dtype, R, c->Vimg, c->KP, c->proj_partial, p, c->d, c->st));
-        else
-            RUN(K_PROJECT, launch_project(g, c->dtype, R, c->Vblk, c->KP, c->proj_partial, p, c->d, c->st));
-        RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, p.splits, nullptr, c->cons_partial, c->ssum,
-                                             2, c->alpha + c->n_rescored, c->st));
+        int slots = 0;
+        rc = project_rows(c, g, R, &slots);
+        if (rc != SAGE_OK) return rc;
+        RUN(K_FINALIZE, launch_score_finalize(c->proj_partial, R, c->KP, c->k, slots, nullptr, c->cons_partial, c->ssum, 2,
+                                             c->alpha + c->n_rescored, c->st));
         c->n_rescored += R;
-        g += (size_t)R * c->d.D * esz;
+        g = g.after(R, c->d.D);
         rows -= R;
     }
     c->alpha_n = c->n_rescored == c->n_scored ? c->n_scored : 0;
     return SAGE_OK;
+}
+
+int sage_rescore(sage_ctx* c, const void* G_batch, int64_t rows) {
+    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    return rescore_impl(c, dense_src(G_batch, c->dtype), rows);
+}
+
+int sage_rescore_outer(sage_ctx* c, const void* E, const void* H, int64_t rows, int64_t n_classes, int64_t n_features) {
+    if (!c || rows < 0) return SAGE_ERR_ARG;
+    if (rows == 0) return rescore_impl(c, RowSrc{}, 0);
+    RowSrc s;
+    if (!outer_src(c, E, H, n_classes, n_features, s)) return SAGE_ERR_ARG;
+    return rescore_impl(c, s, rows);
 }
 
 int sage_select(sage_ctx* c, double keep_rate, int64_t* out_idx, int64_t cap, int64_t* out_m) {

@@ -45,6 +45,13 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_floa
 // copy `rows` batch rows into rows row0.. of a half buffer (half_rows rows per slab)
 hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* half, int half_rows, const Dims& d,
                          hipStream_t st);
+// factored rows (E: rows x C logit errors, H: rows x dh features, both of the row type): column c*dh + t = e_c * h_t
+// rounded as a stored row would be, column C*dh + c = e_c; requires D = C * (dh + 1)
+hipError_t launch_insert_outer(const void* E, const void* H, int dtype, int64_t C, int64_t dh, int64_t rows, int row0,
+                               float* half, int half_rows, const Dims& d, hipStream_t st);
+// ... written out row-major (rows x D of the row type)
+hipError_t launch_expand_outer(const void* E, const void* H, int dtype, int64_t C, int64_t dh, int64_t rows, void* out,
+                               const Dims& d, hipStream_t st);
 hipError_t launch_plain_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
 hipError_t launch_probe_permute(const double* in, double* out, int NP, int LP, int ell, bool both, hipStream_t st);
 hipError_t launch_export_rows(const float* Bblk, int NPsrc, int nrows, float* out, const Dims& d, hipStream_t st);
@@ -143,6 +150,14 @@ hipError_t launch_basis_split(const float* Vblk, int KP, int dtype, void* img, c
 ScorePlan score_split_plan(int64_t R, int dtype, const Dims& d, int num_cu);
 hipError_t launch_project_split(const void* G, int dtype, int64_t R, const void* img, int KP, float* partial,
                                 const ScorePlan& p, const Dims& d, hipStream_t st);
+
+// The projection of factored rows (see launch_insert_outer) without storing them. Needs the images and the fp32 slabs
+// of the basis; writes p.splits + 1 partial slots (the last one holds the bias columns).
+bool outer_path_ok(const void* E, const void* H, int dtype, int64_t C, int64_t dh);
+ScorePlan score_outer_plan(int64_t R, int dtype, int64_t C, int64_t dh, int num_cu);
+hipError_t launch_project_outer(const void* E, const void* H, int dtype, int64_t R, int64_t C, int64_t dh,
+                                const void* img, const float* Vblk, int KP, float* partial, const ScorePlan& p,
+                                hipStream_t st);
 
 // select.hip
 hipError_t launch_cosine(const float* zhat, int64_t N, int k, const double* ssum, float* alpha, hipStream_t st);

@@ -180,3 +180,68 @@ class DeviceStream:
             out[:R].copy_(G)
             return out[:R]
         return G
+
+
+# ---- factored last-layer rows ------------------------------------------------------------------------------
+# For a linear last layer under softmax cross-entropy the per-example gradient is (p_i - y_i) (x) [h_i; 1]. The
+# generators below make the two factors of such rows (never the rows): features h_i = relu(class mean + noise) of a
+# C-class mixture, logits from a fixed random classifier that partly knows the class means, a share of wrong labels.
+# E = softmax(logits) - onehot(label) (rows x C), H = features (rows x dh), labels (rows, int32).
+
+def _factor_params(C, dh, seed):
+    rng = _rng(seed, 11)
+    means = rng.standard_normal((C, dh)) * 0.7
+    Wc = (means * 0.6 + rng.standard_normal((C, dh)) * 0.4) / np.sqrt(dh) * 4.0  # a half-trained classifier
+    bc = rng.standard_normal(C) * 0.1
+    return means, Wc, bc
+
+
+def generate_factors_numpy(N, C, dh, dtype="f32", seed=0, wrong_labels=0.1):
+    """(E, H, labels): float32 arrays, or uint16 bf16 bit patterns when dtype == 'bf16'; labels int32."""
+    means, Wc, bc = _factor_params(C, dh, seed)
+    rng = _rng(seed, 12)
+    cls = rng.integers(0, C, size=N)
+    Hm = np.maximum(means[cls] + rng.standard_normal((N, dh)), 0.0)
+    logits = Hm @ Wc.T + bc
+    logits -= logits.max(axis=1, keepdims=True)
+    P = np.exp(logits)
+    P /= P.sum(axis=1, keepdims=True)
+    labels = np.where(rng.random(N) < wrong_labels, rng.integers(0, C, size=N), cls)
+    E = P.copy()
+    E[np.arange(N), labels] -= 1.0
+    E = E.astype(np.float32)
+    Hm = Hm.astype(np.float32)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(E), f32_to_bf16_bits(Hm), labels.astype(np.int32)
+    return E, Hm, labels.astype(np.int32)
+
+
+class DeviceFactors:
+    """The same recipe batch by batch on the GPU with torch (input synthesis, never timed); a batch is a pure function
+    of (seed, batch index)."""
+
+    def __init__(self, C, dh, dtype="bf16", seed=0, wrong_labels=0.1, device="cuda"):
+        import torch
+
+        self.torch, self.C, self.dh, self.dtype, self.seed = torch, int(C), int(dh), dtype, int(seed)
+        self.wrong = float(wrong_labels)
+        self.device = torch.device(device)
+        means, Wc, bc = _factor_params(self.C, self.dh, self.seed)
+        self.means = torch.from_numpy(means.astype(np.float32)).to(self.device)
+        self.Wc = torch.from_numpy(Wc.astype(np.float32)).to(self.device)
+        self.bc = torch.from_numpy(bc.astype(np.float32)).to(self.device)
+
+    def batch(self, b, rows):
+        torch = self.torch
+        g = torch.Generator(device=self.device)
+        g.manual_seed((self.seed * 1_000_003 + 13) * 1_000_003 + int(b))
+        cls = torch.randint(0, self.C, (rows,), generator=g, device=self.device)
+        Hm = torch.relu(self.means[cls] + torch.randn((rows, self.dh), generator=g, device=self.device))
+        P = torch.softmax(Hm @ self.Wc.T + self.bc, dim=1)
+        wrong = torch.rand((rows,), generator=g, device=self.device) < self.wrong
+        other = torch.randint(0, self.C, (rows,), generator=g, device=self.device)
+        labels = torch.where(wrong, other, cls)
+        E = P
+        E[torch.arange(rows, device=self.device), labels] -= 1.0
+        td = torch.bfloat16 if self.dtype == "bf16" else torch.float32
+        return E.to(td).contiguous(), Hm.to(td).contiguous(), labels.to(torch.int32)

@@ -573,3 +573,122 @@ def test_class_balanced_ties_empty_classes_and_errors():
     with pytest.raises(B.SageError) as e:
         s.select_cb(0.5, Cn)
     assert e.value.code == B.SAGE_ERR_STATE
+
+
+# ------------------------------------------------------------------------------------------ factored last-layer rows
+# name: (dtype, classes, features, N, batch, ell, k). The in-register projection takes features that fill whole
+# 128-byte windows (64 bf16 / 32 fp32 values); the other shapes go through the staging buffer.
+_OUTER_CASES = {
+    "f32_c10_h64": ("f32", 10, 64, 700, 300, 32, 16),
+    "f32_c7_h50_staged": ("f32", 7, 50, 500, 128, 24, 9),
+    "bf16_c24_h128": ("bf16", 24, 128, 1300, 600, 64, 32),
+    "bf16_c40_h64_k128": ("bf16", 40, 64, 1100, 1100, 130, 128),
+    "bf16_c8_h72_staged": ("bf16", 8, 72, 600, 250, 32, 20),
+    "f32_c33_h96_k64": ("f32", 33, 96, 640, 513, 80, 64),
+}
+_OUTER_RUNS = {}
+
+
+def _outer_run(name):
+    """Factors, the rows the oracle writes out from them, and the oracle's full run on those rows."""
+    if name not in _OUTER_RUNS:
+        dt, Cn, dh, N, batch, ell, k = _OUTER_CASES[name]
+        E, H, labels = inputs.generate_factors_numpy(N, Cn, dh, dt, seed=len(name))
+        G = oracle.last_layer_rows(E, H)
+        w = inputs.WORKLOADS[1].scaled(name=name, N=N, D=Cn * (dh + 1), dtype=dt, ell=ell, k=k, batch=batch, keep=0.1)
+        o, oidx = run_oracle(w, G, mode=1)
+        _OUTER_RUNS[name] = (w, E, H, labels, G, o, oidx)
+    return _OUTER_RUNS[name]
+
+
+@pytest.mark.parametrize("name", ["f32_c10_h64", "f32_c7_h50_staged", "bf16_c24_h128", "bf16_c8_h72_staged"])
+def test_outer_update_equals_row_major_update_and_matches_oracle(name):
+    """sage_fd_update_outer writes the very values a row-major batch of the same rows would bring, so its sketch equals
+    sage_fd_update's bit for bit; against the oracle on the written-out rows it meets the covariance bound."""
+    B = _binding()
+    w, E, H, _, G, o, _ = _outer_run(name)
+    s1, s2 = B.Sage(w.ell, w.D, dtype=w.dtype), B.Sage(w.ell, w.D, dtype=w.dtype)
+    Ed, Hd, Gd = to_dev(E, torch), to_dev(H, torch), to_dev(G, torch)
+    for lo in range(0, w.N, w.batch):
+        s1.fd_update_outer(Ed[lo:lo + w.batch], Hd[lo:lo + w.batch])
+        s2.fd_update(Gd[lo:lo + w.batch])
+    B1, B2 = s1.sketch(), s2.sketch()
+    assert torch.equal(B1, B2)
+    st = s1.stats()
+    assert st.n_shrinks == o.n_shrinks and st.fill == o.fill and st.rows_seen == w.N
+    A64 = (inputs.bf16_bits_to_f32(G) if G.dtype == np.uint16 else G).astype(np.float64)
+    fro = (A64 ** 2).sum()
+    assert cov_diff_spec_norm(B1.cpu().numpy(), o.B) / fro <= COV_TOL
+    assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro and abs(st.frob2 - fro) <= 1e-5 * fro
+
+
+@pytest.mark.parametrize("name", list(_OUTER_CASES.keys()))
+def test_outer_scoring_matches_oracle(name):
+    """sage_score_outer on the oracle's basis against the oracle's scoring of the written-out rows: zhat to 1e-5, alpha
+    to 1e-4, selection outside the threshold band; then the store-free run (score + rescore from factors) must give
+    the stored run's scores bit for bit."""
+    B = _binding()
+    w, E, H, labels, G, o, _ = _outer_run(name)
+    V = o.V.astype(np.float32)
+    s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    s.set_basis(torch.from_numpy(V).cuda())
+    o2 = Oracle(w.ell, w.D, 1)
+    o2.set_basis(V.astype(np.float64))
+    Ed, Hd, Ld = to_dev(E, torch), to_dev(H, torch), torch.from_numpy(labels).cuda()
+    for lo in range(0, w.N, w.batch):
+        s.score_outer(Ed[lo:lo + w.batch], Hd[lo:lo + w.batch], Ld[lo:lo + w.batch])
+        o2.score(G[lo:lo + w.batch])
+    gidx = s.select(w.keep).cpu().numpy()
+    oidx2 = o2.select(w.keep)
+    al = s.scores().cpu().numpy()
+    assert np.abs(s.zhat().cpu().numpy() - o2.zhat).max() <= 1e-5
+    assert np.abs(al - o2.alpha).max() <= SCORE_TOL
+    _check_selection(gidx, oidx2, o2.alpha)
+    assert gidx.tolist() == oracle.topm_f32(al, len(gidx)).tolist()
+    # class-balanced selection on the same pass (labels came with the factors)
+    Cn = int(labels.max()) + 1
+    cidx = s.select_cb(w.keep, Cn).cpu().numpy()
+    cal = s.scores().cpu().numpy()
+    oal, _ = o2.select_cb(w.keep, labels, Cn)
+    assert np.abs(cal - oal).max() <= SCORE_TOL
+    assert cidx.tolist() == oracle.cb_select_from_alpha(cal, labels, Cn, w.keep).tolist()
+    # store-free run from the factors
+    s.set_score_store(False)
+    for lo in range(0, w.N, w.batch):
+        s.score_outer(Ed[lo:lo + w.batch], Hd[lo:lo + w.batch])
+    # (another batching on purpose, except for the staged shapes: there the order of summation follows a row's place
+    # in the staging buffer, so only equal batches give equal bits)
+    step = w.batch if name.endswith("_staged") else 211
+    for lo in range(0, w.N, step):
+        s.rescore_outer(Ed[lo:lo + step], Hd[lo:lo + step])
+    idx2 = s.select(w.keep).cpu().numpy()
+    assert np.array_equal(s.scores().cpu().numpy().view(np.uint32), al.view(np.uint32))
+    assert idx2.tolist() == gidx.tolist()
+
+
+def test_outer_end_to_end_and_errors():
+    """Both passes from factors (update, basis, score, select) against the oracle's run on the written-out rows (scores
+    as far as the conditioning of the top-k subspace allows); shape and state errors of the factored calls."""
+    B = _binding()
+    w, E, H, _, G, o, oidx = _outer_run("bf16_c24_h128")
+    s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    Ed, Hd = to_dev(E, torch), to_dev(H, torch)
+    with pytest.raises(B.SageError):                      # no basis yet
+        s.score_outer(Ed[:4], Hd[:4])
+    with pytest.raises(B.SageError):                      # classes * (features + 1) != D
+        s.fd_update_outer(Ed[:4, :23].contiguous(), Hd[:4])
+    s.fd_update_outer(Ed[:0], Hd[:0])                     # empty batch
+    for lo in range(0, w.N, w.batch):
+        s.fd_update_outer(Ed[lo:lo + w.batch], Hd[lo:lo + w.batch])
+    s.fd_basis(w.k)
+    for lo in range(0, w.N, w.batch):
+        s.score_outer(Ed[lo:lo + w.batch], Hd[lo:lo + w.batch])
+    gidx = s.select(w.keep).cpu().numpy()
+    al = s.scores().cpu().numpy()
+    assert gidx.tolist() == oracle.topm_f32(al, len(gidx)).tolist()
+    # the two top-k subspaces agree as far as the spectrum of these rows lets them (see the conditioning test above)
+    Vg = s.basis().cpu().numpy().astype(np.float64)
+    sv = np.linalg.svd(Vg @ o.V.T, compute_uv=False)
+    sin_max = float(np.sqrt(max(0.0, 1.0 - sv.min() ** 2)))
+    err = float(np.abs(al - o.alpha).max())
+    assert err <= max(SCORE_TOL, 20.0 * sin_max), (err, sin_max)

@@ -478,3 +478,52 @@ def test_sketches_merge_with_added_bounds():
     assert ev.max() <= o1.sum_delta + o2.sum_delta + 1e-6 * fro
     assert o1.sum_delta + o2.sum_delta <= fro / ell + 1e-6 * fro
 
+
+
+# ---------------------------------------------------------------- factored last-layer rows
+def test_last_layer_rows_are_the_autograd_gradient():
+    """Layout and sign of oracle.last_layer_rows against torch's autograd: the gradient of the cross-entropy of a linear
+    layer (weights C x dh row-major, then biases) for one example is (softmax - onehot) (x) [h; 1]."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(41)
+    Cn, dh, N = 5, 7, 6
+    W = torch.tensor(rng.standard_normal((Cn, dh)), dtype=torch.float64, requires_grad=True)
+    b = torch.tensor(rng.standard_normal(Cn), dtype=torch.float64, requires_grad=True)
+    Hm = rng.standard_normal((N, dh))
+    y = rng.integers(0, Cn, size=N)
+    logits = Hm @ W.detach().numpy().T + b.detach().numpy()
+    P = np.exp(logits - logits.max(axis=1, keepdims=True))
+    P /= P.sum(axis=1, keepdims=True)
+    E = P.copy()
+    E[np.arange(N), y] -= 1.0
+    rows = oracle.last_layer_rows(E.astype(np.float32), Hm.astype(np.float32))
+    assert rows.shape == (N, Cn * (dh + 1))
+    for i in range(N):
+        loss = torch.nn.functional.cross_entropy((torch.tensor(Hm[i]) @ W.T + b)[None, :], torch.tensor([int(y[i])]))
+        gW, gb = torch.autograd.grad(loss, [W, b])
+        ref = np.concatenate([gW.numpy().reshape(-1), gb.numpy()])
+        assert np.abs(rows[i] - ref).max() <= 2e-7 * max(1.0, np.abs(ref).max())
+
+
+def test_last_layer_rows_gram_closed_form_and_bf16_rounding():
+    """<g_i, g_j> = <e_i, e_j> (<h_i, h_j> + 1): exact for small-integer factors in both row types. The bf16 rounding
+    of the products against torch's own float32 -> bfloat16 conversion on random factors."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(42)
+    E = rng.integers(-3, 4, size=(9, 4)).astype(np.float32)
+    Hm = rng.integers(-3, 4, size=(9, 6)).astype(np.float32)
+    want = (E.astype(np.float64) @ E.T) * (Hm.astype(np.float64) @ Hm.T + 1.0)
+    R32 = oracle.last_layer_rows(E, Hm).astype(np.float64)
+    assert np.array_equal(R32 @ R32.T, want)
+    Rb = oracle.last_layer_rows(inputs.f32_to_bf16_bits(E), inputs.f32_to_bf16_bits(Hm))
+    Rb = inputs.bf16_bits_to_f32(Rb).astype(np.float64)
+    assert np.array_equal(Rb @ Rb.T, want)
+    # random bf16 factors: products need rounding
+    Eb = inputs.f32_to_bf16_bits(rng.standard_normal((16, 8)).astype(np.float32))
+    Hb = inputs.f32_to_bf16_bits(rng.standard_normal((16, 32)).astype(np.float32))
+    got = oracle.last_layer_rows(Eb, Hb)
+    e = torch.from_numpy(inputs.bf16_bits_to_f32(Eb))
+    h = torch.from_numpy(inputs.bf16_bits_to_f32(Hb))
+    prod = (e[:, :, None] * h[:, None, :]).reshape(16, -1)  # exact in float32
+    ref = torch.cat([prod, e], dim=1).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, ref)
