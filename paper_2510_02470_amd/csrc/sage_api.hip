@@ -664,6 +664,20 @@ static int ensure_partial(sage_ctx* c, size_t need) {
     return SAGE_OK;
 }
 
+// staging memory of the factored scoring calls
+static int ensure_stage(sage_ctx* c, size_t need) {
+    if (need <= c->stage_bytes) return SAGE_OK;
+    if (c->stage) {
+        HIPCHK(hipStreamSynchronize(c->st));
+        (void)hipFree(c->stage);
+        c->stage = nullptr;
+        c->stage_bytes = 0;
+    }
+    ALLOC(c->stage, need);
+    c->stage_bytes = need;
+    return SAGE_OK;
+}
+
 // The projection partials of R rows (R <= SCORE_CHUNK) in proj_partial; *slots = partial slots to sum.
 static int project_rows(sage_ctx* c, const RowSrc& src, int64_t R, int* slots) {
     const void* g = src.G;
@@ -671,26 +685,19 @@ static int project_rows(sage_ctx* c, const RowSrc& src, int64_t R, int* slots) {
         if (c->proj_mode != SAGE_PROJ_F32 && outer_path_ok(src.E, src.H, src.dtype, src.C, src.dh)) {
             int rc = ensure_images(c);
             if (rc != SAGE_OK) return rc;
-            ScorePlan p = score_outer_plan(R, src.dtype, src.C, src.dh, c->num_cu);
-            rc = ensure_partial(c, (size_t)(p.splits + 1) * R * c->KP);
+            rc = ensure_stage(c, outer_work_bytes(R, src.dtype, src.C));
             if (rc != SAGE_OK) return rc;
-            RUN(K_PROJECT, launch_project_outer(src.E, src.H, src.dtype, R, src.C, src.dh, c->Vimg, c->Vblk, c->KP,
-                                                c->proj_partial, p, c->st));
-            *slots = p.splits + 1;
+            ScorePlan p = score_outer_plan(R, src.dtype, src.C, src.dh, c->num_cu);
+            rc = ensure_partial(c, (size_t)(p.splits + p.bias_slots) * R * c->KP);
+            if (rc != SAGE_OK) return rc;
+            RUN(K_PROJECT, launch_project_outer(src.E, src.H, src.dtype, R, src.C, src.dh, c->stage, c->Vimg, c->Vblk,
+                                                c->KP, c->proj_partial, p, c->st));
+            *slots = p.splits + p.bias_slots;
             return SAGE_OK;
         }
         // any other shape: write the rows out and project them like a row-major batch
-        const size_t need = (size_t)R * c->d.D * (src.dtype == SAGE_BF16 ? 2 : 4);
-        if (need > c->stage_bytes) {
-            if (c->stage) {
-                HIPCHK(hipStreamSynchronize(c->st));
-                (void)hipFree(c->stage);
-                c->stage = nullptr;
-                c->stage_bytes = 0;
-            }
-            ALLOC(c->stage, need);
-            c->stage_bytes = need;
-        }
+        int rc = ensure_stage(c, (size_t)R * c->d.D * (src.dtype == SAGE_BF16 ? 2 : 4));
+        if (rc != SAGE_OK) return rc;
         RUN(K_INSERT, launch_expand_outer(src.E, src.H, src.dtype, src.C, src.dh, R, c->stage, c->d, c->st));
         g = c->stage;
     }

@@ -133,6 +133,9 @@ struct ScorePlan {
     int row_tiles;    // ceil(R / 128)
     int splits;       // split-K over D
     int64_t slabs_per_split;
+    // factored rows only: the splits form a grid of class groups x feature-window groups
+    int class_groups = 0, classes_per_group = 0, window_groups = 0, windows_per_group = 0;
+    int bias_slots = 0, classes_per_bias_slot = 0;  // ... followed by the slots of the bias columns
 };
 ScorePlan score_plan(int64_t R, const Dims& d, int num_cu);
 hipError_t launch_project(const void* G, int dtype, int64_t R, const float* Vblk, int KP, float* partial,
@@ -152,10 +155,12 @@ hipError_t launch_project_split(const void* G, int dtype, int64_t R, const void*
                                 const ScorePlan& p, const Dims& d, hipStream_t st);
 
 // The projection of factored rows (see launch_insert_outer) without storing them. Needs the images and the fp32 slabs
-// of the basis; writes p.splits + 1 partial slots (the last one holds the bias columns).
+// of the basis; writes p.splits + p.bias_slots partial slots (the last ones hold the bias columns).
 bool outer_path_ok(const void* E, const void* H, int dtype, int64_t C, int64_t dh);
 ScorePlan score_outer_plan(int64_t R, int dtype, int64_t C, int64_t dh, int num_cu);
-hipError_t launch_project_outer(const void* E, const void* H, int dtype, int64_t R, int64_t C, int64_t dh,
+// work: outer_work_bytes(R, dtype, C) bytes (receives the transposed errors)
+size_t outer_work_bytes(int64_t R, int dtype, int64_t C);
+hipError_t launch_project_outer(const void* E, const void* H, int dtype, int64_t R, int64_t C, int64_t dh, void* work,
                                 const void* img, const float* Vblk, int KP, float* partial, const ScorePlan& p,
                                 hipStream_t st);
 

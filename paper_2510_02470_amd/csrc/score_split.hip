@@ -414,26 +414,32 @@ hipError_t launch_project_split(const void* G, int dtype, int64_t R, const void*
 // A per-example gradient of a linear last layer (weights C x dh, bias C) under a loss on the logits is the outer
 // product of the logit error e_i (C values) with [h_i; 1] (dh features and a one): column c*dh + t of row i is
 // e_ic * h_it, column C*dh + c is e_ic (Method, definition of g_i, for that layer). The row is never stored: the
-// kernel below forms the row operand of window m (chunk m of KC columns, inside class m / (dh/KC)) from 128 bytes of
-// h_i and one value of e_i, rounds it as a stored row of the context's type would have been rounded (bf16: nearest
-// even; fp32: the fp32 product, then split as above) and multiplies it with the same basis images. H and E are
-// re-read by every split but stay in L2; from HBM the kernel reads the images once. The C bias columns are added by
-// project_bias_kernel into a partial slot of their own.
+// kernel below forms the row operand of a window (KC columns of class c starting at feature tw*KC) from 128 bytes of
+// h_i and the value e_ic, rounds it as a stored row of the context's type would have been rounded (bf16: nearest
+// even; fp32: the fp32 product, then split as above) and multiplies it with the same basis images. The C bias
+// columns are added by project_bias_kernel into a partial slot of their own.
+//
+// A split is a block of classes x feature windows and is walked feature window by feature window, classes inside:
+// the 128 bytes of h_i stay in registers for all classes of the split, and per window only the image and one value of
+// e per row are fetched (e comes from a transposed copy, so that the 32 rows of a tile read 32 neighbouring values).
+// From HBM the kernel reads little more than the images, once. (Walking the columns in their order instead re-reads
+// the feature rows for every class; they do not stay in L2 beside the image stream, and that variant ran at the
+// speed of the row-major kernel.)
 //
 // Work-group and wave shapes as in project_split_kernel (512 threads, 512 rows; a wave owns rows 64w .. 64w+63).
-// Every window starts on a class-aligned multiple of KC columns, so only the image of the window itself is read and
-// the ring has three slots: m in use, m+1 landed or landing, m+2 requested.
-template <typename T>
-struct OuterOp {
-    u32x4 v[4];  // 128 bytes of the feature row (this lane's pieces)
-    T e;         // the logit error of the window's class
+// Every window is a whole image, so the ring has three slots: the window's image in use, the next landed or landing,
+// the one after requested.
+struct OuterGeom {
+    int C, dh;
+    int class_groups, classes_per_group;  // split -> (class group, window group): split % class_groups, split / ...
+    int window_groups, windows_per_group;
+    int64_t et_pitch;                     // elements between classes in the transposed error matrix
 };
 
 template <int NT, typename T>
-__global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restrict__ E, const T* __restrict__ H,
-                                                               int64_t R, int C, int dh, const u32x4* __restrict__ img,
-                                                               float* __restrict__ partial, int row_tiles,
-                                                               int chunks_main, int chunks_per_split) {
+__global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restrict__ Et, const T* __restrict__ H,
+                                                               int64_t R, OuterGeom g, const u32x4* __restrict__ img,
+                                                               float* __restrict__ partial, int row_tiles) {
     constexpr int KP = NT * 32;
     constexpr int KC = 128 / (int)sizeof(T);
     constexpr int PPR = KC / 8;
@@ -446,37 +452,31 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
     const int xcd = id & 7, y = id >> 3;
     const int rt = y % row_tiles;
     const int split = (y / row_tiles) * 8 + xcd;
-    const int c0 = split * chunks_per_split;
-    int c1 = c0 + chunks_per_split;
-    if (c1 > chunks_main) c1 = chunks_main;
-    const int nv = c1 > c0 ? c1 - c0 : 0;
-    const int cpc = dh / KC;  // chunks per class
+    const int cpc = g.dh / KC;  // windows per class
+    const int kg = split % g.class_groups, tg = split / g.class_groups;
+    const int k0 = kg * g.classes_per_group;
+    int k1 = k0 + g.classes_per_group;
+    if (k1 > g.C) k1 = g.C;
+    int t0 = tg * g.windows_per_group, t1 = t0 + g.windows_per_group;
+    if (t1 > cpc) t1 = cpc;
+    if (tg >= g.window_groups) t1 = t0;  // padding splits: nothing to do, their slot is zero
+    const int nk = k1 > k0 ? k1 - k0 : 0;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
     const int64_t row0 = (int64_t)rt * 512;
-    // lane offsets from the work-group's first row, in bytes (32 bits: the launcher checks that 512 rows fit)
-    const char* hbase = reinterpret_cast<const char*>(H + row0 * dh);
-    const char* ebase = reinterpret_cast<const char*>(E + row0 * C);
-    unsigned hoff[2], eoff[2];
+    // Rows >= R repeat row R-1 for the features; the transposed errors are padded to whole row tiles. Results of such
+    // rows are not written.
+    const char* hrow[2];
+    const T* ecol[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        int64_t r = row0 + wave * 64 + t * 32 + n;
-        if (r > R - 1) r = R - 1;  // rows >= R repeat row R-1; their results are not written
-        hoff[t] = (unsigned)(r - row0) * (unsigned)dh * (unsigned)sizeof(T) + (unsigned)(PB * h);
-        eoff[t] = (unsigned)(r - row0) * (unsigned)C * (unsigned)sizeof(T);
+        const int64_t rr = row0 + wave * 64 + t * 32 + n;
+        const int64_t r = rr > R - 1 ? R - 1 : rr;
+        hrow[t] = reinterpret_cast<const char*>(H + r * g.dh) + PB * h;
+        ecol[t] = Et + rr;
     }
-    auto load_rows = [&](OuterOp<T>& a, int t, int m) __attribute__((always_inline)) {
-        const int cls = m / cpc, tw = m - cls * cpc;
-        const char* src = hbase + tw * 128 + hoff[t];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int xoff = sizeof(T) == 2 ? 32 * x : 64 * (x >> 1) + 16 * (x & 1);
-            a.v[x] = *reinterpret_cast<const u32x4*>(src + xoff);
-        }
-        a.e = *reinterpret_cast<const T*>(ebase + (size_t)cls * sizeof(T) + eoff[t]);
-    };
     int boff[KS];
 #pragma unroll
     for (int j = 0; j < KS; ++j) boff[j] = img_piece<KC>(n, (2 * j + h) & (PPR - 1));
@@ -489,16 +489,18 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[t][ct][i] = 0.f;
 
-    auto stage = [&](int c, int slot) __attribute__((always_inline)) {
-        const int cc = c > chunks_main - 1 ? chunks_main - 1 : c;  // beyond the end: repeat (never used)
-        const u32x4* src = img + (int64_t)cc * IMG + tid;
+    const int64_t n_img = (int64_t)g.C * cpc;
+    auto stage = [&](int cls, int tw, int slot) __attribute__((always_inline)) {
+        int64_t ci = (int64_t)cls * cpc + tw;
+        if (ci > n_img - 1) ci = n_img - 1;  // beyond the end: repeat (never used)
+        const u32x4* src = img + ci * IMG + tid;
 #pragma unroll
         for (int q = 0; q < IMG / 512; ++q)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + q * 512),
                                              (__attribute__((address_space(3))) void*)(lds + slot * IMG + q * 512 + wave * 64),
                                              16, 0, 0);
         if constexpr (IMG % 512 != 0) {  // IMG = 256: waves 4..7 repeat the half round (equal load counts per wave)
-            const u32x4* src2 = img + (int64_t)cc * IMG + (tid & 255);
+            const u32x4* src2 = img + ci * IMG + (tid & 255);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src2),
                                              (__attribute__((address_space(3))) void*)(lds + slot * IMG + (wave & 3) * 64), 16,
                                              0, 0);
@@ -506,11 +508,12 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
     };
     constexpr int VL = (IMG + 511) / 512;
 
+    u32x4 hv[2][4];  // this lane's pieces of the feature rows, current feature window
     // the row operand of k-step j: e * h, rounded to the row type
-    auto operand = [&](const OuterOp<T>& a, int j, u32x4& hi, u32x4& lo) __attribute__((always_inline)) {
+    auto operand = [&](int t, T eraw, int j, u32x4& hi, u32x4& lo) __attribute__((always_inline)) {
         if constexpr (sizeof(T) == 2) {
-            const float e = bf16_to_f32(a.e);
-            const u32x4 raw = a.v[j];
+            const float e = bf16_to_f32(eraw);
+            const u32x4 raw = hv[t][j];
 #pragma unroll
             for (int w = 0; w < 4; ++w)
                 hi[w] = pack_bf16(__uint_as_float(raw[w] << 16) * e, __uint_as_float(raw[w] & 0xffff0000u) * e);
@@ -518,18 +521,23 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
             u32x4 x0, x1;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                x0[w] = __float_as_uint(__uint_as_float(a.v[2 * j][w]) * a.e);
-                x1[w] = __float_as_uint(__uint_as_float(a.v[2 * j + 1][w]) * a.e);
+                x0[w] = __float_as_uint(__uint_as_float(hv[t][2 * j][w]) * eraw);
+                x1[w] = __float_as_uint(__uint_as_float(hv[t][2 * j + 1][w]) * eraw);
             }
             split8(x0, x1, hi, lo);
         }
     };
+    auto load_e = [&](T (&e)[2], int cls) __attribute__((always_inline)) {
+        const int cc = cls > g.C - 1 ? g.C - 1 : cls;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) e[t] = ecol[t][(int64_t)cc * g.et_pitch];
+    };
 
-    // One window: image m sits in slot sc; image m+2 and the rows of window m+2 are requested (rows in two bursts).
-    auto visit = [&](OuterOp<T> (&a)[2], OuterOp<T> (&afar)[2], int m, int sc) __attribute__((always_inline)) {
-        stage(m + 2, sc == 0 ? 2 : sc - 1);
-        const int m2 = m + 2 > c1 - 1 ? c1 - 1 : m + 2;
-        load_rows(afar[0], 0, m2);
+    // One window: class cls of feature window tw, its image in slot sc; the image and the errors of class cls + 2 are
+    // requested.
+    auto visit = [&](const T (&e)[2], T (&efar)[2], int cls, int tw, int sc) __attribute__((always_inline)) {
+        stage(cls + 2, tw, sc == 0 ? 2 : sc - 1);
+        load_e(efar, cls + 2);
         int baddr[KS];
 #pragma unroll
         for (int j = 0; j < KS; ++j) baddr[j] = boff[j] + sc * IMG;
@@ -542,14 +550,13 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
         for (int s = 0; s < STEPS; ++s) {
             const int j = s / (2 * NT), ct = s % (2 * NT);
             if (ct == 0) {
-                operand(a[0], j, ahi[0], alo[0]);
-                operand(a[1], j, ahi[1], alo[1]);
+                operand(0, e[0], j, ahi[0], alo[0]);
+                operand(1, e[1], j, ahi[1], alo[1]);
             }
             if (s + 1 < STEPS) {
                 const int j2 = (s + 1) / (2 * NT), ct2 = (s + 1) % (2 * NT);
                 b[(s + 1) % 2] = lds[baddr[j2] + ct2 * 32 * PPR];
             }
-            if (s == STEPS / 2) load_rows(afar[1], 1, m2);
             const u32x4 bb = b[s % 2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) acc[t][ct % NT] = mfma_bf16(ahi[t], bb, acc[t][ct % NT]);
@@ -561,35 +568,41 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        // This window issued VL image loads and 10 row loads (2 x (4 pieces + 1 scalar)), all for window m+2: with at
-        // most that many outstanding, image m+1 and the rows of window m+1 have landed. Bare barrier as above.
+        // This window issued VL image loads and 2 error loads, all for class cls + 2: with at most that many
+        // outstanding, the image and the errors of class cls + 1 have landed. Bare barrier as above.
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (10 + VL));
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (2 + VL));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    OuterOp<T> a0[2], a1[2], a2[2];
-    if (nv > 0) {
-        const int s0 = c0 % 3, s1 = (s0 + 1) % 3, s2 = (s0 + 2) % 3;
-        stage(c0, s0);
-        stage(c0 + 1, s1);
+    T e0[2], e1[2], e2[2];
+    if (nk > 0) {
+        for (int tw = t0; tw < t1; ++tw) {
+            stage(k0, tw, 0);
+            stage(k0 + 1, tw, 1);
+            load_e(e0, k0);
+            load_e(e1, k0 + 1);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            load_rows(a0[t], t, c0);
-            load_rows(a1[t], t, c0 + 1 > c1 - 1 ? c1 - 1 : c0 + 1);
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int xoff = sizeof(T) == 2 ? 32 * x : 64 * (x >> 1) + 16 * (x & 1);
+                    hv[t][x] = *reinterpret_cast<const u32x4*>(hrow[t] + tw * 128 + xoff);
+                }
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            int i = 0;
+            for (; i + 2 < nk; i += 3) {
+                visit(e0, e2, k0 + i, tw, 0);
+                visit(e1, e0, k0 + i + 1, tw, 1);
+                visit(e2, e1, k0 + i + 2, tw, 2);
+            }
+            if (i < nk) visit(e0, e2, k0 + i, tw, 0);
+            if (i + 1 < nk) visit(e1, e0, k0 + i + 1, tw, 1);
+            // every wave has passed the last window's barrier: the ring may be primed again
         }
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        int i = 0;
-        for (; i + 2 < nv; i += 3) {
-            visit(a0, a2, c0 + i, s0);
-            visit(a1, a0, c0 + i + 1, s1);
-            visit(a2, a1, c0 + i + 2, s2);
-        }
-        if (i < nv) visit(a0, a2, c0 + i, s0);
-        if (i + 1 < nv) visit(a1, a0, c0 + i + 1, s1);
     }
 
     float* out = partial + (int64_t)split * R * KP;
@@ -604,28 +617,55 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
             }
 }
 
-// The bias columns: out[r][j] = sum_c e_rc * V[j][C*dh + c] in fp32 (e is a stored value of the row type, so no
-// rounding is involved). 256 threads, 8 rows x KP outputs per work-group, 16 columns of the basis at a time in LDS.
+// Et[c][r] = E[min(r, R-1)][c] for r < Rp (Rp: R rounded up to whole row tiles). 64 x 64 tiles through LDS.
 template <typename T>
-__global__ __launch_bounds__(256) void project_bias_kernel(const T* __restrict__ E, int64_t R, int C, int64_t col0,
-                                                           const float* __restrict__ Vblk, int KP,
+__global__ __launch_bounds__(256) void transpose_errors_kernel(const T* __restrict__ E, int64_t R, int C, int64_t Rp,
+                                                               T* __restrict__ Et) {
+    __shared__ T tile[64][65];
+    const int64_t r0 = (int64_t)blockIdx.x * 64;
+    const int c0 = blockIdx.y * 64;
+    const int a = threadIdx.x & 63, b = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int rr = b + 4 * i;
+        int64_t r = r0 + rr;
+        if (r > R - 1) r = R - 1;
+        tile[rr][a] = c0 + a < C ? E[r * C + c0 + a] : (T)0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int cc = b + 4 * i;
+        if (c0 + cc < C && r0 + a < Rp) Et[(int64_t)(c0 + cc) * Rp + r0 + a] = tile[a][cc];
+    }
+}
+
+// The bias columns: out[r][j] = sum_c e_rc * V[j][C*dh + c] in fp32 (e is a stored value of the row type, so no
+// rounding is involved). 256 threads, 8 rows x KP outputs per work-group, 16 columns of the basis at a time in LDS;
+// blockIdx.y takes the classes [y * cps, (y + 1) * cps) and writes partial slot y (cps a multiple of 16).
+template <typename T>
+__global__ __launch_bounds__(256) void project_bias_kernel(const T* __restrict__ E, int64_t R, int C, int cps,
+                                                           int64_t col0, const float* __restrict__ Vblk, int KP,
                                                            float* __restrict__ out) {
     __shared__ float Vs[128][17];
     __shared__ float Es[8][16];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.x * 8;
     const int per = KP / 32;  // outputs per thread: (8 * KP) / 256
+    const int cb0 = blockIdx.y * cps;
+    int cb1 = cb0 + cps;
+    if (cb1 > C) cb1 = C;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int cb = 0; cb < C; cb += 16) {
+    for (int cb = cb0; cb < cb1; cb += 16) {
         for (int i = tid; i < KP * 16; i += 256) {
             const int j = i >> 4, cc = i & 15;
-            Vs[j][cc] = cb + cc < C ? Vblk[blk_off(col0 + cb + cc, j, KP)] : 0.f;
+            Vs[j][cc] = cb + cc < cb1 ? Vblk[blk_off(col0 + cb + cc, j, KP)] : 0.f;
         }
         if (tid < 128) {
             const int rr = tid >> 4, cc = tid & 15;
             const int64_t r = r0 + rr;
             float e = 0.f;
-            if (r < R && cb + cc < C) {
+            if (r < R && cb + cc < cb1) {
                 if constexpr (sizeof(T) == 2) e = bf16_to_f32(E[r * C + cb + cc]);
                 else e = E[r * C + cb + cc];
             }
@@ -642,42 +682,57 @@ __global__ __launch_bounds__(256) void project_bias_kernel(const T* __restrict__
         }
         __syncthreads();
     }
+    float* dst = out + (int64_t)blockIdx.y * R * KP;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         if (q < per) {
             const int o = tid + 256 * q, rr = o / KP, j = o % KP;
-            if (r0 + rr < R) out[(r0 + rr) * KP + j] = acc[q];
+            if (r0 + rr < R) dst[(r0 + rr) * KP + j] = acc[q];
         }
     }
 }
 
-// The factored projection needs whole chunks inside a class and 16-byte aligned factor rows.
+// Work space of launch_project_outer: the transposed errors, C x (row tiles * 512) values.
+size_t outer_work_bytes(int64_t R, int dtype, int64_t C) {
+    return (size_t)C * (size_t)((R + 511) / 512 * 512) * (dtype == SAGE_BF16 ? 2 : 4);
+}
+
+// The factored projection needs whole windows inside a class and 16-byte aligned feature rows.
 bool outer_path_ok(const void* E, const void* H, int dtype, int64_t C, int64_t dh) {
     const int64_t esz = dtype == SAGE_BF16 ? 2 : 4;
     const int64_t KC = 128 / esz;
-    return dh >= KC && dh % KC == 0 && C * (dh / KC) < ((int64_t)1 << 30) && 512 * dh * esz < ((int64_t)1 << 32) &&
-           512 * C * esz < ((int64_t)1 << 32) && ((uintptr_t)H) % 16 == 0 && ((uintptr_t)E) % esz == 0;
+    return dh >= KC && dh % KC == 0 && C < ((int64_t)1 << 24) && dh < ((int64_t)1 << 24) && ((uintptr_t)H) % 16 == 0 &&
+           ((uintptr_t)E) % esz == 0;
 }
 
-// splits counts the slots of the main columns; the bias columns go to slot `splits` (splits + 1 slots in all).
+// splits counts the slots of the main columns (a grid of class groups x window groups, padded to a multiple of 8);
+// the bias columns go to the bias_slots slots after them, classes_per_bias_slot classes each. Window groups are kept as small as the split count
+// allows, classes per split as many: the feature rows are read once per window of a split.
 ScorePlan score_outer_plan(int64_t R, int dtype, int64_t C, int64_t dh, int num_cu) {
     ScorePlan p;
     const int KC = dtype == SAGE_BF16 ? 64 : 32;
-    const int64_t chunks = C * (dh / KC);
+    const int64_t cpc = dh / KC;
     p.row_tiles = (int)((R + 511) / 512);
-    int64_t want = ((int64_t)num_cu + p.row_tiles - 1) / p.row_tiles;
-    int64_t s = (want + 7) / 8 * 8;
-    int64_t smax = ((chunks + 7) / 8 + 7) / 8 * 8;
-    if (s > smax) s = smax;
-    if (s < 8) s = 8;
-    if (s > 512) s = 512;
-    p.splits = (int)s;
-    p.slabs_per_split = (chunks + s - 1) / s;
+    int64_t target = (((int64_t)num_cu + p.row_tiles - 1) / p.row_tiles + 7) / 8 * 8;
+    if (target < 8) target = 8;
+    if (target > 512) target = 512;
+    int64_t wg = cpc < target ? cpc : target;
+    int64_t cg = target / wg;
+    if (cg < 1) cg = 1;
+    if (cg > C) cg = C;
+    p.windows_per_group = (int)((cpc + wg - 1) / wg);
+    p.window_groups = (int)((cpc + p.windows_per_group - 1) / p.windows_per_group);
+    p.classes_per_group = (int)((C + cg - 1) / cg);
+    p.class_groups = (int)((C + p.classes_per_group - 1) / p.classes_per_group);
+    p.splits = (p.class_groups * p.window_groups + 7) / 8 * 8;
+    p.slabs_per_split = (int64_t)p.classes_per_group * p.windows_per_group;
+    p.classes_per_bias_slot = (int)(((C + 7) / 8 + 15) / 16 * 16);  // up to 8 slots
+    p.bias_slots = (int)((C + p.classes_per_bias_slot - 1) / p.classes_per_bias_slot);
     return p;
 }
 
 template <int NT, typename T>
-static hipError_t launch_outer_t(const T* E, const T* H, int64_t R, int64_t C, int64_t dh, const void* img,
+static hipError_t launch_outer_t(const T* E, const T* H, int64_t R, int64_t C, int64_t dh, void* work, const void* img,
                                  const float* Vblk, float* partial, const ScorePlan& p, hipStream_t st) {
     constexpr int KC = 128 / (int)sizeof(T);
     constexpr size_t LDS = (size_t)3 * 2 * NT * 32 * (KC / 8) * 16;
@@ -687,31 +742,45 @@ static hipError_t launch_outer_t(const T* E, const T* H, int64_t R, int64_t C, i
                                   (int)LDS);
         attr_set = true;
     }
-    dim3 grid((unsigned)(p.row_tiles * p.splits));
-    hipLaunchKernelGGL((project_outer_kernel<NT, T>), grid, dim3(512), LDS, st, E, H, R, (int)C, (int)dh,
-                       (const u32x4*)img, partial, p.row_tiles, (int)(C * (dh / KC)), (int)p.slabs_per_split);
+    const int64_t Rp = (int64_t)p.row_tiles * 512;
+    hipLaunchKernelGGL(transpose_errors_kernel<T>, dim3((unsigned)(Rp / 64), (unsigned)((C + 63) / 64)), dim3(256), 0, st, E,
+                       R, (int)C, Rp, (T*)work);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(project_bias_kernel<T>, dim3((unsigned)((R + 7) / 8)), dim3(256), 0, st, E, R, (int)C, C * dh, Vblk,
-                       NT * 32, partial + (size_t)p.splits * R * (NT * 32));
+    OuterGeom g;
+    g.C = (int)C;
+    g.dh = (int)dh;
+    g.class_groups = p.class_groups;
+    g.classes_per_group = p.classes_per_group;
+    g.window_groups = p.window_groups;
+    g.windows_per_group = p.windows_per_group;
+    g.et_pitch = Rp;
+    dim3 grid((unsigned)(p.row_tiles * p.splits));
+    hipLaunchKernelGGL((project_outer_kernel<NT, T>), grid, dim3(512), LDS, st, (const T*)work, H, R, g, (const u32x4*)img,
+                       partial, p.row_tiles);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(project_bias_kernel<T>, dim3((unsigned)((R + 7) / 8), (unsigned)p.bias_slots), dim3(256), 0, st, E, R,
+                       (int)C, p.classes_per_bias_slot, C * dh, Vblk, NT * 32, partial + (size_t)p.splits * R * (NT * 32));
     return hipGetLastError();
 }
 
 template <int NT>
-static hipError_t launch_outer_nt(const void* E, const void* H, int dtype, int64_t R, int64_t C, int64_t dh,
+static hipError_t launch_outer_nt(const void* E, const void* H, int dtype, int64_t R, int64_t C, int64_t dh, void* work,
                                   const void* img, const float* Vblk, float* partial, const ScorePlan& p, hipStream_t st) {
     if (dtype == SAGE_BF16)
-        return launch_outer_t<NT, uint16_t>((const uint16_t*)E, (const uint16_t*)H, R, C, dh, img, Vblk, partial, p, st);
-    return launch_outer_t<NT, float>((const float*)E, (const float*)H, R, C, dh, img, Vblk, partial, p, st);
+        return launch_outer_t<NT, uint16_t>((const uint16_t*)E, (const uint16_t*)H, R, C, dh, work, img, Vblk, partial, p,
+                                            st);
+    return launch_outer_t<NT, float>((const float*)E, (const float*)H, R, C, dh, work, img, Vblk, partial, p, st);
 }
 
-hipError_t launch_project_outer(const void* E, const void* H, int dtype, int64_t R, int64_t C, int64_t dh,
+hipError_t launch_project_outer(const void* E, const void* H, int dtype, int64_t R, int64_t C, int64_t dh, void* work,
                                 const void* img, const float* Vblk, int KP, float* partial, const ScorePlan& p,
                                 hipStream_t st) {
     switch (KP / 32) {
-        case 1: return launch_outer_nt<1>(E, H, dtype, R, C, dh, img, Vblk, partial, p, st);
-        case 2: return launch_outer_nt<2>(E, H, dtype, R, C, dh, img, Vblk, partial, p, st);
-        case 4: return launch_outer_nt<4>(E, H, dtype, R, C, dh, img, Vblk, partial, p, st);
+        case 1: return launch_outer_nt<1>(E, H, dtype, R, C, dh, work, img, Vblk, partial, p, st);
+        case 2: return launch_outer_nt<2>(E, H, dtype, R, C, dh, work, img, Vblk, partial, p, st);
+        case 4: return launch_outer_nt<4>(E, H, dtype, R, C, dh, work, img, Vblk, partial, p, st);
         default: return hipErrorInvalidValue;
     }
 }
