@@ -248,6 +248,40 @@ def main():
         "roofline": roof, "kernels": kern,
     }
     del batches
+    # ---- the same path fed with the two factors of last-layer gradient rows instead of the rows (not part of value)
+    shape = {2: (10, 512), 3: (100, 512), 5: (1000, 2048)}.get(args.workload)
+    if shape is not None:
+        Cn, dh = shape
+        Ko = min(K, 8)
+        df = inputs.DeviceFactors(Cn, dh, w.dtype, seed=w.seed)
+        fac = [df.batch(b, w.batch) for b in range(1 + Ko)]
+        s = Sage(ell, D, dtype=w.dtype, max_rows=(1 + Ko) * w.batch)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        s.fd_update_outer(fac[0][0], fac[0][1])
+        s.fd_basis(k)
+        s.score_outer(fac[0][0], fac[0][1])
+        torch.cuda.synchronize()
+        ev[0].record()
+        for E, H, _ in fac[1:]:
+            s.fd_update_outer(E, H)
+        ev[1].record()
+        s.fd_basis(k)
+        ev[2].record()
+        for E, H, _ in fac[1:]:
+            s.score_outer(E, H)
+        ev[3].record()
+        torch.cuda.synchronize()
+        ro = Ko * w.batch
+        out["outer_rows"] = {
+            "classes": Cn, "features": dh, "rows_timed": ro,
+            "update_rows_per_s": ro / (ev[0].elapsed_time(ev[1]) * 1e-3),
+            "score_rows_per_s": ro / (ev[2].elapsed_time(ev[3]) * 1e-3),
+            "note": "sage_fd_update_outer / sage_score_outer: rows given as logit error (x) [features; 1]; "
+                    "the D-long rows are never stored",
+        }
+        s.close()
+        del s, fac
+        note("factored-row pass done")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -105,3 +105,56 @@ def test_update_at_full_width_properties_and_sampled_gram():
     Ct = (T @ T.T).cpu().numpy()
     off = np.abs(Ct - np.diag(np.diag(Ct)))
     assert off.max() <= 1e-5 * np.diag(Ct).max()
+
+
+def test_factored_scoring_at_full_width():
+    """sage_score_outer at the headline shape (1000 classes x 2048 features + 1000 biases = 2,049,000 columns, bf16,
+    k = 128, 2 x 1024 rows): zhat of sampled rows against fp64 on the rows the oracle writes out from the factors, and
+    all scores against the row-major entry point fed with the same rows written out on the device."""
+    from paper_2510_02470_amd.binding import Sage
+
+    w = inputs.WORKLOADS[5]
+    Cn, dh = 1000, 2048
+    assert Cn * (dh + 1) == w.D
+    df = inputs.DeviceFactors(Cn, dh, "bf16", seed=3)
+    fac = [df.batch(b, w.batch) for b in range(2)]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(777)
+    V = torch.randn((w.k, w.D), generator=g, device="cuda", dtype=torch.float32) / np.sqrt(w.D)
+    s = Sage(w.ell, w.D, dtype=w.dtype, max_rows=2 * w.batch)
+    s.set_basis(V)
+    for E, H, _ in fac:
+        s.score_outer(E, H)
+    idx = s.select(0.05).cpu().numpy()
+    alpha = s.scores().cpu().numpy()
+    zhat = s.zhat().cpu().numpy()
+    assert idx.tolist() == oracle.topm_f32(alpha, len(idx)).tolist()
+    # fp64 projection of sampled rows, written out by the oracle's definition of the rows
+    rng = np.random.default_rng(8)
+    sample = np.sort(rng.choice(2 * w.batch, size=24, replace=False))
+    Eh = torch.cat([f[0] for f in fac]).view(torch.int16).cpu().numpy().view(np.uint16)
+    Hh = torch.cat([f[1] for f in fac]).view(torch.int16).cpu().numpy().view(np.uint16)
+    Z = np.zeros((len(sample), w.k))
+    for lo in range(0, len(sample), 8):
+        rows = inputs.bf16_bits_to_f32(oracle.last_layer_rows(Eh[sample[lo:lo + 8]], Hh[sample[lo:lo + 8]]))
+        step = 1 << 18
+        for c0 in range(0, w.D, step):
+            c1 = min(w.D, c0 + step)
+            Z[lo:lo + 8] += rows[:, c0:c1].astype(np.float64) @ V[:, c0:c1].cpu().numpy().astype(np.float64).T
+        del rows
+    q = np.sqrt((Z * Z).sum(axis=1))
+    Zh = Z / q[:, None]
+    assert np.abs(zhat[sample] - Zh).max() <= 1e-5
+    # the row-major entry point on the same rows (written out on the device, rounded to bf16 like stored rows)
+    s.set_basis(V)
+    for E, H, _ in fac:
+        G = torch.empty((w.batch, w.D), dtype=torch.bfloat16, device="cuda")
+        for lo in range(0, w.batch, 128):
+            e, h = E[lo:lo + 128].float(), H[lo:lo + 128].float()
+            G[lo:lo + 128, :Cn * dh] = (e[:, :, None] * h[:, None, :]).reshape(e.shape[0], -1).to(torch.bfloat16)
+            G[lo:lo + 128, Cn * dh:] = E[lo:lo + 128]
+        s.score(G)
+        del G
+    s.select(0.05)
+    assert np.abs(s.zhat().cpu().numpy() - zhat).max() <= 1e-5
+    assert np.abs(s.scores().cpu().numpy() - alpha).max() <= 1e-4
