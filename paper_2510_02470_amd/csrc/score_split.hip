@@ -39,12 +39,17 @@ __device__ __forceinline__ unsigned pack_bf16(float x, float y) {
 // Chunk c covers columns c*KC .. c*KC + KC - 1 (KC = 64 for bf16 rows, 32 for fp32 rows: 128 bytes of a row).
 // Its image has 2*KP rows of KC bf16: image row cc < KP is hi(v_cc), image row KP + cc is lo(v_cc). A row is cut
 // into 16-byte pieces (8 columns); piece p of image row cc is stored at position swz(cc, p) of that row so that the
-// lanes of a matrix-core operand read (32 consecutive image rows, one piece each) spread over all LDS banks:
-//   KC = 64 (8 pieces, 128 B rows): swz = p ^ (cc & 7);  KC = 32 (4 pieces, 64 B rows): swz = p ^ ((cc >> 1) & 3).
+// lanes of a matrix-core operand read (32 consecutive image rows, one piece each) spread over all LDS banks. A
+// 16-byte read is served 16 lanes at a time from 64 banks of 4 bytes (256 bytes), so the 16 pieces that 16
+// consecutive image rows ask for must fall on 16 different 16-byte columns modulo 256 bytes:
+//   KC = 64 (8 pieces, 128 B rows: even and odd rows are 128 bytes apart): swz = p ^ ((cc >> 1) & 7);
+//   KC = 32 (4 pieces,  64 B rows: four rows span 256 bytes):              swz = p ^ ((cc >> 2) & 3).
+// (With swz = p ^ (cc & 7), conflict-free for 8 lanes over 32 banks, the hardware counters showed one conflict
+// cycle for every useful cycle of the operand reads.)
 template <int KC>
 __device__ __forceinline__ int img_piece(int cc, int p) {
-    if constexpr (KC == 64) return cc * 8 + (p ^ (cc & 7));
-    else return cc * 4 + (p ^ ((cc >> 1) & 3));
+    if constexpr (KC == 64) return cc * 8 + (p ^ ((cc >> 1) & 7));
+    else return cc * 4 + (p ^ ((cc >> 2) & 3));
 }
 
 // One thread writes one 16-byte piece. Vblk is the fp32 column-slab basis (KP rows); columns >= D are zero there and
