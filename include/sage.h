@@ -227,6 +227,16 @@ int sage_set_basis(sage_ctx* ctx, const float* Vt, int k);
 typedef enum { SAGE_PROJ_AUTO = 0, SAGE_PROJ_F32 = 1 } sage_proj_mode;
 int sage_set_projection_mode(sage_ctx* ctx, int mode);
 
+/*
+ * Arithmetic of the shrink's rebuild S <- Sigma' V^T = diag(w) Y^T B (Method, FD paragraph; Algorithm 1, Phase I).
+ * SAGE_MM_F32: the fp32 matrix cores. SAGE_MM_SPLIT: both factors written as three bf16 parts (24 significant bits)
+ * and the six products that matter run on the bf16 matrix cores, accumulated in fp32 -- the fp32 result to within a
+ * few 2^-24 per term, at a multiple of the fp32 matrix-core rate; used for ell >= 97 (padded sketch size 128 or 256),
+ * the fp32 path otherwise. May be changed at any time between calls.
+ */
+typedef enum { SAGE_MM_F32 = 0, SAGE_MM_SPLIT = 1 } sage_mm_mode;
+int sage_set_update_arithmetic(sage_ctx* ctx, int mode);
+
 /* View of the scores of the last sage_select: *alpha receives a DEVICE pointer to N fp32 owned by the library,
  * valid until the next scoring call; *n receives N. HOST pointers. */
 int sage_scores(sage_ctx* ctx, const float** alpha, int64_t* n);

@@ -17,7 +17,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 
 # every symbol include/sage.h declares
 EXPORTS = (
-    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
+    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_update_arithmetic", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix", "sage_probe_eig_psd", "sage_set_eig_precondition",
     "sage_profile_enable", "sage_copy_probe",
@@ -53,6 +53,7 @@ def lib():
     L.sage_fd_create_ex.argtypes = [C.POINTER(vp), i32, i64, i32, i64, vp]
     L.sage_fd_update.argtypes = [vp, vp, i64]
     L.sage_fd_merge.argtypes = [vp, vp, i64]
+    L.sage_set_update_arithmetic.argtypes = [vp, C.c_int]
     L.sage_fd_update_outer.argtypes = [vp, vp, vp, i64, i64, i64]
     L.sage_score_outer.argtypes = [vp, vp, vp, vp, i64, i64, i64]
     L.sage_rescore_outer.argtypes = [vp, vp, vp, i64, i64, i64]
@@ -150,6 +151,10 @@ class Sage:
         """Feed the rows of another sketch (fp32 device tensor, rows x D) to this one."""
         assert B_other.is_cuda and B_other.is_contiguous() and B_other.dtype == self.torch.float32 and B_other.shape[1] == self.D
         _check(self.L.sage_fd_merge(self.h, _ptr(B_other), B_other.shape[0]), "sage_fd_merge")
+
+    def set_update_arithmetic(self, split):
+        """True: the rebuild runs on the bf16 matrix cores with three-way split factors; False: fp32 matrix cores."""
+        _check(self.L.sage_set_update_arithmetic(self.h, 1 if split else 0), "sage_set_update_arithmetic")
 
     def _factors(self, E, H):
         for t in (E, H):

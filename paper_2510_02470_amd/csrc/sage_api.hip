@@ -45,6 +45,8 @@ struct sage_ctx {
     float* gram_partial_new[2] = {nullptr, nullptr};
     EigWork ew{};
     float* Mt = nullptr;
+    void* Mt3 = nullptr;   // the rebuild's coefficients split into bf16 parts (SAGE_MM_SPLIT)
+    int mm_mode = SAGE_MM_F32;
     double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps
 
     // Sweeps to launch for a shrink's eigensolve: what the last read-back solve needed, plus one. The count comes back
@@ -261,7 +263,10 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
         RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweep_cap, c->st));
     RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, LP, ell, c->cnt_top, c->fill_top, LP + c->cnt_new, LP + c->fill_new,
                                       c->Mt, c->acc, JACOBI_TOL_SHRINK, c->st));
-    RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], ell, c->Mt, c->top, LP, LP, c->d, c->st));
+    if (c->mm_mode == SAGE_MM_SPLIT && c->Mt3)
+        RUN(K_REBUILD, launch_rebuild_split(c->top, c->nw[c->cur], ell, c->Mt, c->Mt3, c->top, LP, LP, c->d, c->st));
+    else
+        RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], ell, c->Mt, c->top, LP, LP, c->d, c->st));
     post_sweeps(c);
     if (use_side(c)) c->cur ^= 1;  // two new halves alternate; with a single Gram panel there is only nw[0]
     c->fill_top = ell;
@@ -465,6 +470,7 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     CALLOC(c->ew.scal, 8 * sizeof(double));
     c->precond = false;  // see sage_set_eig_precondition
     CALLOC(c->Mt, (size_t)NP * c->d.LP * sizeof(float));
+    if (rebuild_split_ok(c->d.LP)) CALLOC(c->Mt3, rebuild_split_bytes(c->d, c->d.LP));
     CALLOC(c->acc, 8 * sizeof(double));
 #undef CALLOC
     // only the top half must start as zeros: rows of a new half beyond its fill are never read
@@ -490,7 +496,7 @@ void sage_destroy(sage_ctx* c) {
     void* ptrs[] = {c->top,     c->nw[0],    c->nw[1],  c->gram_partial, c->gram_partial_new[0], c->gram_partial_new[1],
                     c->ew.C,    c->ew.Y,     c->ew.C2,  c->ew.Y2,        c->ew.Q,    c->ew.diag0, c->ew.stat,
                     c->ew.pos,  c->ew.lam,   c->ew.known, c->ew.L, c->ew.Ld, c->ew.perm, c->ew.scal, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
-                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work, c->stage};
+                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work, c->stage, c->Mt3};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (c->st2) (void)hipStreamDestroy(c->st2);
@@ -631,6 +637,12 @@ int sage_set_projection_mode(sage_ctx* c, int mode) {
     if (!c || (mode != SAGE_PROJ_AUTO && mode != SAGE_PROJ_F32)) return SAGE_ERR_ARG;
     c->proj_mode = mode;
     c->has_basis = false;
+    return SAGE_OK;
+}
+
+int sage_set_update_arithmetic(sage_ctx* c, int mode) {
+    if (!c || (mode != SAGE_MM_F32 && mode != SAGE_MM_SPLIT)) return SAGE_ERR_ARG;
+    c->mm_mode = mode;
     return SAGE_OK;
 }
 

@@ -40,6 +40,31 @@ __device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 acc) {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// v_mfma_f32_32x32x16_bf16: acc(32x32) += a(32x16) b(16x32). Lane l supplies a[l%32][8*(l/32) .. +8] and
+// b[8*(l/32) .. +8][l%32]; acc element i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+__device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 acc) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0,
+                                                   0, 0);
+}
+
+__device__ __forceinline__ unsigned pack_bf16(float x, float y) {
+    bf16x2 h = {(__bf16)x, (__bf16)y};  // round to nearest even (v_cvt_pk_bf16_f32)
+    return __builtin_bit_cast(unsigned, h);
+}
+
+// An fp32 pair as three bf16 pairs hi + mid + lo (each the nearest bf16 of what the previous ones left): the three
+// parts carry 24 significant bits, |x - hi - mid - lo| <= 2^-26 |x|.
+__device__ __forceinline__ void split3_bf16(float x, float y, unsigned& hi, unsigned& mid, unsigned& lo) {
+    hi = pack_bf16(x, y);
+    const float rx = x - __uint_as_float(hi << 16), ry = y - __uint_as_float(hi & 0xffff0000u);
+    mid = pack_bf16(rx, ry);
+    lo = pack_bf16(rx - __uint_as_float(mid << 16), ry - __uint_as_float(mid & 0xffff0000u));
+}
+
 // ---- kernel launchers (each enqueues on `st` and returns hipGetLastError()) ---------------------------------
 // fd_insert.hip
 // copy `rows` batch rows into rows row0.. of a half buffer (half_rows rows per slab)
@@ -127,6 +152,13 @@ __host__ __device__ inline int64_t coeff_offset(int i, int m, int MP) {
 // coefficients in coeff_offset order; out has out_NP rows per slab and may be `top` itself (in place).
 hipError_t launch_rebuild(const float* top, const float* nw, int nfill, const float* Mc, float* out, int out_NP, int MP,
                           const Dims& d, hipStream_t st);
+// The same product on the bf16 matrix cores with both factors split into three bf16 parts (six products: 24-bit
+// accuracy at 2.7 times the fp32 matrix-core rate). Mc3: work space of rebuild_split_bytes(d, MP) bytes (receives the
+// split coefficients). Only for MP = 128 or 256 (rebuild_split_ok).
+bool rebuild_split_ok(int MP);
+size_t rebuild_split_bytes(const Dims& d, int MP);
+hipError_t launch_rebuild_split(const float* top, const float* nw, int nfill, const float* Mc, void* Mc3, float* out,
+                                int out_NP, int MP, const Dims& d, hipStream_t st);
 
 // score.hip
 struct ScorePlan {

@@ -19,22 +19,6 @@
 
 namespace sage {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-// v_mfma_f32_32x32x16_bf16: acc(32x32) += a(32x16) b(16x32). Lane l supplies a[l%32][8*(l/32) .. +8] and
-// b[8*(l/32) .. +8][l%32]; acc element i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
-__device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 acc) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0,
-                                                   0, 0);
-}
-
-__device__ __forceinline__ unsigned pack_bf16(float x, float y) {
-    bf16x2 h = {(__bf16)x, (__bf16)y};  // round to nearest even (v_cvt_pk_bf16_f32)
-    return __builtin_bit_cast(unsigned, h);
-}
-
 // ---- basis images -----------------------------------------------------------------------------------------
 // Chunk c covers columns c*KC .. c*KC + KC - 1 (KC = 64 for bf16 rows, 32 for fp32 rows: 128 bytes of a row).
 // Its image has 2*KP rows of KC bf16: image row cc < KP is hi(v_cc), image row KP + cc is lo(v_cc). A row is cut

@@ -263,6 +263,35 @@ def test_sketch_with_preconditioned_eigensolve(name):
     assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro
 
 
+@pytest.mark.parametrize("name", ["cfg3_small", "cfg4_small", "cfg5_small_bf16", "cfg5_k64_bf16_aligned", "long128"])
+def test_sketch_with_split_arithmetic(name):
+    """SAGE_MM_SPLIT: the shrink's matrix products on the bf16 matrix cores with both factors split into three bf16
+    parts. Same bar as the fp32 matrix cores against the oracle (long128: 60 shrink cycles)."""
+    B = _binding()
+    if name == "long128":
+        w = inputs.WORKLOADS[2].scaled(N=128 * 61 + 17, D=512, ell=128, k=64, batch=1000, r=48)
+        G = inputs.generate_numpy(w)
+        o, _ = run_oracle(w, G, mode=1, score=False)
+    else:
+        w, G, o, _ = _oracle_run(name)
+    s = B.Sage(w.ell, w.D, dtype=w.dtype)
+    s.set_update_arithmetic(True)
+    Gd = to_dev(G, torch)
+    for lo in range(0, w.N, w.batch):
+        s.fd_update(Gd[lo:lo + w.batch])
+    Bg = s.sketch().cpu().numpy()
+    A64 = (inputs.bf16_bits_to_f32(G) if G.dtype == np.uint16 else G).astype(np.float64)
+    fro = (A64 ** 2).sum()
+    st = s.stats()
+    assert st.n_shrinks == o.n_shrinks and st.fill == o.fill and st.last_sweeps < 100
+    assert cov_diff_spec_norm(Bg, o.B) / fro <= COV_TOL
+    assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro and abs(st.frob2 - fro) <= 1e-5 * fro
+    # the rows a shrink wrote are orthogonal to fp32 accuracy
+    T = Bg[:w.ell - 1].astype(np.float64)
+    Ct = T @ T.T
+    assert np.abs(Ct - np.diag(np.diag(Ct))).max() <= 1e-5 * np.diag(Ct).max()
+
+
 def test_sketch_is_deterministic():
     w = inputs.WORKLOADS[1].scaled(N=700)
     G = inputs.generate_numpy(w)
