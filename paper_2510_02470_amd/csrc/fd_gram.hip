@@ -293,6 +293,135 @@ __global__ __launch_bounds__(256, 2) void gram_cross8_kernel(const float* __rest
     }
 }
 
+// The same rectangle on the bf16 matrix cores: every fp32 value is written as three bf16 parts (24 significant bits)
+// and the six products that matter (hi*hi, hi*mid, mid*hi, hi*lo, lo*hi, mid*mid) are accumulated in fp32 -- the
+// fp32 result to a few 2^-24 per term, 6 x 32 cycles per 32 x 32 x 16 block instead of 8 x 64 on the fp32 matrix
+// cores. One slab (16 columns) is exactly one k-step. The values are split when they are staged, once per
+// work-group, so one work-group of 8 waves owns all 8 wave tiles of a column range (staging traffic is half of
+// gram_cross8_kernel's, where two work-groups stage the same slabs). LDS holds a slab as [part][k-half][row] pieces
+// of 16 bytes (8 bf16: the k-half of a row), 48 KB, double buffered; the 32 rows a matrix-core operand reads are
+// 512 contiguous bytes. The next slab is split and stored piece by piece between the six groups of matrix-core
+// instructions (all waves of a work-group run in step: conversions done in one block would leave the matrix cores
+// idle), from registers that were loaded a stage earlier and are reloaded, for the slab after next, as soon as they
+// have been consumed.
+__global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* __restrict__ top,
+                                                                   const float* __restrict__ nw, int nfill,
+                                                                   float* __restrict__ partial, int64_t slabs_total,
+                                                                   int64_t slabs_per_group) {
+    constexpr int NP = 512, LP = 256;
+    constexpr int HALF4 = LP * 4;        // 16-byte pieces of a half buffer per slab
+    constexpr int PART16 = 2 * NP;       // pieces per part: [k-half][row]
+    constexpr int STAGE16 = 3 * PART16;  // 48 KB
+    extern __shared__ u32x4 ldsx[];      // 2 * STAGE16
+
+    const int id = blockIdx.x;
+    const int xcd = id & 7;
+    const int group = (id >> 3) * 8 + xcd;
+    const int64_t s0 = (int64_t)group * slabs_per_group;
+    int64_t s1 = s0 + slabs_per_group;
+    if (s1 > slabs_total) s1 = slabs_total;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int ag = wave >> 2, bg = wave & 3;  // new rows 128*ag .. + 128, top rows 64*bg .. + 64
+    const int arow = LP + ag * 128 + l32;     // + 32 * i, i < 4
+    const int brow = bg * 64 + l32;           // + 32 * cb
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][b][e] = 0.f;
+
+    // staging: piece ps = it * 512 + tid is columns 4p .. 4p+3 of row ps >> 2 (rows >= LP: the new half)
+    const f32x4* Tv = reinterpret_cast<const f32x4*>(top);
+    const f32x4* Nv = reinterpret_cast<const f32x4*>(nw);
+    int src[4], dst8[4];  // source piece in the half buffer (-1: a new row not in use), LDS offset in 8-byte units
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int ps = it * 512 + tid, row = ps >> 2, p = ps & 3;
+        const int hr = row >= LP ? row - LP : row;
+        src[it] = (row >= LP && hr >= nfill) ? -1 : hr * 4 + p;
+        dst8[it] = (((p >> 1) * NP + row) << 1) + (p & 1);
+    }
+    f32x4 pre[4];
+    auto fetch1 = [&](int it, int64_t sl) __attribute__((always_inline)) {
+        const int64_t sc = sl < s1 ? sl : s1 - 1;  // beyond the end: repeat (never used)
+        const f32x4* base = (it >= 2 ? Nv : Tv) + sc * HALF4;
+        pre[it] = src[it] >= 0 ? base[src[it]] : f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto store1 = [&](int it, int buf) __attribute__((always_inline)) {
+        unsigned a0, a1, a2, b0, b1, b2;
+        split3_bf16(pre[it][0], pre[it][1], a0, a1, a2);
+        split3_bf16(pre[it][2], pre[it][3], b0, b1, b2);
+        uint2* d = reinterpret_cast<uint2*>(ldsx + buf * STAGE16) + dst8[it];
+        d[0] = make_uint2(a0, b0);
+        d[2 * PART16] = make_uint2(a1, b1);
+        d[4 * PART16] = make_uint2(a2, b2);
+    };
+    if (s0 < s1) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) fetch1(it, s0);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            store1(it, 0);
+            fetch1(it, s0 + 1);
+        }
+    }
+    __syncthreads();
+
+    for (int64_t s = s0; s < s1; ++s) {
+        const int cur = (int)((s - s0) & 1);
+        const u32x4* st = ldsx + cur * STAGE16 + h * NP;
+        u32x4 a[4][3], b[2][3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i][p] = st[p * PART16 + arow + 32 * i];
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) b[cb][p] = st[p * PART16 + brow + 32 * cb];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {  // smallest terms first
+            constexpr int PA[6] = {2, 0, 1, 1, 0, 0}, PB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) acc[i][cb] = mfma_bf16(a[i][PA[q]], b[cb][PB[q]], acc[i][cb]);
+            if (q < 4) {  // slab s + 1 into the other buffer, slab s + 2 on its way
+                store1(q, cur ^ 1);
+                fetch1(q, s + 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the LDS stores above must be visible, the reads of this stage are consumed; the loads for slab s + 2 stay
+        // in flight (a bare barrier: __syncthreads() would wait for them)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+
+    // tiles (ti - 4, tj) = (2*ag + i/2, bg); rows (i & 1) * 32 .. + 32 of the tile
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int tidx = (2 * ag + (i >> 1)) * 4 + bg;
+        float* out = partial + ((int64_t)group * 16 + tidx) * 4096 + (i & 1) * 2048;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int r = 8 * (e >> 2) + 4 * h + (e & 3);
+                int c = cb * 32 + l32;
+                out[r * 64 + c] = acc[i][cb][e];
+            }
+    }
+}
+
 // The (new rows) x (new rows) triangle for NP = 512: 256 rows, i.e. 8 row blocks of 32 and 36 blocks (bi >= bj) of
 // 32 x 32. Only the new rows are staged (16 KB per slab). The 36 blocks are dealt to the 4 waves, 9 each, so that a
 // wave needs at most 6 operand rows-blocks per k-step: three 3 x 3 rectangles
@@ -505,11 +634,34 @@ GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_pe
     return p;
 }
 
+GramPlan gram_plan_split(const GramPlan& cross, const Dims& d) {
+    GramPlan p = cross;
+    if (cross.mode != 1 || d.NP != 512 || cross.tiles != 16) {
+        p.tiles = 0;  // not available
+        return p;
+    }
+    p.wg_per_group = 1;
+    p.split = true;
+    return p;
+}
+
 hipError_t launch_gram(const float* top, const float* nw, int nfill, float* partial, const GramPlan& p, const Dims& d,
                        hipStream_t st) {
     if (p.tiles <= 0) return hipSuccess;
     dim3 grid((unsigned)(p.groups * p.wg_per_group));
     size_t lds = (size_t)2 * d.NP * 64;
+    if (p.mode == 1 && d.NP == 512 && p.split) {
+        constexpr int LDS_SPLIT = 2 * 3 * 2 * 512 * 16;  // two stages of [part][k-half][row] pieces
+        static bool attrs = false;
+        if (!attrs) {
+            (void)hipFuncSetAttribute((const void*)gram_cross8_split_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      LDS_SPLIT);
+            attrs = true;
+        }
+        hipLaunchKernelGGL(gram_cross8_split_kernel, grid, dim3(512), LDS_SPLIT, st, top, nw, nfill, partial, d.S,
+                           p.slabs_per_group);
+        return hipGetLastError();
+    }
     if (p.mode == 1 && d.NP == 512) {
         static bool attr8 = false;
         if (!attr8) {

@@ -38,6 +38,7 @@ struct sage_ctx {
     GramPlan gp{};        // whole lower triangle
     GramPlan gp_skip{};   // without the top x top block (known after a shrink)
     GramPlan gp_cross{};  // new rows x top rows
+    GramPlan gp_cross_split{};  // ... for the split-arithmetic kernel (tiles = 0: not available for this sketch size)
     GramPlan gp_new{};    // new rows x new rows, one work-group per CU (it shares the chip with the eigensolve)
     GramPlan gp_new2{};   // the same block with the chip to itself (context stream, when there was nothing to look ahead to)
     bool top_shrunk = false;  // top holds exactly what the last shrink wrote
@@ -236,8 +237,9 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
             gn = &c->gp_new2;
             RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial_new[c->cur], *gn, c->d, c->st));
         }
-        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, c->gp_cross, c->d, c->st));
-        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->gp_cross, c->gram_partial_new[c->cur], gn, c->ew.C, true,
+        const GramPlan& gc = c->mm_mode == SAGE_MM_SPLIT && c->gp_cross_split.tiles > 0 ? c->gp_cross_split : c->gp_cross;
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, gc, c->d, c->st));
+        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gc, c->gram_partial_new[c->cur], gn, c->ew.C, true,
                                          c->ew.known, c->d, c->st));
     } else {
         const bool skip = c->top_shrunk && c->gp_skip.t0 > 0;
@@ -416,6 +418,7 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     c->gp_skip = gram_plan(c->d, c->num_cu, 0, P >= 2, 2);
     if (P >= 2) {
         c->gp_cross = gram_plan(c->d, c->num_cu, 1, false, 2);
+        c->gp_cross_split = gram_plan_split(c->gp_cross, c->d);
         c->gp_new = gram_plan(c->d, c->num_cu, 2, false, 1);
         c->gp_new2 = gram_plan(c->d, c->num_cu, 2, false, 2);
     }
