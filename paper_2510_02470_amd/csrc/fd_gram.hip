@@ -549,6 +549,115 @@ __global__ __launch_bounds__(256, 2) void gram_new8_kernel(const float* __restri
     }
 }
 
+// The same triangle on the bf16 matrix cores with three-way split values (see gram_cross8_split_kernel): the new rows
+// of a slab are split when they are staged ([part][k-half][row] pieces, 24 KB per stage), a wave's six operand row
+// blocks are 18 LDS reads per 54 matrix-core instructions, and the next slab is split and stored between the six
+// groups of matrix-core instructions.
+template <int W>
+__device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ Nv, int nfill, float* __restrict__ partial,
+                                                     int group, int64_t s0, int64_t s1, u32x4* lds) {
+    using M = New8Map<W>;
+    constexpr int LP = 256, HALF4 = LP * 4;
+    constexpr int PART16 = 2 * LP;       // pieces per part: [k-half][row]
+    constexpr int STAGE16 = 3 * PART16;  // 24 KB
+    const int tid = threadIdx.x & 255, lane = tid & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    f32x16 acc[9];
+#pragma unroll
+    for (int q = 0; q < 9; ++q)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+
+    int src[4], dst8[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int ps = it * 256 + tid, row = ps >> 2, p = ps & 3;
+        src[it] = row >= nfill ? -1 : row * 4 + p;
+        dst8[it] = (((p >> 1) * LP + row) << 1) + (p & 1);
+    }
+    f32x4 pre[4];
+    auto fetch1 = [&](int it, int64_t sl) __attribute__((always_inline)) {
+        const int64_t sc = sl < s1 ? sl : s1 - 1;  // beyond the end: repeat (never used)
+        pre[it] = src[it] >= 0 ? Nv[sc * HALF4 + src[it]] : f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto store1 = [&](int it, int buf) __attribute__((always_inline)) {
+        unsigned a0, a1, a2, b0, b1, b2;
+        split3_bf16(pre[it][0], pre[it][1], a0, a1, a2);
+        split3_bf16(pre[it][2], pre[it][3], b0, b1, b2);
+        uint2* d = reinterpret_cast<uint2*>(lds + buf * STAGE16) + dst8[it];
+        d[0] = make_uint2(a0, b0);
+        d[2 * PART16] = make_uint2(a1, b1);
+        d[4 * PART16] = make_uint2(a2, b2);
+    };
+    if (s0 < s1) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) fetch1(it, s0);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            store1(it, 0);
+            fetch1(it, s0 + 1);
+        }
+    }
+    __syncthreads();
+
+    for (int64_t s = s0; s < s1; ++s) {
+        const int cur = (int)((s - s0) & 1);
+        const u32x4* st = lds + cur * STAGE16 + h * LP + l32;
+        u32x4 op[6][3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int o = 0; o < 6; ++o) op[o][p] = st[p * PART16 + M::rows[o] * 32];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {  // smallest terms first
+            constexpr int PA[6] = {2, 0, 1, 1, 0, 0}, PB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+            for (int q = 0; q < 9; ++q) acc[q] = mfma_bf16(op[M::pa[q]][PA[k]], op[M::pb[q]][PB[k]], acc[q]);
+            if (k < 4) {
+                store1(k, cur ^ 1);
+                fetch1(k, s + 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the LDS stores; the loads for slab s + 2 stay in flight
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+
+#pragma unroll
+    for (int q = 0; q < 9; ++q) {
+        const int bi = M::rows[M::pa[q]], bj = M::rows[M::pb[q]];
+        const int ti = bi >> 1, tj = bj >> 1;
+        float* out = partial + ((int64_t)group * 10 + ti * (ti + 1) / 2 + tj) * 4096 + (bi & 1) * 2048 + (bj & 1) * 32;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int r = 8 * (e >> 2) + 4 * h + (e & 3);
+            out[r * 64 + l32] = acc[q][e];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void gram_new8_split_kernel(const float* __restrict__ nw, int nfill,
+                                                                 float* __restrict__ partial, int64_t slabs_total,
+                                                                 int64_t slabs_per_group) {
+    extern __shared__ u32x4 ldsn[];
+    const int group = blockIdx.x;
+    int64_t s0 = (int64_t)group * slabs_per_group;
+    int64_t s1 = s0 + slabs_per_group;
+    if (s1 > slabs_total) s1 = slabs_total;
+    if (s0 > s1) s0 = s1;
+    const f32x4* Nv = reinterpret_cast<const f32x4*>(nw);
+    switch (threadIdx.x >> 6) {  // wave-uniform
+        case 0: gram_new8_split_wave<0>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+        case 1: gram_new8_split_wave<1>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+        case 2: gram_new8_split_wave<2>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+        default: gram_new8_split_wave<3>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+    }
+}
+
 // C (NP x NP, fp64, both triangles) = sum over groups of the partial tiles, in group order. With q = P/2:
 // known_top: tiles with ti < q are not summed, their block is diag(known) (the top rows are the orthogonal rows the
 // last shrink wrote, whose squared norms it recorded). Otherwise tile (ti, tj) comes from source A when its mode
@@ -634,14 +743,22 @@ GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_pe
     return p;
 }
 
-GramPlan gram_plan_split(const GramPlan& cross, const Dims& d) {
-    GramPlan p = cross;
-    if (cross.mode != 1 || d.NP != 512 || cross.tiles != 16) {
+GramPlan gram_plan_split(const GramPlan& base, const Dims& d, int groups) {
+    GramPlan p = base;
+    const bool ok = d.NP == 512 && ((base.mode == 1 && base.tiles == 16) || (base.mode == 2 && base.tiles == 10));
+    if (!ok) {
         p.tiles = 0;  // not available
         return p;
     }
     p.wg_per_group = 1;
     p.split = true;
+    if (groups > 0) {
+        int64_t gmax = ((d.S + 3) / 4 + 7) / 8 * 8;
+        if (gmax < 8) gmax = 8;
+        p.groups = groups > gmax ? (int)gmax : groups;
+        p.slabs_per_group = (d.S + p.groups - 1) / p.groups;
+        p.partial_floats = (size_t)p.groups * p.tiles * 4096;
+    }
     return p;
 }
 
@@ -669,6 +786,12 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
             attr8 = true;
         }
         hipLaunchKernelGGL(gram_cross8_kernel, grid, dim3(256), lds, st, top, nw, nfill, partial, d.S, p.slabs_per_group);
+        return hipGetLastError();
+    }
+    if (p.mode == 2 && d.NP == 512 && p.split) {
+        constexpr int LDS_SPLIT = 2 * 3 * 2 * 256 * 16;
+        hipLaunchKernelGGL(gram_new8_split_kernel, grid, dim3(256), LDS_SPLIT, st, nw, nfill, partial, d.S,
+                           p.slabs_per_group);
         return hipGetLastError();
     }
     if (p.mode == 2 && d.NP == 512 && p.wg_per_group == 1) {

@@ -38,7 +38,9 @@ struct sage_ctx {
     GramPlan gp{};        // whole lower triangle
     GramPlan gp_skip{};   // without the top x top block (known after a shrink)
     GramPlan gp_cross{};  // new rows x top rows
-    GramPlan gp_cross_split{};  // ... for the split-arithmetic kernel (tiles = 0: not available for this sketch size)
+    // ... and their counterparts for the split-arithmetic kernels (tiles = 0: not available for this sketch size)
+    GramPlan gp_cross_split{}, gp_new_split{}, gp_new2_split{};
+    const GramPlan* gp_side_used[2] = {nullptr, nullptr};  // the plan the side stream's launch into gram_partial_new[i] used
     GramPlan gp_new{};    // new rows x new rows, one work-group per CU (it shares the chip with the eigensolve)
     GramPlan gp_new2{};   // the same block with the chip to itself (context stream, when there was nothing to look ahead to)
     bool top_shrunk = false;  // top holds exactly what the last shrink wrote
@@ -230,14 +232,15 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
     if (c->new_block_ready || (c->top_shrunk && c->gp_cross.tiles > 0)) {
         // The top x top block is known. The new x new block came from the side stream, or is formed here when there
         // was nothing to look ahead to (first cycle of a call); then only new x top is left.
-        const GramPlan* gn = &c->gp_new;
+        const bool split = c->mm_mode == SAGE_MM_SPLIT;
+        const GramPlan* gn = c->gp_side_used[c->cur];
         if (c->new_block_ready) {
             HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
         } else {
-            gn = &c->gp_new2;
+            gn = split && c->gp_new2_split.tiles > 0 ? &c->gp_new2_split : &c->gp_new2;
             RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial_new[c->cur], *gn, c->d, c->st));
         }
-        const GramPlan& gc = c->mm_mode == SAGE_MM_SPLIT && c->gp_cross_split.tiles > 0 ? c->gp_cross_split : c->gp_cross;
+        const GramPlan& gc = split && c->gp_cross_split.tiles > 0 ? c->gp_cross_split : c->gp_cross;
         RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, gc, c->d, c->st));
         RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gc, c->gram_partial_new[c->cur], gn, c->ew.C, true,
                                          c->ew.known, c->d, c->st));
@@ -255,7 +258,8 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
         HIPCHK(hipEventRecord(c->ev_mark, c->st));
         HIPCHK(hipStreamWaitEvent(c->st2, c->ev_mark, 0));
         HIPCHK(insert_rows(*next, ell, 0, c->nw[o], LP, c->d, c->st2));
-        HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], c->gp_new, c->d, c->st2));
+        c->gp_side_used[o] = c->mm_mode == SAGE_MM_SPLIT && c->gp_new_split.tiles > 0 ? &c->gp_new_split : &c->gp_new;
+        HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], *c->gp_side_used[o], c->d, c->st2));
         HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
     }
     poll_sweeps(c);
@@ -418,9 +422,12 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     c->gp_skip = gram_plan(c->d, c->num_cu, 0, P >= 2, 2);
     if (P >= 2) {
         c->gp_cross = gram_plan(c->d, c->num_cu, 1, false, 2);
-        c->gp_cross_split = gram_plan_split(c->gp_cross, c->d);
         c->gp_new = gram_plan(c->d, c->num_cu, 2, false, 1);
         c->gp_new2 = gram_plan(c->d, c->num_cu, 2, false, 2);
+        c->gp_cross_split = gram_plan_split(c->gp_cross, c->d, 0);
+        c->gp_new2_split = gram_plan_split(c->gp_new2, c->d, 0);
+        // beside the eigensolve: one work-group per CU, 16 CUs left free (see gram_plan)
+        c->gp_new_split = gram_plan_split(c->gp_new2, c->d, c->num_cu > 32 ? (c->num_cu - 16) / 8 * 8 : 8);
     }
     c->fixed_cap = max_rows > 0;
     c->cap_rows = max_rows > 0 ? max_rows : 65536;

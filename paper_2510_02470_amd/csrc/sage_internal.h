@@ -93,10 +93,11 @@ struct GramPlan {
     int groups;       // split-K groups (multiple of 8)
     int64_t slabs_per_group;
     size_t partial_floats; // groups * tiles * 4096
-    bool split = false;    // mode 1, NP = 512 only: gram_cross8_split_kernel (bf16 matrix cores, three-way split values)
+    bool split = false;    // modes 1 and 2, NP = 512 only: the kernels on the bf16 matrix cores (three-way split values)
 };
-// the plan of the same block for the split-arithmetic kernel: one work-group of 8 waves per group, same partial tiles
-GramPlan gram_plan_split(const GramPlan& cross, const Dims& d);
+// The plan of the same block (mode 1 or 2) for the split-arithmetic kernels: one work-group per group, same partial
+// tiles; groups > 0 overrides the group count (tiles = 0 in the result: not available for this sketch size).
+GramPlan gram_plan_split(const GramPlan& base, const Dims& d, int groups);
 GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_per_cu);
 hipError_t launch_gram(const float* top, const float* nw, int nfill, float* partial, const GramPlan& p, const Dims& d,
                        hipStream_t st);
