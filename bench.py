@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32 = 157.3e12   # flop/s, dense fp32 matrix cores, MI355X
+PEAK_MFMA_BF16 = 2.5e15    # flop/s, dense bf16 matrix cores
 PEAK_HBM = 8.0e12          # B/s
 
 
@@ -169,12 +170,21 @@ def main():
     roof = None
     tile_flop = 2.0 * 64 * 64 * D                       # one 64x64 Gram tile over D columns
     gram_tiles = (n // 64) * (n // 64 + 1) // 2 - (ell // 64) * (ell // 64 + 1) // 2   # top x top block is known
+    # The library's default arithmetic for the shrink's products (SAGE_MM_SPLIT): fp32 values as three bf16 parts, six
+    # bf16 matrix-core products per fp32 product, where a kernel exists (rebuild: padded ell 128 or 256; the steady-state
+    # Gram blocks: padded ell 256). Those kernels are priced in executed bf16 flops against the bf16 peak.
+    LP = 32
+    while LP < ell:
+        LP *= 2
+    split_rebuild, split_gram = LP in (128, 256), LP == 256
     algo = {
-        # work per launch: (bound, executed flops or algorithmic bytes)
-        "gram": ("mfma", gram_tiles * tile_flop),          # per cycle; split over the cycle's launches below
-        "rebuild": ("mfma", 2.0 * ell * n * D),
-        "project": ("hbm", w.batch * (esz * D + 4.0 * k) + 4.0 * k * D),
-        "insert": ("hbm", (esz + 4.0) * ell * D),
+        # work per launch: (bound, executed flops or algorithmic bytes, peak)
+        "gram": ("mfma", gram_tiles * tile_flop * (6.0 if split_gram else 1.0),   # per cycle; split over its launches below
+                 PEAK_MFMA_BF16 if split_gram else PEAK_MFMA_F32),
+        "rebuild": ("mfma", 2.0 * ell * n * D * (6.0 if split_rebuild else 1.0),
+                    PEAK_MFMA_BF16 if split_rebuild else PEAK_MFMA_F32),
+        "project": ("hbm", w.batch * (esz * D + 4.0 * k) + 4.0 * k * D, PEAK_HBM),
+        "insert": ("hbm", (esz + 4.0) * ell * D, PEAK_HBM),
     }
     if not args.no_kernel_timing:
         s = Sage(ell, D, dtype=w.dtype, max_rows=(W + K) * w.batch)
@@ -206,23 +216,28 @@ def main():
                 continue
             e = {"avg_ms": ms / cnt, "launches": cnt, "total_ms": ms}
             if name in algo:
-                bound, work = algo[name]
+                bound, work, peak = algo[name]
                 if name == "gram":   # two launches per cycle (new x new block, new x top block): rate over both
                     work = work * pr["rebuild"][1] / cnt
                 rate = work / (ms / cnt * 1e-3)
                 e["bound"] = bound
                 e["achieved"] = rate / 1e12 if bound == "mfma" else rate / 1e9
                 e["unit"] = "TFLOP/s" if bound == "mfma" else "GB/s"
-                e["frac"] = rate / (PEAK_MFMA_F32 if bound == "mfma" else PEAK_HBM)
+                e["frac"] = rate / peak
+                e["peak"] = peak / (1e12 if bound == "mfma" else 1e9)
             if name in traffic:
                 e["traffic"] = traffic[name]
             kern[name] = e
         g = kern.get("rebuild")
         if g:
-            roof = {"kernel": "rebuild_kernel<8> (B[0:ell] <- diag(w) Y^T B, fp32 MFMA; the longest kernel of a cycle)",
-                    "bound": "mfma", "achieved": g["achieved"], "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
+            roof = {"kernel": ("rebuild_split_kernel (B[0:ell] <- diag(w) Y^T B; bf16 MFMA on three-way split fp32 values, "
+                               "6 bf16 products per fp32 product; the longest kernel of a cycle)") if split_rebuild else
+                              "rebuild_kernel (B[0:ell] <- diag(w) Y^T B, fp32 MFMA; the longest kernel of a cycle)",
+                    "bound": "mfma", "achieved": g["achieved"], "peak": g["peak"], "unit": "TFLOP/s",
                     "frac": g["frac"], "traffic": g.get("traffic"), "avg_launch_ms": g["avg_ms"],
-                    "launches": g["launches"], "algorithmic_flop_per_launch": 2.0 * ell * n * D}
+                    "launches": g["launches"],
+                    "algorithmic_flop_per_launch": 2.0 * ell * n * D * (6.0 if split_rebuild else 1.0),
+                    "fp32_equivalent_TFLOPs": 2.0 * ell * n * D / (g["avg_ms"] * 1e-3) / 1e12}
 
     score_bytes_row = esz * D + 4.0 * k * D / w.batch + 4.0 * k
     exec_flop_row = (gram_tiles * tile_flop + 2.0 * ell * n * D) / ell      # what the update executes per row
@@ -234,7 +249,10 @@ def main():
         "config": {"workload": w.name, "N_timed": rows, "D": D, "ell": ell, "k": k, "batch": w.batch,
                    "row_dtype": w.dtype, "keep": w.keep},
         "update_rows_per_s": upd_rows_s,
-        # executed flops (Gram without the known block + rebuild); the 8*ell*D convention counts the whole triangle
+        "update_arithmetic": ("fp32 values as three bf16 parts, 6 bf16 MFMA products per fp32 product (fp32 accuracy)"
+                              if split_rebuild else "fp32 MFMA"),
+        # fp32-equivalent flops (Gram without the known block + rebuild) against the fp32 matrix-core peak; the
+        # 8*ell*D convention counts the whole triangle
         "update_frac_mfma_peak": upd_rows_s * exec_flop_row / PEAK_MFMA_F32,
         "update_frac_mfma_peak_8ellD": upd_rows_s * 8.0 * ell * D / PEAK_MFMA_F32,
         "score_rows_per_s": sc_rows_s,

@@ -228,11 +228,13 @@ typedef enum { SAGE_PROJ_AUTO = 0, SAGE_PROJ_F32 = 1 } sage_proj_mode;
 int sage_set_projection_mode(sage_ctx* ctx, int mode);
 
 /*
- * Arithmetic of the shrink's rebuild S <- Sigma' V^T = diag(w) Y^T B (Method, FD paragraph; Algorithm 1, Phase I).
- * SAGE_MM_F32: the fp32 matrix cores. SAGE_MM_SPLIT: both factors written as three bf16 parts (24 significant bits)
- * and the six products that matter run on the bf16 matrix cores, accumulated in fp32 -- the fp32 result to within a
- * few 2^-24 per term, at a multiple of the fp32 matrix-core rate; used for ell >= 97 (padded sketch size 128 or 256),
- * the fp32 path otherwise. May be changed at any time between calls.
+ * Arithmetic of the shrink's dense products: the Gram blocks C = B B^T and the rebuild S <- Sigma' V^T = diag(w) Y^T B
+ * (Method, FD paragraph; Algorithm 1, Phase I). SAGE_MM_SPLIT (default): every fp32 value is written as three bf16
+ * parts (24 significant bits) and the six partial products that matter run on the bf16 matrix cores, accumulated in
+ * fp32 -- the fp32 result to within a few 2^-24 per term, at a multiple of the fp32 matrix-core rate. It is used where
+ * a kernel exists: the rebuild for ell >= 97 (padded sketch size 128 or 256), the Gram blocks of the steady state
+ * (new rows x top rows, new rows x new rows) for ell >= 193 (padded size 256); everything else, and everything under
+ * SAGE_MM_F32, runs on the fp32 matrix cores. May be changed at any time between calls.
  */
 typedef enum { SAGE_MM_F32 = 0, SAGE_MM_SPLIT = 1 } sage_mm_mode;
 int sage_set_update_arithmetic(sage_ctx* ctx, int mode);

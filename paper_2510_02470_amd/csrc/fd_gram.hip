@@ -310,8 +310,10 @@ __global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* 
                                                                    int64_t slabs_per_group) {
     constexpr int NP = 512, LP = 256;
     constexpr int HALF4 = LP * 4;        // 16-byte pieces of a half buffer per slab
-    constexpr int PART16 = 2 * NP;       // pieces per part: [k-half][row]
-    constexpr int STAGE16 = 3 * PART16;  // 48 KB
+    constexpr int HREG = NP + 8;         // pieces per k-half region: the rows plus 128 bytes, so that the two regions a
+                                         // staging store touches fall on different banks
+    constexpr int PART16 = 2 * HREG;     // pieces per part: [k-half][row]
+    constexpr int STAGE16 = 3 * PART16;  // 48.4 KB
     extern __shared__ u32x4 ldsx[];      // 2 * STAGE16
 
     const int id = blockIdx.x;
@@ -345,7 +347,7 @@ __global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* 
         const int ps = it * 512 + tid, row = ps >> 2, p = ps & 3;
         const int hr = row >= LP ? row - LP : row;
         src[it] = (row >= LP && hr >= nfill) ? -1 : hr * 4 + p;
-        dst8[it] = (((p >> 1) * NP + row) << 1) + (p & 1);
+        dst8[it] = (((p >> 1) * HREG + row) << 1) + (p & 1);
     }
     f32x4 pre[4];
     auto fetch1 = [&](int it, int64_t sl) __attribute__((always_inline)) {
@@ -375,7 +377,7 @@ __global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* 
 
     for (int64_t s = s0; s < s1; ++s) {
         const int cur = (int)((s - s0) & 1);
-        const u32x4* st = ldsx + cur * STAGE16 + h * NP;
+        const u32x4* st = ldsx + cur * STAGE16 + h * HREG;
         u32x4 a[4][3], b[2][3];
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
@@ -386,8 +388,8 @@ __global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* 
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {  // smallest terms first
-            constexpr int PA[6] = {2, 0, 1, 1, 0, 0}, PB[6] = {0, 2, 1, 0, 1, 0};
+        for (int q = 0; q < 6; ++q) {  // in the order the parts were read: the first group needs the hi parts only
+            constexpr int PA[6] = {0, 0, 1, 1, 0, 2}, PB[6] = {0, 1, 0, 1, 2, 0};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -558,8 +560,9 @@ __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ N
                                                      int group, int64_t s0, int64_t s1, u32x4* lds) {
     using M = New8Map<W>;
     constexpr int LP = 256, HALF4 = LP * 4;
-    constexpr int PART16 = 2 * LP;       // pieces per part: [k-half][row]
-    constexpr int STAGE16 = 3 * PART16;  // 24 KB
+    constexpr int HREG = LP + 8;         // pieces per k-half region (padded, see gram_cross8_split_kernel)
+    constexpr int PART16 = 2 * HREG;     // pieces per part: [k-half][row]
+    constexpr int STAGE16 = 3 * PART16;  // 24.4 KB
     const int tid = threadIdx.x & 255, lane = tid & 63;
     const int l32 = lane & 31, h = lane >> 5;
 
@@ -574,7 +577,7 @@ __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ N
     for (int it = 0; it < 4; ++it) {
         const int ps = it * 256 + tid, row = ps >> 2, p = ps & 3;
         src[it] = row >= nfill ? -1 : row * 4 + p;
-        dst8[it] = (((p >> 1) * LP + row) << 1) + (p & 1);
+        dst8[it] = (((p >> 1) * HREG + row) << 1) + (p & 1);
     }
     f32x4 pre[4];
     auto fetch1 = [&](int it, int64_t sl) __attribute__((always_inline)) {
@@ -603,7 +606,7 @@ __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ N
 
     for (int64_t s = s0; s < s1; ++s) {
         const int cur = (int)((s - s0) & 1);
-        const u32x4* st = lds + cur * STAGE16 + h * LP + l32;
+        const u32x4* st = lds + cur * STAGE16 + h * HREG + l32;
         u32x4 op[6][3];
 #pragma unroll
         for (int p = 0; p < 3; ++p)
@@ -611,8 +614,8 @@ __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ N
             for (int o = 0; o < 6; ++o) op[o][p] = st[p * PART16 + M::rows[o] * 32];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int k = 0; k < 6; ++k) {  // smallest terms first
-            constexpr int PA[6] = {2, 0, 1, 1, 0, 0}, PB[6] = {0, 2, 1, 0, 1, 0};
+        for (int k = 0; k < 6; ++k) {  // in the order the parts were read
+            constexpr int PA[6] = {0, 0, 1, 1, 0, 2}, PB[6] = {0, 1, 0, 1, 2, 0};
 #pragma unroll
             for (int q = 0; q < 9; ++q) acc[q] = mfma_bf16(op[M::pa[q]][PA[k]], op[M::pb[q]][PB[k]], acc[q]);
             if (k < 4) {
@@ -768,7 +771,7 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
     dim3 grid((unsigned)(p.groups * p.wg_per_group));
     size_t lds = (size_t)2 * d.NP * 64;
     if (p.mode == 1 && d.NP == 512 && p.split) {
-        constexpr int LDS_SPLIT = 2 * 3 * 2 * 512 * 16;  // two stages of [part][k-half][row] pieces
+        constexpr int LDS_SPLIT = 2 * 3 * 2 * (512 + 8) * 16;  // two stages of [part][k-half][row + pad] pieces
         static bool attrs = false;
         if (!attrs) {
             (void)hipFuncSetAttribute((const void*)gram_cross8_split_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -789,7 +792,7 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
         return hipGetLastError();
     }
     if (p.mode == 2 && d.NP == 512 && p.split) {
-        constexpr int LDS_SPLIT = 2 * 3 * 2 * 256 * 16;
+        constexpr int LDS_SPLIT = 2 * 3 * 2 * (256 + 8) * 16;
         hipLaunchKernelGGL(gram_new8_split_kernel, grid, dim3(256), LDS_SPLIT, st, nw, nfill, partial, d.S,
                            p.slabs_per_group);
         return hipGetLastError();

@@ -49,7 +49,7 @@ struct sage_ctx {
     EigWork ew{};
     float* Mt = nullptr;
     void* Mt3 = nullptr;   // the rebuild's coefficients split into bf16 parts (SAGE_MM_SPLIT)
-    int mm_mode = SAGE_MM_F32;
+    int mm_mode = SAGE_MM_SPLIT;
     double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps
 
     // Sweeps to launch for a shrink's eigensolve: what the last read-back solve needed, plus one. The count comes back

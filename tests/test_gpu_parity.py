@@ -263,10 +263,12 @@ def test_sketch_with_preconditioned_eigensolve(name):
     assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro
 
 
+@pytest.mark.parametrize("split", [True, False])
 @pytest.mark.parametrize("name", ["cfg3_small", "cfg4_small", "cfg5_small_bf16", "cfg5_k64_bf16_aligned", "long128"])
-def test_sketch_with_split_arithmetic(name):
-    """SAGE_MM_SPLIT: the shrink's matrix products on the bf16 matrix cores with both factors split into three bf16
-    parts. Same bar as the fp32 matrix cores against the oracle (long128: 60 shrink cycles)."""
+def test_sketch_with_either_arithmetic(name, split):
+    """sage_set_update_arithmetic: the shrink's matrix products on the bf16 matrix cores with both factors split into
+    three bf16 parts (SAGE_MM_SPLIT, the default) or on the fp32 matrix cores (SAGE_MM_F32), chosen explicitly. Same
+    bar against the oracle either way (long128: 60 shrink cycles)."""
     B = _binding()
     if name == "long128":
         w = inputs.WORKLOADS[2].scaled(N=128 * 61 + 17, D=512, ell=128, k=64, batch=1000, r=48)
@@ -275,7 +277,7 @@ def test_sketch_with_split_arithmetic(name):
     else:
         w, G, o, _ = _oracle_run(name)
     s = B.Sage(w.ell, w.D, dtype=w.dtype)
-    s.set_update_arithmetic(True)
+    s.set_update_arithmetic(split)
     Gd = to_dev(G, torch)
     for lo in range(0, w.N, w.batch):
         s.fd_update(Gd[lo:lo + w.batch])
