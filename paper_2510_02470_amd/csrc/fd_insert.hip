@@ -68,8 +68,21 @@ __global__ __launch_bounds__(256) void insert_outer_kernel(const T* __restrict__
     const T* e = E + r * C;
     const T* h = H + r * dh;
     float v[4];
+    if (d0 + 3 < main) {  // one division per thread: the class and feature of column d0, then step with wrap-around
+        int64_t cls = d0 / dh, t = d0 - cls * dh;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) v[c] = outer_value(e, h, d0 + c, main, dh, D);
+        for (int c = 0; c < 4; ++c) {
+            if constexpr (sizeof(T) == 2) v[c] = (float)(__bf16)(bf16_to_f32(e[cls]) * bf16_to_f32(h[t]));
+            else v[c] = e[cls] * h[t];
+            if (++t == dh) {
+                t = 0;
+                ++cls;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = outer_value(e, h, d0 + c, main, dh, D);
+    }
     float4* dst = reinterpret_cast<float4*>(B + blk_off(d0, row0 + (int)r, NP));
     *dst = make_float4(v[0], v[1], v[2], v[3]);
 }

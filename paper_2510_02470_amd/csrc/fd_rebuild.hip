@@ -267,6 +267,7 @@ __global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* __re
 #pragma unroll
                     for (int p = 0; p < 3; ++p) a[((i >> 1) + 1) & 1][t][p] = A[p * 2 * MP + (i + 2 + t) * 32];
             }
+            __builtin_amdgcn_sched_barrier(0);  // the reads go out before this pair's matrix-core instructions, not after
             const int bsel = (i >> 1) & 1;
 #pragma unroll
             for (int q = 0; q < 6; ++q) {  // smallest terms first
