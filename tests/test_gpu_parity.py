@@ -294,6 +294,35 @@ def test_sketch_with_either_arithmetic(name, split):
     assert np.abs(Ct - np.diag(np.diag(Ct))).max() <= 1e-5 * np.diag(Ct).max()
 
 
+@pytest.mark.parametrize("split", [True, False])
+def test_long_stream_at_full_sketch_size_keeps_the_fd_invariants(split):
+    """200 shrink cycles at ell = 256 (the size at which every dense kernel of the cycle has a split-arithmetic version),
+    too long for the oracle in a test: the properties that hold for any FD run are checked against the data itself --
+    0 <= A^T A - B^T B <= sum(delta) I, ell * sum(delta) <= ||A||_F^2 - ||B||_F^2, frob2 = ||A||_F^2 -- and the rows
+    the last shrink wrote are orthogonal. Rounding that piled up over the cycles would break the first one."""
+    B = _binding()
+    ell, D, cycles = 256, 2048, 200
+    w = inputs.WORKLOADS[2].scaled(N=ell * (cycles + 1) + 33, D=D, ell=ell, k=128, batch=1000, r=64)
+    G = inputs.generate_numpy(w)
+    s = B.Sage(ell, D, dtype=w.dtype)
+    s.set_update_arithmetic(split)
+    Gd = to_dev(G, torch)
+    for lo in range(0, w.N, w.batch):
+        s.fd_update(Gd[lo:lo + w.batch])
+    st = s.stats()
+    assert st.n_shrinks == cycles and st.fill == ell + 33 and st.last_sweeps < 100
+    A64 = G.astype(np.float64)
+    fro = (A64 ** 2).sum()
+    Bg = s.sketch().cpu().numpy().astype(np.float64)
+    assert abs(st.frob2 - fro) <= 1e-6 * fro
+    assert ell * st.sum_delta <= fro - (Bg ** 2).sum() + 1e-5 * fro
+    ev = np.linalg.eigvalsh(A64.T @ A64 - Bg.T @ Bg)
+    assert ev.min() >= -1e-5 * fro and ev.max() <= st.sum_delta + 1e-5 * fro, (ev.min() / fro, (ev.max() - st.sum_delta) / fro)
+    T = Bg[:ell - 1]
+    Ct = T @ T.T
+    assert np.abs(Ct - np.diag(np.diag(Ct))).max() <= 1e-5 * np.diag(Ct).max()
+
+
 def test_sketch_is_deterministic():
     w = inputs.WORKLOADS[1].scaled(N=700)
     G = inputs.generate_numpy(w)
@@ -518,6 +547,14 @@ def test_argument_and_state_errors():
     s.fd_update(g)  # invalidates the basis
     assert L.sage_score(s.h, C.c_void_p(g.data_ptr()), 1) == B.SAGE_ERR_STATE
     assert B.lib().sage_strerror(B.SAGE_ERR_STATE) == b"call not allowed in this state"
+    assert L.sage_set_update_arithmetic(s.h, 2) == B.SAGE_ERR_ARG and L.sage_set_update_arithmetic(None, 0) == B.SAGE_ERR_ARG
+    assert L.sage_set_update_arithmetic(s.h, 0) == 0 and L.sage_set_update_arithmetic(s.h, 1) == 0
+    # factored rows: classes * (features + 1) must be D = 40; null factors; negative row count
+    assert L.sage_fd_update_outer(s.h, C.c_void_p(g.data_ptr()), C.c_void_p(g.data_ptr()), 2, 4, 8) == B.SAGE_ERR_ARG
+    assert L.sage_fd_update_outer(s.h, None, C.c_void_p(g.data_ptr()), 2, 4, 9) == B.SAGE_ERR_ARG
+    assert L.sage_fd_update_outer(s.h, C.c_void_p(g.data_ptr()), C.c_void_p(g.data_ptr()), -1, 4, 9) == B.SAGE_ERR_ARG
+    assert L.sage_fd_update_outer(s.h, C.c_void_p(g.data_ptr()), C.c_void_p(g.data_ptr()), 2, 4, 9) == 0
+    assert L.sage_score_outer(s.h, C.c_void_p(g.data_ptr()), C.c_void_p(g.data_ptr()), None, 2, 4, 9) == B.SAGE_ERR_STATE
 
 
 def test_score_store_grows():
