@@ -325,6 +325,7 @@ __global__ __launch_bounds__(512, 1) void project_split_kernel(const T* __restri
         const int64_t rot = nv >= 8 ? (int64_t)(((unsigned)split * 37u) % (unsigned)(nv - 4)) + 2 : 0;  // 2 .. nv - 3
         run(c0 + rot, nv - rot);
         if (rot > 0) run(c0, rot);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing on its way to LDS when the work-group ends
     }
 
     float* out = partial + (int64_t)split * R * KP;
@@ -592,6 +593,7 @@ __global__ __launch_bounds__(512, 1) void project_outer_kernel(const T* __restri
             if (i + 1 < nk) visit(e1, e0, k0 + i + 1, tw, 1);
             // every wave has passed the last window's barrier: the ring may be primed again
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing on its way to LDS when the work-group ends
     }
 
     float* out = partial + (int64_t)split * R * KP;
