@@ -270,6 +270,14 @@ int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* 
 int sage_probe_gram_eig(sage_ctx* ctx, double* C_out, int eig, double* Y_out, double* lam_out, int* n_pad);
 
 /*
+ * Stage probe: the two Gram blocks of the steady-state cycle, (new rows) x (top rows) and (new rows) x (new rows),
+ * formed by the split-arithmetic kernels (see sage_set_update_arithmetic) from the current buffer. C_out as above
+ * (buffer-row order, both triangles); its top x top block is zero. SAGE_ERR_STATE when this sketch size has no such
+ * kernels (ell < 193). The sketch is not modified. Waits.
+ */
+int sage_probe_gram_split(sage_ctx* ctx, double* C_out, int* n_pad);
+
+/*
  * Stage probe: run the context's Jacobi eigensolve on a symmetric matrix given by the caller. C_in: DEVICE,
  * n_pad*n_pad doubles (n_pad as reported by sage_probe_gram_eig), left untouched. Y_out, lam_out as above.
  * sweep_stat_out: DEVICE, 18 doubles: [0] trace, [1+s] largest |off-diagonal| / trace met in sweep s (0 for

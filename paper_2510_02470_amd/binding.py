@@ -17,7 +17,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 
 # every symbol include/sage.h declares
 EXPORTS = (
-    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_update_arithmetic", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
+    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_update_arithmetic", "sage_probe_gram_split", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix", "sage_probe_eig_psd", "sage_set_eig_precondition",
     "sage_profile_enable", "sage_copy_probe",
@@ -54,6 +54,7 @@ def lib():
     L.sage_fd_update.argtypes = [vp, vp, i64]
     L.sage_fd_merge.argtypes = [vp, vp, i64]
     L.sage_set_update_arithmetic.argtypes = [vp, C.c_int]
+    L.sage_probe_gram_split.argtypes = [vp, vp, C.POINTER(C.c_int)]
     L.sage_fd_update_outer.argtypes = [vp, vp, vp, i64, i64, i64]
     L.sage_score_outer.argtypes = [vp, vp, vp, vp, i64, i64, i64]
     L.sage_rescore_outer.argtypes = [vp, vp, vp, i64, i64, i64]
@@ -262,6 +263,15 @@ class Sage:
         _check(self.L.sage_probe_gram_eig(self.h, _ptr(Cm), 1 if eig else 0, _ptr(Y), _ptr(lam), C.byref(npad)),
                "sage_probe_gram_eig")
         return Cm, Y, lam
+
+    def probe_gram_split(self):
+        """The new x top and new x new Gram blocks from the split-arithmetic kernels (top x top block zero)."""
+        npad = C.c_int(0)
+        _check(self.L.sage_probe_gram_split(self.h, C.c_void_p(0), C.byref(npad)), "sage_probe_gram_split")
+        n = npad.value
+        Cm = self.torch.empty((n, n), dtype=self.torch.float64, device="cuda")
+        _check(self.L.sage_probe_gram_split(self.h, _ptr(Cm), C.byref(npad)), "sage_probe_gram_split")
+        return Cm
 
     def probe_eig_matrix(self, Cm):
         n = Cm.shape[0]

@@ -216,9 +216,20 @@ int decompose(sage_ctx* c, double tol, bool full) {
         RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, 1, c->st));
         return SAGE_OK;
     }
-    const GramPlan& gp = skip ? c->gp_skip : c->gp;
-    RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, gp, c->d, c->st));
-    RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
+    if (skip && c->mm_mode == SAGE_MM_SPLIT && c->gp_cross_split.tiles > 0 && c->gp_new2_split.tiles > 0 &&
+        !c->new_block_ready && !c->pre_stored) {
+        // the two blocks that are not known, with the split-arithmetic kernels (the side stream is idle here: its
+        // partial buffer of the current half is free)
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp_cross_split, c->d, c->st));
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial_new[c->cur], c->gp_new2_split, c->d,
+                                c->st));
+        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->gp_cross_split, c->gram_partial_new[c->cur], &c->gp_new2_split,
+                                         c->ew.C, true, c->ew.known, c->d, c->st));
+    } else {
+        const GramPlan& gp = skip ? c->gp_skip : c->gp;
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, gp, c->d, c->st));
+        RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
+    }
     RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, MAX_SWEEPS, c->st));
     return SAGE_OK;
 }
@@ -633,7 +644,10 @@ static int basis_impl(sage_ctx* c, int k, bool weighted) {
                                      c->d.LP + c->cnt_new, c->d.LP + c->fill_new, c->Mt, c->acc, JACOBI_TOL_BASIS, c->st));
     c->cnt_top = c->fill_top;
     c->cnt_new = c->fill_new;
-    RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Vblk, KP, KP, c->d, c->st));
+    if (c->mm_mode == SAGE_MM_SPLIT && c->Mt3 && rebuild_split_ok(KP) && KP <= c->d.LP)
+        RUN(K_REBUILD, launch_rebuild_split(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Mt3, c->Vblk, KP, KP, c->d, c->st));
+    else
+        RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Vblk, KP, KP, c->d, c->st));
     c->k = k;
     c->KP = KP;
     rc = finish_basis(c);
@@ -1058,6 +1072,24 @@ int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, doub
             HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double),
                                     NP, hipMemcpyDeviceToDevice, c->st));
     }
+    HIPCHK(hipStreamSynchronize(c->st));
+    return SAGE_OK;
+}
+
+int sage_probe_gram_split(sage_ctx* c, double* C_out, int* n_pad) {
+    if (!c) return SAGE_ERR_ARG;
+    const int NP = c->d.NP, LP = c->d.LP, ell = c->d.ell;
+    if (n_pad) *n_pad = NP;
+    if (c->gp_cross_split.tiles <= 0 || c->gp_new2_split.tiles <= 0) return SAGE_ERR_STATE;
+    if (!C_out) return SAGE_OK;
+    int rcf = flush_pending(c);
+    if (rcf != SAGE_OK) return rcf;
+    if (c->new_block_ready || c->pre_stored) return SAGE_ERR_STATE;  // (never after flush_pending)
+    HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp_cross_split, c->d, c->st));
+    HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial_new[c->cur], c->gp_new2_split, c->d, c->st));
+    HIPCHK(launch_gram_reduce(c->gram_partial, c->gp_cross_split, c->gram_partial_new[c->cur], &c->gp_new2_split, c->ew.C,
+                              false, c->ew.known, c->d, c->st));
+    HIPCHK(launch_probe_permute(c->ew.C, C_out, NP, LP, ell, true, c->st));
     HIPCHK(hipStreamSynchronize(c->st));
     return SAGE_OK;
 }

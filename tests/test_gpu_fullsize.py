@@ -100,6 +100,16 @@ def test_update_at_full_width_properties_and_sampled_gram():
     got = Cm[np.ix_(rows, rows)]
     scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref))).max()
     assert np.abs(got - ref).max() <= 2e-5 * scale  # fp32 accumulation of ~25,000 products per split
+    # the same for the split-arithmetic kernels of the steady state (new x top and new x new blocks)
+    Cs = s.probe_gram_split().cpu().numpy()
+    rows_new = [r for r in rows if r >= ell]
+    cols = sorted(set(rows) | {1, ell - 3})
+    Bn = B[rows_new].cpu().numpy().astype(np.float64)
+    Bc = B[cols].cpu().numpy().astype(np.float64)
+    ref2 = Bn @ Bc.T
+    got2 = Cs[np.ix_(rows_new, cols)]
+    sc2 = np.sqrt(np.outer((Bn * Bn).sum(axis=1), (Bc * Bc).sum(axis=1))).max()
+    assert np.abs(got2 - ref2).max() <= 2e-5 * sc2
     # the rows a shrink wrote are mutually orthogonal (relative to their norms)
     T = B[:ell - 1].double()
     Ct = (T @ T.T).cpu().numpy()

@@ -68,6 +68,35 @@ def test_gram_and_eigensolve(ell, D, rows):
     assert abs(st.frob2 - (A64 ** 2).sum()) <= 1e-5 * (A64 ** 2).sum()
 
 
+@pytest.mark.parametrize("dtype,D,rows", [("f32", 3000, 256 + 100), ("bf16", 4104, 256 + 255), ("f32", 1000, 3 * 256 + 7)])
+def test_split_gram_blocks_match_fp64(dtype, D, rows):
+    """The Gram kernels of the steady state on the bf16 matrix cores (fp32 values as three bf16 parts), element by
+    element against fp64 dot products of the exported buffer rows: the new x top and new x new blocks with a partly
+    filled new half (rows beyond the fill are zero)."""
+    B = _binding()
+    ell = 256
+    rng = np.random.default_rng(D + rows)
+    G = (rng.standard_normal((rows, D)) * np.exp(rng.standard_normal((rows, 1)))).astype(np.float32)
+    if dtype == "bf16":
+        G = inputs.f32_to_bf16_bits(G)
+    s = B.Sage(ell, D, dtype=dtype)
+    s.fd_update(to_dev(G, torch))
+    fill = s.stats().fill
+    assert fill > ell
+    Cs = s.probe_gram_split().cpu().numpy()
+    Bs = s.sketch().cpu().numpy().astype(np.float64)
+    ref = Bs @ Bs.T
+    n = 2 * ell
+    scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref)))[:n, :n]
+    scale = np.maximum(scale, np.diag(ref).max() * 1e-6)
+    got = Cs[:n, :n]
+    assert not got[:ell, :ell].any()                                  # the known block is not formed
+    assert np.abs(got[ell:, :] - ref[ell:, :]).max() <= 3e-6 * np.diag(ref).max()
+    assert (np.abs(got[ell:, :] - ref[ell:, :]) / scale[ell:, :]).max() <= 2e-5
+    assert np.array_equal(got[ell:, :ell], got[:ell, ell:].T)         # mirrored exactly
+    assert not got[fill:, :].any() and not Cs[n:, :].any()            # unused rows and padding
+
+
 def test_eigensolve_on_given_matrices():
     """Jacobi on matrices that are hard for it: clustered and repeated eigenvalues, rank deficiency, zero."""
     B = _binding()
