@@ -238,8 +238,22 @@ int decompose(sage_ctx* c, double tol, bool full) {
 // next / next_rows: what is left of the running update call after this buffer. If a whole further cycle of rows is
 // there, they are stored in the other new half and their own Gram block is formed on the side stream while the
 // eigensolve runs on the context stream (neither needs its result, and the eigensolve leaves most of the chip idle).
+// The next ell rows of the running call into the other new half and their own Gram block, on the side stream.
+int side_ahead(sage_ctx* c, const RowSrc* next) {
+    // The other half was last read by the rebuild before last, which precedes the mark on the context stream.
+    const int LP = c->d.LP, ell = c->d.ell, o = c->cur ^ 1;
+    HIPCHK(hipEventRecord(c->ev_mark, c->st));
+    HIPCHK(hipStreamWaitEvent(c->st2, c->ev_mark, 0));
+    HIPCHK(insert_rows(*next, ell, 0, c->nw[o], LP, c->d, c->st2));
+    c->gp_side_used[o] = c->mm_mode == SAGE_MM_SPLIT && c->gp_new_split.tiles > 0 ? &c->gp_new_split : &c->gp_new;
+    HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], *c->gp_side_used[o], c->d, c->st2));
+    HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
+    return SAGE_OK;
+}
+
 int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
     const int LP = c->d.LP, ell = c->d.ell;
+    const bool ahead = use_side(c) && !c->prof && next && next_rows >= ell;
     if (c->new_block_ready || (c->top_shrunk && c->gp_cross.tiles > 0)) {
         // The top x top block is known. The new x new block came from the side stream, or is formed here when there
         // was nothing to look ahead to (first cycle of a call); then only new x top is left.
@@ -262,16 +276,11 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
         RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gp, nullptr, nullptr, c->ew.C, skip, c->ew.known, c->d, c->st));
     }
     c->new_block_ready = false;
-    const bool ahead = use_side(c) && !c->prof && next && next_rows >= ell;
     if (ahead) {
-        // The other half was last read by the rebuild before last, which precedes the mark on the context stream.
-        const int o = c->cur ^ 1;
-        HIPCHK(hipEventRecord(c->ev_mark, c->st));
-        HIPCHK(hipStreamWaitEvent(c->st2, c->ev_mark, 0));
-        HIPCHK(insert_rows(*next, ell, 0, c->nw[o], LP, c->d, c->st2));
-        c->gp_side_used[o] = c->mm_mode == SAGE_MM_SPLIT && c->gp_new_split.tiles > 0 ? &c->gp_new_split : &c->gp_new;
-        HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], *c->gp_side_used[o], c->d, c->st2));
-        HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
+        // after the Gram launches of this cycle: started beside them, the side stream's work slowed the cross block more
+        // than it gained under the eigensolve (28.4 k against 29.7 k rows/s at D = 2,049,000)
+        int rc = side_ahead(c, next);
+        if (rc != SAGE_OK) return rc;
     }
     poll_sweeps(c);
     if (c->precond)
