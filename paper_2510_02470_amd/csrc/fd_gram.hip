@@ -792,7 +792,10 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
         return hipGetLastError();
     }
     if (p.mode == 2 && d.NP == 512 && p.split) {
-        constexpr int LDS_SPLIT = 2 * 3 * 2 * (256 + 8) * 16;
+        // 49.5 KB are used; 64 KB are asked for, so that the eigensolve's pivot kernel (which asks for 100 KB for this
+        // purpose) never shares a CU with one of these work-groups when the launch runs beside it
+        constexpr int LDS_SPLIT = 65536;
+        static_assert(2 * 3 * 2 * (256 + 8) * 16 <= LDS_SPLIT, "two stages must fit");
         hipLaunchKernelGGL(gram_new8_split_kernel, grid, dim3(256), LDS_SPLIT, st, nw, nfill, partial, d.S,
                            p.slabs_per_group);
         return hipGetLastError();
