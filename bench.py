@@ -283,6 +283,7 @@ def main():
         for E, H, _ in fac[1:]:
             s.fd_update_outer(E, H)
         ev[1].record()
+        sweeps_outer = s.stats().last_sweeps   # (waits for the update; the basis call below starts its own count)
         s.fd_basis(k)
         ev[2].record()
         for E, H, _ in fac[1:]:
@@ -294,7 +295,7 @@ def main():
             "classes": Cn, "features": dh, "rows_timed": ro,
             "update_rows_per_s": ro / (ev[0].elapsed_time(ev[1]) * 1e-3),
             "score_rows_per_s": ro / (ev[2].elapsed_time(ev[3]) * 1e-3),
-            "jacobi_sweeps_last": s.stats().last_sweeps,   # these rows have another spectrum than the row-major stream's
+            "jacobi_sweeps_last": sweeps_outer,   # these rows have another spectrum than the row-major stream's
             "note": "sage_fd_update_outer / sage_score_outer: rows given as logit error (x) [features; 1]; "
                     "the D-long rows are never stored",
         }
