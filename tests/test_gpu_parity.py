@@ -682,6 +682,7 @@ _OUTER_CASES = {
     "bf16_c40_h64_k128": ("bf16", 40, 64, 1100, 1100, 130, 128),
     "bf16_c8_h72_staged": ("bf16", 8, 72, 600, 250, 32, 20),
     "f32_c33_h96_k64": ("f32", 33, 96, 640, 513, 80, 64),
+    "bf16_c10_h64_one_call": ("bf16", 10, 64, 4500, 4500, 32, 16),   # more rows per call than one projection launch takes
 }
 _OUTER_RUNS = {}
 
