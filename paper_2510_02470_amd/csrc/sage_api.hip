@@ -277,8 +277,9 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
     }
     c->new_block_ready = false;
     if (ahead) {
-        // after the Gram launches of this cycle: started beside them, the side stream's work slowed the cross block more
-        // than it gained under the eigensolve (28.4 k against 29.7 k rows/s at D = 2,049,000)
+        // after the Gram launches of this cycle: started beside them, the side stream's work (all of it, or the insert
+        // alone) slowed the cross block more than it gained under the eigensolve (28.4 k against 29.7 k rows/s at
+        // D = 2,049,000, both ways)
         int rc = side_ahead(c, next);
         if (rc != SAGE_OK) return rc;
     }
