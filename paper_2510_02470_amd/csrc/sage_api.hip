@@ -447,7 +447,8 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
         c->gp_new2 = gram_plan(c->d, c->num_cu, 2, false, 2);
         c->gp_cross_split = gram_plan_split(c->gp_cross, c->d, 0);
         c->gp_new2_split = gram_plan_split(c->gp_new2, c->d, 0);
-        // beside the eigensolve: one work-group per CU, 16 CUs left free (see gram_plan)
+        // beside the eigensolve: one work-group per CU, 16 CUs left free (see gram_plan); 64, 120 and 240 work-groups
+        // gave the same update rate, 480 a lower one
         c->gp_new_split = gram_plan_split(c->gp_new2, c->d, c->num_cu > 32 ? (c->num_cu - 16) / 8 * 8 : 8);
     }
     c->fixed_cap = max_rows > 0;
