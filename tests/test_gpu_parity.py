@@ -352,6 +352,39 @@ def test_long_stream_at_full_sketch_size_keeps_the_fd_invariants(split):
     assert np.abs(Ct - np.diag(np.diag(Ct))).max() <= 1e-5 * np.diag(Ct).max()
 
 
+@pytest.mark.parametrize("D,ell,k", [(3, 2, 1), (1, 2, 1), (17, 8, 3), (40, 33, 5)])
+def test_tiny_and_rank_deficient_shapes(D, ell, k):
+    """Fewer columns than buffer rows (the Gram matrix is singular in every cycle), a single column, a row count just
+    above a padding boundary: sketch covariance, scores and selection against the oracle."""
+    B = _binding()
+    rng = np.random.default_rng(100 * D + ell)
+    N = 23 * ell + 5
+    G = (rng.standard_normal((N, D)) * np.exp(0.5 * rng.standard_normal((N, 1)))).astype(np.float32)
+    G[::7] *= 3.0
+    o = Oracle(ell, D, 1)
+    s = B.Sage(ell, D)
+    Gd = torch.from_numpy(G).cuda()
+    step = 3 * ell + 1
+    for lo in range(0, N, step):
+        o.update(G[lo:lo + step])
+        s.fd_update(Gd[lo:lo + step])
+    fro = (G.astype(np.float64) ** 2).sum()
+    st = s.stats()
+    assert st.n_shrinks == o.n_shrinks and st.fill == o.fill
+    assert cov_diff_spec_norm(s.sketch().cpu().numpy(), o.B) / fro <= COV_TOL
+    assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro
+    kk = min(k, D)
+    V = np.linalg.qr(rng.standard_normal((D, kk)))[0].T.astype(np.float32)      # a given orthonormal basis
+    s.set_basis(torch.from_numpy(np.ascontiguousarray(V)).cuda())
+    o.set_basis(V.astype(np.float64))
+    s.score(Gd)
+    o.score(G)
+    gidx = s.select(0.2).cpu().numpy()
+    oidx = o.select(0.2)
+    assert np.abs(s.scores().cpu().numpy() - o.alpha).max() <= SCORE_TOL
+    _check_selection(gidx, oidx, o.alpha)
+
+
 def test_sketch_is_deterministic():
     w = inputs.WORKLOADS[1].scaled(N=700)
     G = inputs.generate_numpy(w)
