@@ -385,6 +385,39 @@ def test_tiny_and_rank_deficient_shapes(D, ell, k):
     _check_selection(gidx, oidx, o.alpha)
 
 
+def test_any_cut_of_the_stream_into_calls_gives_the_same_sketch_quality():
+    """The update's state machine (a shrink deferred to the next call, the side stream's look-ahead, a buffer that fills
+    up exactly at a call's end, single rows) under call sizes around ell = 128: every cut must meet the covariance bar
+    against the oracle, whose result does not depend on the cut."""
+    B = _binding()
+    ell, D = 128, 700
+    w = inputs.WORKLOADS[3].scaled(N=ell * 9 + 11, D=D, ell=ell, k=32, batch=ell, r=40)
+    G = inputs.generate_numpy(w)
+    o, _ = run_oracle(w, G, mode=1, score=False)
+    fro = (G.astype(np.float64) ** 2).sum()
+    Gd = to_dev(G, torch)
+    cuts = [[1, 127, 128, 129, 255, 1, 256, 257, 3, 2 * ell - 1, 1, 1, ell],   # then the rest in one call
+            [ell] * 9,
+            [w.N],
+            [5 * ell, 1, ell - 1, 2 * ell + 1]]
+    for sizes in cuts:
+        s = B.Sage(ell, D, dtype=w.dtype)
+        lo = 0
+        for n in sizes:
+            if lo >= w.N:
+                break
+            s.fd_update(Gd[lo:lo + n])
+            lo += n
+            if n == 1:
+                s.stats()          # a reader between calls: forces the deferred shrink
+        if lo < w.N:
+            s.fd_update(Gd[lo:])
+        st = s.stats()
+        assert st.n_shrinks == o.n_shrinks and st.fill == o.fill and st.rows_seen == w.N, sizes
+        assert cov_diff_spec_norm(s.sketch().cpu().numpy(), o.B) / fro <= COV_TOL, sizes
+        assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro and abs(st.frob2 - fro) <= 1e-5 * fro, sizes
+
+
 def test_sketch_is_deterministic():
     w = inputs.WORKLOADS[1].scaled(N=700)
     G = inputs.generate_numpy(w)
