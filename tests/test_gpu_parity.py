@@ -418,6 +418,43 @@ def test_any_cut_of_the_stream_into_calls_gives_the_same_sketch_quality():
         assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro and abs(st.frob2 - fro) <= 1e-5 * fro, sizes
 
 
+def test_cuts_at_full_sketch_size_agree_with_each_other():
+    """The same at ell = 256, where the split-arithmetic Gram kernels and both of their plans (beside the eigensolve,
+    chip to itself) are in play and the oracle is too slow for a test: the sketch does not depend on how the stream is
+    cut into calls, so every cut must give the covariance of the one-call run (to rounding), and the FD bound holds."""
+    B = _binding()
+    ell, D = 256, 1500
+    w = inputs.WORKLOADS[3].scaled(N=ell * 7 + 19, D=D, ell=ell, k=64, batch=ell, r=60)
+    G = inputs.generate_numpy(w)
+    A64 = G.astype(np.float64)
+    fro = (A64 ** 2).sum()
+    Gd = to_dev(G, torch)
+    cuts = [[w.N], [ell] * 7, [1, 255, 256, 257, 511, 1, 2, 3 * ell], [3 * ell + 1, 1, 1, ell - 2]]
+    ref = None
+    for sizes in cuts:
+        s = B.Sage(ell, D, dtype=w.dtype)
+        lo = 0
+        for n in sizes:
+            if lo >= w.N:
+                break
+            s.fd_update(Gd[lo:lo + n])
+            lo += n
+            if n == 1:
+                s.stats()
+        if lo < w.N:
+            s.fd_update(Gd[lo:])
+        st = s.stats()
+        Bg = s.sketch().cpu().numpy()
+        assert st.n_shrinks == 6 and st.fill == ell + 19 and abs(st.frob2 - fro) <= 1e-6 * fro, sizes
+        if ref is None:
+            ref = (Bg, st.sum_delta)
+            ev = np.linalg.eigvalsh(A64.T @ A64 - Bg.astype(np.float64).T @ Bg.astype(np.float64))
+            assert ev.min() >= -1e-5 * fro and ev.max() <= st.sum_delta + 1e-5 * fro
+        else:
+            assert cov_diff_spec_norm(Bg, ref[0]) / fro <= 1e-5, sizes
+            assert abs(st.sum_delta - ref[1]) <= 1e-6 * fro, sizes
+
+
 def test_sketch_is_deterministic():
     w = inputs.WORKLOADS[1].scaled(N=700)
     G = inputs.generate_numpy(w)
