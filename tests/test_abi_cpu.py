@@ -60,3 +60,15 @@ def test_workload_recipes():
     x = np.array([1.0, 1.00390625, 1.01171875, -3.0e-5], dtype=np.float32)
     h = inputs.f32_to_bf16_bits(x)
     assert h.tolist() == [0x3F80, 0x3F80, 0x3F82, 0xB7FC]  # ties to even, then plain rounding
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message (this build runs on one GPU)."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and not r.stdout.strip()
