@@ -262,6 +262,19 @@ int sage_stats(sage_ctx* ctx, sage_stats_t* out);
 int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* hip_stream);
 
 /*
+ * sage_topm for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. Same arguments and result as sage_topm, but the work space (a histogram, the
+ * select state and two counters per block of 2048 keys, 67 KB in all) is a fixed array inside the library, one copy
+ * per GPU, held until the process ends; the call allocates and frees nothing and does not wait: the work is enqueued
+ * on hip_stream and out_idx is complete when that stream reaches the end of it. N > SAGE_TOPM_STATIC_MAX_N gives
+ * SAGE_ERR_CAPACITY. All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race; calls on one stream, or otherwise ordered, are safe -- every call clears what it needs
+ * cleared with its own first kernel.
+ */
+#define SAGE_TOPM_STATIC_MAX_N 16777216
+int sage_topm_static(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* hip_stream);
+
+/*
  * Stage probes for tests: run the Gram of the current buffer (C_out: DEVICE, n_pad*n_pad doubles, row-major,
  * n_pad returned in *n_pad) and, if eig != 0, the Jacobi eigensolve of it (Y_out: DEVICE n_pad*n_pad doubles
  * with eigenvectors in columns, lam_out: DEVICE n_pad doubles, unsorted). Any output pointer may be NULL.

@@ -19,7 +19,7 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 EXPORTS = (
     "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_update_arithmetic", "sage_probe_gram_split", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
-    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_probe_gram_eig", "sage_probe_eig_matrix", "sage_probe_eig_psd", "sage_set_eig_precondition",
+    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_topm_static", "sage_probe_gram_eig", "sage_probe_eig_matrix", "sage_probe_eig_psd", "sage_set_eig_precondition",
     "sage_profile_enable", "sage_copy_probe",
     "sage_profile_read", "sage_strerror",
 )
@@ -78,6 +78,7 @@ def lib():
     L.sage_scores_export.argtypes = [vp, vp]
     L.sage_stats.argtypes = [vp, C.POINTER(SageStats)]
     L.sage_topm.argtypes = [vp, i64, i64, vp, vp]
+    L.sage_topm_static.argtypes = [vp, i64, i64, vp, vp]
     L.sage_probe_gram_eig.argtypes = [vp, vp, i32, vp, vp, C.POINTER(i32)]
     L.sage_probe_eig_matrix.argtypes = [vp, vp, vp, vp, vp]
     L.sage_probe_eig_psd.argtypes = [vp, vp, vp, vp, vp]
@@ -324,4 +325,19 @@ def topm(alpha, m):
     out = torch.empty(max(int(m), 1), dtype=torch.int64, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     _check(lib().sage_topm(_ptr(alpha), alpha.numel(), int(m), _ptr(out), C.c_void_p(stream)), "sage_topm")
+    return out[: int(m)]
+
+
+TOPM_STATIC_MAX_N = 16777216  # SAGE_TOPM_STATIC_MAX_N
+
+
+def topm_static(alpha, m, out):
+    """sage_topm_static: as topm, into the caller's int64 tensor, without allocating and without waiting."""
+    import torch
+
+    assert alpha.is_cuda and alpha.dtype == torch.float32 and alpha.is_contiguous()
+    assert out.is_cuda and out.dtype == torch.int64 and out.is_contiguous() and out.numel() >= int(m)
+    stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().sage_topm_static(_ptr(alpha), alpha.numel(), int(m), _ptr(out), C.c_void_p(stream)),
+           "sage_topm_static")
     return out[: int(m)]
