@@ -18,7 +18,11 @@
  *   - ell is the sketch size; the buffer holds n = 2*ell rows; k is the rank of the scoring basis; the example
  *     index of a scored row is its 0-based arrival order within the scoring pass.
  *   - Every call returns 0 on success or a negative sage_status; nothing throws. Non-finite input is not
- *     detected and gives unspecified (but memory-safe) results.
+ *     detected and gives unspecified (but memory-safe) results, unless sage_set_debug_checks is on.
+ *   - A call that fails with SAGE_ERR_ARG, SAGE_ERR_STATE, SAGE_ERR_CAPACITY or SAGE_ERR_ALLOC leaves the context
+ *     as it was. A call that fails with SAGE_ERR_HIP (a runtime call or a kernel launch failed after part of the
+ *     call's work was enqueued) leaves it poisoned: every later call on it returns SAGE_ERR_STATE; only
+ *     sage_destroy is still allowed.
  */
 #ifndef SAGE_H
 #define SAGE_H
@@ -55,6 +59,11 @@ typedef struct {
     int last_sweeps;     /* Jacobi sweeps used by the most recent eigensolve (100 + the sweeps launched if they did
                             not reach the tolerance; the next solves then launch the full number) */
     int fill;            /* buffer rows in use, 0..2*ell-1 */
+    int64_t n_unconverged; /* eigensolves so far (shrinks and bases) that ended above their tolerance: sticky. Such a
+                            shrink is still a valid FD step (the rows are rotated by an exactly orthogonal matrix and
+                            damped; the Gram block the next cycle takes as known includes what was left off the
+                            diagonal), but its delta is not exactly sigma_ell^2 */
+    double last_offdiag; /* largest |off-diagonal| / trace the most recent eigensolve left */
 } sage_stats_t;
 
 /* ---- the five calls of the path --------------------------------------------------------------------------- */
@@ -95,7 +104,9 @@ int sage_fd_update(sage_ctx* ctx, const void* G_batch, int64_t rows);
 /*
  * Freeze the sketch (Algorithm 1, "Freeze S for scoring") and form the scoring basis: the top-k right singular
  * vectors of the buffer as it stands (filled rows and zero rows; no shrink; the sketch is left unchanged).
- * A direction whose sigma_j^2 <= 2*ell * 2^-23 * sigma_1^2 is returned as the zero vector. 1 <= k <= ell-1.
+ * A direction whose sigma_j^2 <= 2*ell * 2^-23 * sigma_1^2 is returned as the zero vector.
+ * 1 <= k <= min(ell-1, 128) (SAGE_ERR_ARG otherwise; 128 is this library's limit: the score kernels keep two
+ * coordinates per lane).
  * Resets the scoring pass (row count, consensus sum, score store). Asynchronous.
  */
 int sage_fd_basis(sage_ctx* ctx, int k);
@@ -133,9 +144,11 @@ int sage_select(sage_ctx* ctx, double keep_rate, int64_t* out_idx, int64_t cap, 
  *
  * sage_select_cb: for every class c, zbar_c = mean of zhat over its rows, u_c = zbar_c / ||zbar_c||_2 (0 if the sum is 0),
  * alpha_i = <zhat_i, u_c(i)> clamped to [-1, 1] (-0 stored as +0), and the k_c rows of the class that are greatest under
- * (alpha descending, index ascending) are kept, with k_c = floor(keep_rate * N_c + 0.5) -- the paper leaves the k_c
- * open; this takes the same rate in every class, so that sum(k_c) is the subset size. All kept indices are written in
- * ascending order. out_idx: DEVICE, room for `cap` int64 (SAGE_ERR_CAPACITY if sum(k_c) > cap); out_m: HOST, receives
+ * (alpha descending, index ascending) are kept. The paper asks for sum_c k_c = k and leaves the k_c open; here the
+ * subset size is the plain selection's m = floor(keep_rate * N + 0.5), class c gets floor(keep_rate * N_c), and the rows
+ * still missing from m go one each to the classes with the largest fractional part of keep_rate * N_c (equal parts:
+ * the lower class first) that are not yet full -- proportional budgets that sum to m exactly. All kept indices are
+ * written in ascending order. out_idx: DEVICE, room for `cap` int64 (SAGE_ERR_CAPACITY if sum(k_c) > cap); out_m: HOST, receives
  * sum(k_c). 1 <= n_classes <= 65536. A label outside [0, n_classes) gives SAGE_ERR_ARG. Waits for the stream.
  * sage_scores / sage_scores_export then give these class-wise scores. Class sums are accumulated in 64-bit fixed
  * point (2^-40 resolution), so the result does not depend on the order in which the device adds.
@@ -299,19 +312,6 @@ int sage_probe_gram_split(sage_ctx* ctx, double* C_out, int* n_pad);
 int sage_probe_eig_matrix(sage_ctx* ctx, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out);
 
 /*
- * The shrink's eigensolve route (Method, FD paragraph: the SVD of the buffer, here through its Gram matrix): with
- * on != 0 the positive semi-definite Gram matrix is first put through one Cholesky step (C + eps I = L L^T with the
- * diagonal sorted, Jacobi on L^T L, eigenvectors L W (Lambda + eps I)^{-1/2}), which saves two Jacobi sweeps of seven at
- * n = 512; with on = 0 (the default) Jacobi runs on the Gram matrix itself. On an MI355X the factorisation costs about
- * what the two sweeps save once the side stream's work is counted, so it is off unless asked for. The basis of
- * sage_fd_basis always takes the plain route. ell >= 32 only (on is ignored below that).
- * sage_probe_eig_psd: that route on a given positive semi-definite n_pad x n_pad matrix (DEVICE, row-major), shrink
- * tolerance; outputs as sage_probe_eig_matrix (eigenvector columns of eigenvalues near 0 are not meaningful).
- */
-int sage_set_eig_precondition(sage_ctx* ctx, int on);
-int sage_probe_eig_psd(sage_ctx* ctx, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out);
-
-/*
  * A plain device-to-device copy kernel of `bytes` bytes (16 bytes per work-item; bytes and both DEVICE pointers
  * multiples of 16), asynchronous on hip_stream. Harnesses run it under a profiler to learn what the memory-traffic
  * counters report for a known amount of traffic (bytes read, bytes written), and scale the readings of the path's
@@ -328,6 +328,35 @@ int sage_copy_probe(void* dst, const void* src, int64_t bytes, void* hip_stream)
  */
 int sage_profile_enable(sage_ctx* ctx, int on);
 int sage_profile_read(sage_ctx* ctx, int which, double* ms, int64_t* launches);
+
+/*
+ * How many Jacobi sweeps a shrink's eigensolve may use (Method, FD paragraph: the SVD of the buffer). Sweeps are
+ * enqueued ahead of time, and a sweep that finds the matrix already diagonal to tolerance returns at once, but its
+ * launches still cost time (about 50 us per sweep at ell = 256). SAGE_SWEEPS_ADAPTIVE (default): as many sweeps as
+ * the most demanding of the last eight solves whose count has come back needed, plus two; a solve that still ends above the tolerance is
+ * counted in sage_stats_t.n_unconverged (and the next 64 solves get every sweep); such a shrink remains a valid step,
+ * see there. SAGE_SWEEPS_ALL: always the full 14 sweeps, for streams whose spectrum may change abruptly from one
+ * cycle to the next: no solve ends early for want of sweeps, at about 4% of the update rate at ell = 256.
+ * sage_fd_basis always has every sweep. May be changed between calls.
+ */
+typedef enum { SAGE_SWEEPS_ADAPTIVE = 0, SAGE_SWEEPS_ALL = 1 } sage_sweep_policy;
+int sage_set_sweep_policy(sage_ctx* ctx, int policy);
+
+/*
+ * Debug checks of caller data (off by default: they cost a pass over the batch and a wait). With on != 0,
+ * sage_fd_update, sage_fd_merge, sage_fd_update_outer, sage_score, sage_score_labeled and sage_score_outer first
+ * scan their batch (the factors, for the factored calls) and return SAGE_ERR_ARG, leaving the context as it was, if
+ * any entry is an infinity or a NaN.
+ */
+int sage_set_debug_checks(sage_ctx* ctx, int on);
+
+/*
+ * Test hook for the error path: the nth kernel launch from now that the context issues for its main sequence (Gram,
+ * reduce, eigensolve, coefficients, rebuild, insert, projection, finalise, select) is not made and is reported as a
+ * failed launch instead, so that the call in progress returns SAGE_ERR_HIP and the context becomes poisoned exactly as
+ * after a real launch failure. Nothing faulty runs on the GPU. nth = 0 disarms the hook.
+ */
+int sage_debug_fail_launch(sage_ctx* ctx, int nth);
 
 /* Static description of a status code (HOST string, never NULL). */
 const char* sage_strerror(int code);

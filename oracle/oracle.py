@@ -59,6 +59,8 @@ def _load():
         getattr(L, name).argtypes = [vp]
         getattr(L, name).restype = dbl
     L.orc_threads.restype = i32
+    L.orc_row_dot.argtypes = [vp, vp, i64]
+    L.orc_row_dot.restype = dbl
     _lib = L
     return L
 
@@ -133,8 +135,8 @@ class Oracle:
 
     def select_cb(self, keep_rate, labels, n_classes):
         """Class-balanced selection (Algorithm 1, "if class balance required"): per class c the unit centroid u_c of the
-        stored zhat of its rows, alpha_i = <zhat_i, u_c(i)> clamped, and the k_c = floor(keep*N_c + 0.5) rows of the
-        class greatest under (alpha as float32 descending, index ascending). Returns (alpha float64, indices ascending)."""
+        stored zhat of its rows, alpha_i = <zhat_i, u_c(i)> clamped, and the k_c (cb_budgets: they sum to the plain
+        selection's m) rows of the class greatest under (alpha as float32 descending, index ascending). Returns (alpha float64, indices ascending)."""
         return cb_scores_and_selection(self.zhat, labels, n_classes, keep_rate)
 
     # ---- views (copies) ----
@@ -226,6 +228,14 @@ def sym_jacobi(Cm):
     return lam, Y
 
 
+def row_dot(a, b):
+    """<a, b> in fp64, summed in index order: one entry of the Gram matrix the Gram route forms."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    b = np.ascontiguousarray(b, dtype=np.float64)
+    assert a.ndim == 1 and a.shape == b.shape
+    return float(_load().orc_row_dot(a.ctypes.data, b.ctypes.data, a.shape[0]))
+
+
 def topm_f32(alpha, m):
     L = _load()
     alpha = np.ascontiguousarray(alpha, dtype=np.float32)
@@ -254,16 +264,34 @@ def cb_alpha(zhat, labels, n_classes):
     return alpha
 
 
+def cb_budgets(counts, keep_rate):
+    """The class budgets k_c (Algorithm 1, class-balanced branch: "sum_c k_c = k"). The subset size is that of the plain
+    selection, m = floor(keep*N + 0.5); class c gets floor(keep*N_c), and the rows still missing from m go one each to
+    the classes with the largest fractional part keep*N_c - floor(keep*N_c) (equal parts: the lower class first) that
+    are not yet full (largest-remainder rule). Returns an int64 array with sum m."""
+    counts = np.asarray(counts, dtype=np.int64)
+    q = float(keep_rate) * counts.astype(np.float64)
+    kc = np.minimum(np.floor(q).astype(np.int64), counts)
+    frac = q - np.floor(q)
+    m = keep_count(keep_rate, int(counts.sum()))
+    rem = m - int(kc.sum())
+    open_classes = [c for c in range(counts.size) if kc[c] < counts[c]]
+    for c in sorted(open_classes, key=lambda c: (-frac[c], c))[:max(rem, 0)]:
+        kc[c] += 1
+    return kc
+
+
 def cb_select_from_alpha(alpha, labels, n_classes, keep_rate):
-    """Per class the k_c = floor(keep*N_c + 0.5) rows greatest under (float32 alpha descending, index ascending);
-    all kept indices ascending."""
+    """Per class the k_c (cb_budgets) rows greatest under (float32 alpha descending, index ascending); all kept indices
+    ascending."""
     a32 = np.asarray(alpha).astype(np.float32)
     a32 = np.where(a32 == 0, np.float32(0), a32)     # -0 -> +0
     labels = np.asarray(labels)
+    budgets = cb_budgets([int((labels == c).sum()) for c in range(int(n_classes))], keep_rate)
     kept = []
     for c in range(int(n_classes)):
         rows = np.nonzero(labels == c)[0]
-        kc = keep_count(keep_rate, rows.size)
+        kc = int(budgets[c])
         if kc == 0:
             continue
         order = sorted(rows.tolist(), key=lambda i: (-float(a32[i]), i))

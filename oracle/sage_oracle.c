@@ -206,6 +206,13 @@ int orc_sym_jacobi(double *C, int n, double *Y, double *lam) {
     return sweeps;
 }
 
+/* One entry of the Gram matrix B B^T: the plain dot product of two rows, summed in index order. */
+double orc_row_dot(const double *a, const double *b, int64_t D) {
+    double acc = 0;
+    for (int64_t d = 0; d < D; ++d) acc += a[d] * b[d];
+    return acc;
+}
+
 /* Gram route: decompose the n x D matrix A. On return W (n x D) holds sigma_j v_j^T (descending), sig2 the
  * squared singular values. A is left untouched. */
 static int gram_route(const double *A, int n, int64_t D, double *W, double *sig2) {
@@ -214,9 +221,7 @@ static int gram_route(const double *A, int n, int64_t D, double *W, double *sig2
 #pragma omp parallel for schedule(dynamic, 1)
     for (int i = 0; i < n; ++i) {
         for (int j = 0; j <= i; ++j) {
-            const double *a = A + (int64_t)i * D, *b = A + (int64_t)j * D;
-            double acc = 0;
-            for (int64_t d = 0; d < D; ++d) acc += a[d] * b[d];
+            double acc = orc_row_dot(A + (int64_t)i * D, A + (int64_t)j * D, D);
             C[(int64_t)i * n + j] = acc;
             C[(int64_t)j * n + i] = acc;
         }

@@ -19,8 +19,8 @@ KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild"
 EXPORTS = (
     "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_update_arithmetic", "sage_probe_gram_split", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
-    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_topm_static", "sage_probe_gram_eig", "sage_probe_eig_matrix", "sage_probe_eig_psd", "sage_set_eig_precondition",
-    "sage_profile_enable", "sage_copy_probe",
+    "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_topm_static", "sage_probe_gram_eig", "sage_probe_eig_matrix",
+    "sage_profile_enable", "sage_copy_probe", "sage_set_debug_checks", "sage_debug_fail_launch", "sage_set_sweep_policy",
     "sage_profile_read", "sage_strerror",
 )
 
@@ -28,7 +28,8 @@ EXPORTS = (
 class SageStats(C.Structure):
     _fields_ = [("rows_seen", C.c_int64), ("n_shrinks", C.c_int64), ("n_scored", C.c_int64),
                 ("sum_delta", C.c_double), ("frob2", C.c_double), ("last_delta", C.c_double),
-                ("last_sweeps", C.c_int), ("fill", C.c_int)]
+                ("last_sweeps", C.c_int), ("fill", C.c_int), ("n_unconverged", C.c_int64),
+                ("last_offdiag", C.c_double)]
 
 
 class SageError(RuntimeError):
@@ -81,9 +82,10 @@ def lib():
     L.sage_topm_static.argtypes = [vp, i64, i64, vp, vp]
     L.sage_probe_gram_eig.argtypes = [vp, vp, i32, vp, vp, C.POINTER(i32)]
     L.sage_probe_eig_matrix.argtypes = [vp, vp, vp, vp, vp]
-    L.sage_probe_eig_psd.argtypes = [vp, vp, vp, vp, vp]
-    L.sage_set_eig_precondition.argtypes = [vp, i32]
     L.sage_copy_probe.argtypes = [vp, vp, i64, vp]
+    L.sage_set_debug_checks.argtypes = [vp, i32]
+    L.sage_set_sweep_policy.argtypes = [vp, i32]
+    L.sage_debug_fail_launch.argtypes = [vp, i32]
     L.sage_profile_enable.argtypes = [vp, i32]
     L.sage_profile_read.argtypes = [vp, i32, C.POINTER(dbl), C.POINTER(i64)]
     L.sage_strerror.argtypes = [i32]
@@ -283,17 +285,15 @@ class Sage:
         _check(self.L.sage_probe_eig_matrix(self.h, _ptr(Cm), _ptr(Y), _ptr(lam), _ptr(stat)), "sage_probe_eig_matrix")
         return Y, lam, stat
 
-    def probe_eig_psd(self, Cm):
-        n = Cm.shape[0]
-        assert Cm.is_cuda and Cm.dtype == self.torch.float64 and Cm.is_contiguous()
-        Y = self.torch.empty((n, n), dtype=self.torch.float64, device="cuda")
-        lam = self.torch.empty((n,), dtype=self.torch.float64, device="cuda")
-        stat = self.torch.empty((18,), dtype=self.torch.float64, device="cuda")
-        _check(self.L.sage_probe_eig_psd(self.h, _ptr(Cm), _ptr(Y), _ptr(lam), _ptr(stat)), "sage_probe_eig_psd")
-        return Y, lam, stat
+    def set_sweep_policy(self, all_sweeps):
+        """True: every shrink's eigensolve gets all its sweeps; False (default): as many as recent solves needed, plus two."""
+        _check(self.L.sage_set_sweep_policy(self.h, 1 if all_sweeps else 0), "sage_set_sweep_policy")
 
-    def set_eig_precondition(self, on=True):
-        _check(self.L.sage_set_eig_precondition(self.h, 1 if on else 0), "sage_set_eig_precondition")
+    def set_debug_checks(self, on=True):
+        _check(self.L.sage_set_debug_checks(self.h, 1 if on else 0), "sage_set_debug_checks")
+
+    def debug_fail_launch(self, nth):
+        _check(self.L.sage_debug_fail_launch(self.h, int(nth)), "sage_debug_fail_launch")
 
     def profile_enable(self, on=True):
         _check(self.L.sage_profile_enable(self.h, 1 if on else 0), "sage_profile_enable")

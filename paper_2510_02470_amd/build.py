@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsage_hip.so")
-SOURCES = ["fd_insert.hip", "fd_gram.hip", "fd_eig.hip", "fd_chol.hip", "fd_rebuild.hip", "score.hip", "score_split.hip", "select.hip", "select_cb.hip", "topm_static.hip", "sage_api.hip"]
+SOURCES = ["fd_insert.hip", "fd_gram.hip", "fd_eig.hip", "fd_rebuild.hip", "score.hip", "score_split.hip", "select.hip", "select_cb.hip", "topm_static.hip", "launch_util.hip", "sage_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -577,25 +577,40 @@ __global__ __launch_bounds__(512) void eig_sort_kernel(const double* __restrict_
     if (j == 0) {
         const int launched = (int)stat[MAX_SWEEPS + 3];
         int used = launched + SWEEPS_NOT_CONVERGED;  // the measurement after the last launched sweep was still > tol
+        int last = launched <= MAX_SWEEPS ? launched : MAX_SWEEPS;
         for (int s = 0; s <= launched && s <= MAX_SWEEPS; ++s)
-            if (stat[1 + s] <= tol) { used = s; break; }
+            if (stat[1 + s] <= tol) { used = s; last = s; break; }
         acc[3] = (double)used;
+        if (used >= SWEEPS_NOT_CONVERGED) acc[4] += 1.0;  // sticky: solves that ended above their tolerance
+        acc[5] = stat[1 + last];                          // largest |off-diagonal| / trace the solve left
     }
 }
 
 // Shrink coefficients (Method, FD paragraph: delta = sigma_ell^2, Sigma'_jj = sqrt(max(sigma_j^2 - delta, 0))):
 // new row m = w_m * y_m^T B with w_m = sqrt(max(lambda_m - delta, 0) / lambda_m); stored in coeff_offset order.
+// Also records the Gram matrix of the rows the rebuild is about to write, diag(w) (Y^T C Y) diag(w), from the rotated
+// matrix Crot the eigensolve left: the next cycle takes that block as known instead of recomputing it. Its diagonal
+// is max(lambda_j - delta, 0); its off-diagonal entries are what the solve did not annihilate (at most its tolerance,
+// more if it ran out of sweeps), so that the next Gram matrix is right whether or not the rows came out orthogonal.
 __global__ __launch_bounds__(256) void shrink_coeffs_kernel(const double* __restrict__ Y, const int* __restrict__ pos,
                                                             const double* __restrict__ lam,
-                                                            const double* __restrict__ diag0, int NP, int LP, int ell,
+                                                            const double* __restrict__ diag0,
+                                                            const double* __restrict__ Crot, int NP, int LP, int ell,
                                                             int ra0, int ra1, int rb0, int rb1,
                                                             float* __restrict__ Mt, double* __restrict__ acc,
                                                             double* __restrict__ known) {
     int e = blockIdx.x * 256 + threadIdx.x;
     const double delta = lam[ell - 1];
-    if (e < NP) {  // squared norm of new row e: w_e^2 lambda_e
-        double keep = e < ell ? lam[e] - delta : 0.0;
-        known[e] = keep > 0.0 ? keep : 0.0;
+    if (e < LP * LP) {
+        const int i = e / LP, j = e % LP;
+        double v = 0.0;
+        if (i < ell && j < ell) {
+            const double li = lam[i], lj = lam[j];
+            const double ki = li - delta, kj = lj - delta;
+            if (i == j) v = ki > 0.0 ? ki : 0.0;
+            else if (ki > 0.0 && kj > 0.0) v = sqrt(ki / li) * sqrt(kj / lj) * Crot[(int64_t)pos[i] * NP + pos[j]];
+        }
+        known[e] = v;
     }
     if (e < NP * LP) {
         int i = e / LP, m = e % LP;
@@ -654,12 +669,9 @@ static const size_t CROSS_PAD_LDS = 100 * 1024;
 static const size_t APPLY_LDS = (size_t)(64 * LDX + 64 * LDQB + 64 * LDQ) * sizeof(double);
 
 hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st) {
-    static bool attr = false;
-    if (!attr) {
-        (void)hipFuncSetAttribute((const void*)jac_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)APPLY_LDS);
-        (void)hipFuncSetAttribute((const void*)jac_pivot_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CROSS_PAD_LDS);
-        attr = true;
-    }
+    hipError_t ea = ensure_dynamic_lds((const void*)jac_apply_kernel, (int)APPLY_LDS);
+    if (ea == hipSuccess) ea = ensure_dynamic_lds((const void*)jac_pivot_kernel, (int)CROSS_PAD_LDS);
+    if (ea != hipSuccess) return ea;
     if (max_sweeps > MAX_SWEEPS) max_sweeps = MAX_SWEEPS;
     if (max_sweeps < 1) max_sweeps = 1;
     hipLaunchKernelGGL(jac_init_kernel, dim3(NP), dim3(256), 0, st, w.C, w.Y, w.diag0, w.stat, NP, max_sweeps);
@@ -685,7 +697,7 @@ hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int r
                                 double* acc, double tol, hipStream_t st) {
     hipLaunchKernelGGL(eig_sort_kernel, dim3(1), dim3(512), 0, st, w.C, w.stat, w.pos, w.lam, NP, acc, tol);
     hipLaunchKernelGGL(shrink_coeffs_kernel, dim3((NP * LP + 255) / 256), dim3(256), 0, st, w.Y, w.pos, w.lam, w.diag0,
-                       NP, LP, ell, ra0, ra1, rb0, rb1, Mt, acc, w.known);
+                       w.C, NP, LP, ell, ra0, ra1, rb0, rb1, Mt, acc, w.known);
     return hipGetLastError();
 }
 

@@ -662,8 +662,8 @@ __global__ __launch_bounds__(256, 2) void gram_new8_split_kernel(const float* __
 }
 
 // C (NP x NP, fp64, both triangles) = sum over groups of the partial tiles, in group order. With q = P/2:
-// known_top: tiles with ti < q are not summed, their block is diag(known) (the top rows are the orthogonal rows the
-// last shrink wrote, whose squared norms it recorded). Otherwise tile (ti, tj) comes from source A when its mode
+// known_top: tiles with ti < q are not summed, their block is `known` (the top rows are the rows the last shrink
+// wrote, whose Gram matrix it recorded: diagonal up to the tolerance of its eigensolve). Otherwise tile (ti, tj) comes from source A when its mode
 // covers it, else from source B (mode-1 and mode-2 launches write separate partial buffers).
 struct GramSrc {
     const float* partial;
@@ -687,7 +687,7 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(GramSrc a, GramSrc b, 
     int gr = ti * 64 + r, gc = tj * 64 + c;
     double s = 0.0;
     if (known_top && ti < (P >> 1)) {
-        if (gr == gc) s = known[gr];
+        s = known[(int64_t)gr * (NP >> 1) + gc];
     } else {
         int ia = gram_src_index(a, P, t, ti, tj);
         const GramSrc& g = ia >= 0 ? a : b;
@@ -772,22 +772,13 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
     size_t lds = (size_t)2 * d.NP * 64;
     if (p.mode == 1 && d.NP == 512 && p.split) {
         constexpr int LDS_SPLIT = 2 * 3 * 2 * (512 + 8) * 16;  // two stages of [part][k-half][row + pad] pieces
-        static bool attrs = false;
-        if (!attrs) {
-            (void)hipFuncSetAttribute((const void*)gram_cross8_split_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      LDS_SPLIT);
-            attrs = true;
-        }
+        if (hipError_t ea = ensure_dynamic_lds((const void*)gram_cross8_split_kernel, LDS_SPLIT); ea != hipSuccess) return ea;
         hipLaunchKernelGGL(gram_cross8_split_kernel, grid, dim3(512), LDS_SPLIT, st, top, nw, nfill, partial, d.S,
                            p.slabs_per_group);
         return hipGetLastError();
     }
     if (p.mode == 1 && d.NP == 512) {
-        static bool attr8 = false;
-        if (!attr8) {
-            (void)hipFuncSetAttribute((const void*)gram_cross8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
-            attr8 = true;
-        }
+        if (hipError_t ea = ensure_dynamic_lds((const void*)gram_cross8_kernel, 65536); ea != hipSuccess) return ea;
         hipLaunchKernelGGL(gram_cross8_kernel, grid, dim3(256), lds, st, top, nw, nfill, partial, d.S, p.slabs_per_group);
         return hipGetLastError();
     }
@@ -801,22 +792,14 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
         return hipGetLastError();
     }
     if (p.mode == 2 && d.NP == 512 && p.wg_per_group == 1) {
-        static bool attrn = false;
-        if (!attrn) {
-            (void)hipFuncSetAttribute((const void*)gram_new8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
-            attrn = true;
-        }
+        if (hipError_t ea = ensure_dynamic_lds((const void*)gram_new8_kernel, 65536); ea != hipSuccess) return ea;
         hipLaunchKernelGGL(gram_new8_kernel, grid, dim3(256), 32768, st, nw, nfill, partial, d.S, p.slabs_per_group);
         return hipGetLastError();
     }
     switch (d.NP / 64) {
 #define SAGE_GRAM_CASE(PP)                                                                                          \
     case PP: {                                                                                                      \
-        static bool attr_set = false;                                                                               \
-        if (!attr_set) {                                                                                            \
-            (void)hipFuncSetAttribute((const void*)gram_kernel<PP>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);   \
-            attr_set = true;                                                                                        \
-        }                                                                                                           \
+        if (hipError_t ea = ensure_dynamic_lds((const void*)gram_kernel<PP>, 65536); ea != hipSuccess) return ea;   \
         hipLaunchKernelGGL(gram_kernel<PP>, grid, dim3(256), lds, st, top, nw, nfill, partial, p.mode, p.t0, p.tiles,    \
                            p.wg_per_group, d.S, p.slabs_per_group);                                                 \
     } break;
@@ -831,7 +814,7 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
     return hipGetLastError();
 }
 
-// a, b: the launches whose partial tiles make up C (b may be null); known: NP doubles, read when known_top
+// a, b: the launches whose partial tiles make up C (b may be null); known: LP x LP doubles, read when known_top
 hipError_t launch_gram_reduce(const float* partial_a, const GramPlan& a, const float* partial_b, const GramPlan* b,
                               double* C, bool known_top, const double* known, const Dims& d, hipStream_t st) {
     const int P = d.NP / 64;

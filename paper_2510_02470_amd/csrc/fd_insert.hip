@@ -194,6 +194,29 @@ hipError_t launch_plain_copy(const void* src, void* dst, int64_t bytes, hipStrea
     return hipGetLastError();
 }
 
+// Debug check of caller data: *count += the number of entries that are not finite (exponent bits all ones).
+template <typename T>
+__global__ __launch_bounds__(256) void count_nonfinite_kernel(const T* __restrict__ p, int64_t n, unsigned* __restrict__ count) {
+    unsigned bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        if (sizeof(T) == 2) bad += (((unsigned)p[i]) & 0x7F80u) == 0x7F80u;
+        else bad += (((unsigned)p[i]) & 0x7F800000u) == 0x7F800000u;
+    }
+    for (int o = 32; o >= 1; o >>= 1) bad += __shfl_xor(bad, o);
+    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(count, bad);
+}
+
+hipError_t launch_count_nonfinite(const void* p, int dtype, int64_t n, unsigned* count, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    if (dtype == SAGE_BF16)
+        hipLaunchKernelGGL(count_nonfinite_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, st, (const uint16_t*)p, n, count);
+    else
+        hipLaunchKernelGGL(count_nonfinite_kernel<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, st, (const uint32_t*)p, n, count);
+    return hipGetLastError();
+}
+
 // zero buffer rows [r0, r1) in every slab
 __global__ __launch_bounds__(256) void zero_rows_kernel(float* __restrict__ Bblk, int NP, int r0, int r1, int64_t S) {
     int per_slab = (r1 - r0) * 4;  // float4 pieces per slab

@@ -8,7 +8,8 @@
 // LP .. NP-1 of which the first nfill hold data (the others count as zero, whatever they hold).
 // A wave owns 32 columns for the whole product: it reads all NP buffer rows of those columns (its B operand comes
 // straight from global memory, one 128 B line per row pair), keeps the MP x 32 result in accumulators, and only
-// then writes. Nobody else touches those columns, so the update is safely in place (out == top). The coefficient matrix
+// then writes. Nobody else touches those columns, so the update is safely in place (out == top, which is why neither
+// pointer is declared restrict). The coefficient matrix
 // streams through LDS in chunks of 16 buffer rows shared by the 4 waves of the work-group; it is stored in the
 // order the matrix cores consume it (see coeff_offset), so a lane fetches the 8 coefficients of a chunk with two
 // 16-byte LDS reads.
@@ -17,9 +18,9 @@
 namespace sage {
 
 template <int MT>  // MT = MP / 32 accumulator tiles per wave
-__global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict__ top, const float* __restrict__ nw,
-                                                         int nfill, const float* __restrict__ Mc,
-                                                         float* __restrict__ out, int NP, int out_NP, int64_t Dp) {
+__global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* top, const float* __restrict__ nw, int nfill,
+                                                         const float* __restrict__ Mc, float* out, int NP, int out_NP,
+                                                         int64_t Dp) {
     constexpr int MP = MT * 32;
     constexpr int CHUNK4 = 16 * MP / 4;  // 16-byte pieces per stage (16 buffer rows x MP coefficients)
     constexpr int PER = CHUNK4 / 256;    // pieces per thread per stage (MT / 2 ... at least 1)
@@ -34,7 +35,9 @@ __global__ __launch_bounds__(256, 2) void rebuild_kernel(const float* __restrict
     const int64_t dc = live ? d : Dp - 1;
     const int LP = NP >> 1;
     const int64_t coff = ((dc / DC) * LP) * (int64_t)DC + (dc % DC) + (int64_t)h * DC;  // row h of this column, either half
-    const float* tcol = top + coff;
+    // lanes beyond the last column compute nothing that is stored; they read the new half only, which this kernel never
+    // writes (out may be top: top and out are the same memory then, hence not declared restrict)
+    const float* tcol = (live ? top : nw) + coff;
     const float* ncol = nw + coff;
     // rows 16*stg + 2*s + h of the matrix: stage stg lies in the top half when stg < LP/16. Rows of the new half are
     // always loaded (they exist); those not in use are zeroed when the stage consumes them (use_b), not here, so
@@ -191,9 +194,9 @@ __global__ __launch_bounds__(256) void coeff_split_kernel(const float* __restric
 }
 
 template <int MT>
-__global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* __restrict__ top, const float* __restrict__ nw,
-                                                               int nfill, const u32x4* __restrict__ Mc3,
-                                                               float* __restrict__ out, int NP, int out_NP, int64_t Dp) {
+__global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* top, const float* __restrict__ nw, int nfill,
+                                                               const u32x4* __restrict__ Mc3, float* out, int NP,
+                                                               int out_NP, int64_t Dp) {
     constexpr int MP = MT * 32;
     constexpr int STAGE16 = 3 * 2 * MP;   // 16-byte pieces of coefficients per stage
     constexpr int ML = STAGE16 / 256;     // direct-to-LDS loads per thread and stage
@@ -208,7 +211,9 @@ __global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* __re
     const int64_t dc = live ? d : Dp - 1;
     const int LP = NP >> 1;
     const int64_t coff = ((dc / DC) * LP) * (int64_t)DC + (dc % DC) + (int64_t)h * DC;  // row h of this column, either half
-    const float* tcol = top + coff;
+    // lanes beyond the last column compute nothing that is stored; they read the new half only, which this kernel never
+    // writes (out may be top: top and out are the same memory then, hence not declared restrict)
+    const float* tcol = (live ? top : nw) + coff;
     const float* ncol = nw + coff;
     const int nstage = NP / 16;
     auto fetch_b = [&](int stg, float (&b)[8]) __attribute__((always_inline)) {
@@ -328,11 +333,7 @@ static hipError_t launch_rebuild_split_t(const float* top, const float* nw, int 
                                          float* out, int out_NP, const Dims& d, hipStream_t st) {
     constexpr int MP = MT * 32;
     constexpr size_t LDS = (size_t)3 * 3 * 2 * MP * 16;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)rebuild_split_kernel<MT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
-        attr_set = true;
-    }
+    if (hipError_t ea = ensure_dynamic_lds((const void*)rebuild_split_kernel<MT>, (int)LDS); ea != hipSuccess) return ea;
     const int n = (d.NP / 16) * 2 * MP;
     hipLaunchKernelGGL(coeff_split_kernel<MT>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, Mc, d.NP, (u32x4*)Mc3);
     hipError_t e = hipGetLastError();

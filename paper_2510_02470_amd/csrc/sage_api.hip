@@ -50,11 +50,21 @@ struct sage_ctx {
     float* Mt = nullptr;
     void* Mt3 = nullptr;   // the rebuild's coefficients split into bf16 parts (SAGE_MM_SPLIT)
     int mm_mode = SAGE_MM_SPLIT;
-    double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps
+    double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps [4] unconverged solves [5] last off-diagonal
 
-    // Sweeps to launch for a shrink's eigensolve: what the last read-back solve needed, plus one. The count comes back
-    // through pinned host memory without the host ever waiting for it.
+    bool poisoned = false;   // a HIP call failed while work of a call was partly enqueued: the state is not trustworthy
+    int fail_in = 0;         // test hook (sage_debug_fail_launch): the fail_in-th launch from now fails without running
+    bool debug_checks = false;      // sage_set_debug_checks: scan caller batches for non-finite values
+    unsigned* dbg_count = nullptr;  // device counter of that scan
+
+    // Sweeps to launch for a shrink's eigensolve (a sweep that finds the matrix converged returns at once, but its 30
+    // launches still cost about 50 us): what the last read-back solve needed, plus two. The count comes back through
+    // pinned host memory without the host ever waiting for it.
     int sweep_cap = MAX_SWEEPS;
+    int sweep_hold = 0;      // solves still to be launched with every sweep after one came back unconverged
+    int sweep_recent[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // sweeps the last eight reported solves needed
+    int sweep_recent_at = 0;
+    bool sweeps_all = false; // sage_set_sweep_policy(SAGE_SWEEPS_ALL): always launch MAX_SWEEPS
     double* h_sweeps = nullptr;                    // pinned, SWEEP_RING slots
     hipEvent_t ev_sweeps[4] = {nullptr, nullptr, nullptr, nullptr};
     bool sweeps_pending[4] = {false, false, false, false};
@@ -77,7 +87,6 @@ struct sage_ctx {
     int proj_mode = SAGE_PROJ_AUTO;
     float* zhat = nullptr;
     int64_t cap_rows = 0, n_scored = 0;
-    bool precond = false;     // shrink: eigensolve through one Cholesky step (fd_chol.hip)
     bool store_zhat = true;   // false: zhat is not kept; alpha comes from a second pass over the rows (sage_rescore)
     int64_t n_rescored = 0;
     int* labels = nullptr;       // class label of every scored row (sage_score_labeled), same capacity as zhat
@@ -101,10 +110,24 @@ struct sage_ctx {
 
 namespace {
 
+// A HIP call that fails in the middle of a library call leaves work of that call partly enqueued: the context is
+// marked poisoned (every later call except sage_destroy returns SAGE_ERR_STATE). `c` must be in scope.
+inline int hip_failed(sage_ctx* c) {
+    (void)hipGetLastError();
+    c->poisoned = true;
+    return SAGE_ERR_HIP;
+}
 #define HIPCHK(expr)                                 \
     do {                                             \
         hipError_t e_ = (expr);                      \
-        if (e_ != hipSuccess) return SAGE_ERR_HIP;   \
+        if (e_ != hipSuccess) return hip_failed(c);  \
+    } while (0)
+
+// first statement of every call on a context
+#define ALIVE(c)                                      \
+    do {                                              \
+        if (!(c)) return SAGE_ERR_ARG;                \
+        if ((c)->poisoned) return SAGE_ERR_STATE;     \
     } while (0)
 
 #define ALLOC(ptr, bytes)                                                  \
@@ -118,6 +141,7 @@ namespace {
 // run a launcher, optionally bracketed by events of kernel class `cls`
 template <typename F>
 int run(sage_ctx* c, int cls, F&& f) {
+    if (c->fail_in > 0 && --c->fail_in == 0) return hip_failed(c);  // sage_debug_fail_launch
     if (c->prof) HIPCHK(hipEventRecord(c->ev0, c->st));
     HIPCHK(f());
     if (c->prof) {
@@ -185,8 +209,21 @@ void poll_sweeps(sage_ctx* c) {
         c->sweeps_pending[i] = false;
         if (e != hipSuccess) continue;
         const int used = (int)c->h_sweeps[i];
-        if (used >= SWEEPS_NOT_CONVERGED) c->sweep_cap = MAX_SWEEPS;  // ran out: launch them all next time
-        else c->sweep_cap = used + 1 < 3 ? 3 : (used + 1 > MAX_SWEEPS ? MAX_SWEEPS : used + 1);
+        if (used >= SWEEPS_NOT_CONVERGED) {
+            // ran out (sage_stats counts it): every sweep is launched for the solves to come
+            c->sweep_cap = MAX_SWEEPS;
+            c->sweep_hold = 64;
+        } else {
+            c->sweep_recent[c->sweep_recent_at] = used;
+            c->sweep_recent_at = (c->sweep_recent_at + 1) & 7;
+            if (c->sweep_hold > 0) {
+                c->sweep_hold -= 1;
+            } else {
+                int most = used;
+                for (int v : c->sweep_recent) most = v > most ? v : most;
+                c->sweep_cap = most + 2 < 4 ? 4 : (most + 2 > MAX_SWEEPS ? MAX_SWEEPS : most + 2);
+            }
+        }
     }
 }
 
@@ -203,17 +240,17 @@ void post_sweeps(sage_ctx* c) {
     c->sweeps_next = (i + 1) % SWEEP_RING;
 }
 
-// Gram + eigensolve of the buffer as it stands. After a shrink the top rows are orthogonal with known squared norms
-// (lambda_j - delta), so their block is not recomputed.
+// Gram + eigensolve of the buffer as it stands. After a shrink the Gram matrix of the top rows is known (the shrink
+// recorded it: diagonal lambda_j - delta, off-diagonal what its eigensolve left), so their block is not recomputed.
 int decompose(sage_ctx* c, double tol, bool full) {
     const bool skip = !full && c->top_shrunk && c->gp_skip.t0 > 0;
     if (skip && c->fill_new == 0) {
-        // Only the rows the last shrink wrote are there: the Gram matrix is diag(known), nothing to compute and
-        // nothing to rotate (one sweep is launched; it finds the matrix diagonal and returns).
+        // Only the rows the last shrink wrote are there: the Gram matrix is the block that shrink recorded, nothing to
+        // compute (its off-diagonal entries are at most the shrink's tolerance: a sweep or two at a tighter one).
         GramPlan none = c->gp_skip;
         none.tiles = 0;
         RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, none, nullptr, nullptr, c->ew.C, true, c->ew.known, c->d, c->st));
-        RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, 1, c->st));
+        RUN(K_EIG, launch_eig(c->ew, c->d.NP, tol, MAX_SWEEPS, c->st));
         return SAGE_OK;
     }
     if (skip && c->mm_mode == SAGE_MM_SPLIT && c->gp_cross_split.tiles > 0 && c->gp_new2_split.tiles > 0 &&
@@ -284,10 +321,7 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
         if (rc != SAGE_OK) return rc;
     }
     poll_sweeps(c);
-    if (c->precond)
-        RUN(K_EIG, launch_eig_precond(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweep_cap, c->st));
-    else
-        RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweep_cap, c->st));
+    RUN(K_EIG, launch_eig(c->ew, c->d.NP, JACOBI_TOL_SHRINK, c->sweeps_all ? MAX_SWEEPS : c->sweep_cap, c->st));
     RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, LP, ell, c->cnt_top, c->fill_top, LP + c->cnt_new, LP + c->fill_new,
                                       c->Mt, c->acc, JACOBI_TOL_SHRINK, c->st));
     if (c->mm_mode == SAGE_MM_SPLIT && c->Mt3)
@@ -495,12 +529,7 @@ int sage_fd_create_ex(sage_ctx** out, int ell, int64_t D, sage_dtype in_dtype, i
     CALLOC(c->ew.stat, 32 * sizeof(double));
     CALLOC(c->ew.pos, (size_t)NP * sizeof(int));
     CALLOC(c->ew.lam, (size_t)NP * sizeof(double));
-    CALLOC(c->ew.known, (size_t)NP * sizeof(double));
-    CALLOC(c->ew.L, (size_t)NP * NP * sizeof(double));
-    CALLOC(c->ew.Ld, (size_t)NP * 64 * sizeof(double));
-    CALLOC(c->ew.perm, (size_t)NP * sizeof(int));
-    CALLOC(c->ew.scal, 8 * sizeof(double));
-    c->precond = false;  // see sage_set_eig_precondition
+    CALLOC(c->ew.known, (size_t)c->d.LP * c->d.LP * sizeof(double));
     CALLOC(c->Mt, (size_t)NP * c->d.LP * sizeof(float));
     if (rebuild_split_ok(c->d.LP)) CALLOC(c->Mt3, rebuild_split_bytes(c->d, c->d.LP));
     CALLOC(c->acc, 8 * sizeof(double));
@@ -527,8 +556,8 @@ void sage_destroy(sage_ctx* c) {
     if (c->st2) (void)hipStreamSynchronize(c->st2);
     void* ptrs[] = {c->top,     c->nw[0],    c->nw[1],  c->gram_partial, c->gram_partial_new[0], c->gram_partial_new[1],
                     c->ew.C,    c->ew.Y,     c->ew.C2,  c->ew.Y2,        c->ew.Q,    c->ew.diag0, c->ew.stat,
-                    c->ew.pos,  c->ew.lam,   c->ew.known, c->ew.L, c->ew.Ld, c->ew.perm, c->ew.scal, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
-                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work, c->stage, c->Mt3};
+                    c->ew.pos,  c->ew.lam,   c->ew.known, c->Mt,         c->acc,     c->Vblk,     c->Vimg,
+                    c->zhat,    c->proj_partial, c->cons_partial, c->ssum, c->alpha, c->labels, c->cb_work, c->stage, c->Mt3, c->dbg_count};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (c->st2) (void)hipStreamDestroy(c->st2);
@@ -544,14 +573,15 @@ void sage_destroy(sage_ctx* c) {
 }
 
 int sage_sync(sage_ctx* c) {
-    if (!c) return SAGE_ERR_ARG;
+    ALIVE(c);
     HIPCHK(hipStreamSynchronize(c->st));
     return SAGE_OK;
 }
 
 // Rows of type `dtype` (the context's own for sage_fd_update, fp32 for sage_fd_merge) go through the insert / shrink cycle.
 static int update_rows(sage_ctx* c, RowSrc g, int64_t rows) {
-    if (!c || rows < 0) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows < 0) return SAGE_ERR_ARG;
     if (rows == 0) return SAGE_OK;
     c->has_basis = false;
     const int ell = c->d.ell, LP = c->d.LP;
@@ -599,6 +629,19 @@ static int update_rows(sage_ctx* c, RowSrc g, int64_t rows) {
     return SAGE_OK;
 }
 
+// sage_set_debug_checks: a batch with a non-finite entry is refused before anything is enqueued for it (the scan
+// waits for the stream; the context is left as it was).
+static int check_finite(sage_ctx* c, const void* p, int dtype, int64_t n) {
+    if (!c->debug_checks || n <= 0 || !p) return SAGE_OK;
+    if (!c->dbg_count) ALLOC(c->dbg_count, sizeof(unsigned));
+    unsigned bad = 0;
+    HIPCHK(hipMemsetAsync(c->dbg_count, 0, sizeof(unsigned), c->st));
+    HIPCHK(launch_count_nonfinite(p, dtype, n, c->dbg_count, c->st));
+    HIPCHK(hipMemcpyAsync(&bad, c->dbg_count, sizeof(unsigned), hipMemcpyDeviceToHost, c->st));
+    HIPCHK(hipStreamSynchronize(c->st));
+    return bad ? SAGE_ERR_ARG : SAGE_OK;
+}
+
 static RowSrc dense_src(const void* G, int dtype) {
     RowSrc s;
     s.G = G;
@@ -618,20 +661,27 @@ static bool outer_src(const sage_ctx* c, const void* E, const void* H, int64_t C
 }
 
 int sage_fd_update(sage_ctx* c, const void* G_batch, int64_t rows) {
-    if (!c || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows > 0 && !G_batch) return SAGE_ERR_ARG;
+    if (int rc = check_finite(c, G_batch, c->dtype, rows * c->d.D); rc != SAGE_OK) return rc;
     return update_rows(c, dense_src(G_batch, c->dtype), rows);
 }
 
 int sage_fd_update_outer(sage_ctx* c, const void* E, const void* H, int64_t rows, int64_t n_classes, int64_t n_features) {
-    if (!c || rows < 0) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows < 0) return SAGE_ERR_ARG;
     if (rows == 0) return SAGE_OK;
     RowSrc s;
     if (!outer_src(c, E, H, n_classes, n_features, s)) return SAGE_ERR_ARG;
+    if (int rc = check_finite(c, E, c->dtype, rows * n_classes); rc != SAGE_OK) return rc;
+    if (int rc = check_finite(c, H, c->dtype, rows * n_features); rc != SAGE_OK) return rc;
     return update_rows(c, s, rows);
 }
 
 int sage_fd_merge(sage_ctx* c, const float* B_other, int64_t rows) {
-    if (!c || (rows > 0 && !B_other)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows > 0 && !B_other) return SAGE_ERR_ARG;
+    if (int rc = check_finite(c, B_other, SAGE_F32, rows * c->d.D); rc != SAGE_OK) return rc;
     return update_rows(c, dense_src(B_other, SAGE_F32), rows);
 }
 
@@ -642,7 +692,7 @@ int sage_fd_basis(sage_ctx* c, int k) { return basis_impl(c, k, false); }
 int sage_fd_basis_weighted(sage_ctx* c, int k) { return basis_impl(c, k, true); }
 
 static int basis_impl(sage_ctx* c, int k, bool weighted) {
-    if (!c) return SAGE_ERR_ARG;
+    ALIVE(c);
     if (k < 1 || k > c->d.ell - 1 || k > 128) return SAGE_ERR_ARG;
     const int KP = pad_pow2_32(k);
     int rc = flush_pending(c);
@@ -669,20 +719,23 @@ static int basis_impl(sage_ctx* c, int k, bool weighted) {
 }
 
 int sage_set_projection_mode(sage_ctx* c, int mode) {
-    if (!c || (mode != SAGE_PROJ_AUTO && mode != SAGE_PROJ_F32)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if ((mode != SAGE_PROJ_AUTO && mode != SAGE_PROJ_F32)) return SAGE_ERR_ARG;
     c->proj_mode = mode;
     c->has_basis = false;
     return SAGE_OK;
 }
 
 int sage_set_update_arithmetic(sage_ctx* c, int mode) {
-    if (!c || (mode != SAGE_MM_F32 && mode != SAGE_MM_SPLIT)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if ((mode != SAGE_MM_F32 && mode != SAGE_MM_SPLIT)) return SAGE_ERR_ARG;
     c->mm_mode = mode;
     return SAGE_OK;
 }
 
 int sage_set_basis(sage_ctx* c, const float* Vt, int k) {
-    if (!c || !Vt || k < 1 || k > 128) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (!Vt || k < 1 || k > 128) return SAGE_ERR_ARG;
     const int KP = pad_pow2_32(k);
     int rc = ensure_vblk(c, KP);
     if (rc != SAGE_OK) return rc;
@@ -763,27 +816,35 @@ static int project_rows(sage_ctx* c, const RowSrc& src, int64_t R, int* slots) {
 static int score_impl(sage_ctx* c, RowSrc g, const int* labels, int64_t rows);
 
 int sage_score(sage_ctx* c, const void* G_batch, int64_t rows) {
-    if (!c || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows > 0 && !G_batch) return SAGE_ERR_ARG;
+    if (int rc = check_finite(c, G_batch, c->dtype, rows * c->d.D); rc != SAGE_OK) return rc;
     return score_impl(c, dense_src(G_batch, c->dtype), nullptr, rows);
 }
 
 int sage_score_labeled(sage_ctx* c, const void* G_batch, const int32_t* labels, int64_t rows) {
-    if (!c || (rows > 0 && (!labels || !G_batch))) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows > 0 && (!labels || !G_batch)) return SAGE_ERR_ARG;
+    if (int rc = check_finite(c, G_batch, c->dtype, rows * c->d.D); rc != SAGE_OK) return rc;
     return score_impl(c, dense_src(G_batch, c->dtype), labels, rows);
 }
 
 int sage_score_outer(sage_ctx* c, const void* E, const void* H, const int32_t* labels, int64_t rows, int64_t n_classes,
                      int64_t n_features) {
-    if (!c || rows < 0) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows < 0) return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     if (rows == 0) return SAGE_OK;
     RowSrc s;
     if (!outer_src(c, E, H, n_classes, n_features, s)) return SAGE_ERR_ARG;
+    if (int rc = check_finite(c, E, c->dtype, rows * n_classes); rc != SAGE_OK) return rc;
+    if (int rc = check_finite(c, H, c->dtype, rows * n_features); rc != SAGE_OK) return rc;
     return score_impl(c, s, labels, rows);
 }
 
 static int score_impl(sage_ctx* c, RowSrc g, const int* labels, int64_t rows) {
-    if (!c || rows < 0) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows < 0) return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     if (rows == 0) return SAGE_OK;
     if (!c->store_zhat && (labels || c->n_rescored > 0)) return SAGE_ERR_STATE;  // no labels without zhat; pass 2 is over
@@ -798,7 +859,7 @@ static int score_impl(sage_ctx* c, RowSrc g, const int* labels, int64_t rows) {
                 hipSuccess ||
             hipStreamSynchronize(c->st) != hipSuccess) {
             (void)hipFree(nz);
-            return SAGE_ERR_HIP;
+            return hip_failed(c);
         }
         (void)hipFree(c->zhat);
         c->zhat = nz;
@@ -809,7 +870,7 @@ static int score_impl(sage_ctx* c, RowSrc g, const int* labels, int64_t rows) {
                     hipSuccess ||
                 hipStreamSynchronize(c->st) != hipSuccess) {
                 (void)hipFree(nl);
-                return SAGE_ERR_HIP;
+                return hip_failed(c);
             }
             (void)hipFree(c->labels);
             c->labels = nl;
@@ -848,7 +909,7 @@ static int ensure_alpha(sage_ctx* c, int64_t N) {
         if (hipMemcpyAsync(na, c->alpha, (size_t)c->alpha_cap * sizeof(float), hipMemcpyDeviceToDevice, c->st) != hipSuccess ||
             hipStreamSynchronize(c->st) != hipSuccess) {
             (void)hipFree(na);
-            return SAGE_ERR_HIP;
+            return hip_failed(c);
         }
         (void)hipFree(c->alpha);
     }
@@ -861,7 +922,7 @@ static int ensure_alpha(sage_ctx* c, int64_t N) {
 }
 
 int sage_set_score_store(sage_ctx* c, int store_zhat) {
-    if (!c) return SAGE_ERR_ARG;
+    ALIVE(c);
     c->store_zhat = store_zhat != 0;
     reset_scoring(c);
     if (c->ssum) HIPCHK(hipMemsetAsync(c->ssum, 0, 128 * sizeof(double), c->st));
@@ -869,6 +930,7 @@ int sage_set_score_store(sage_ctx* c, int store_zhat) {
 }
 
 static int rescore_impl(sage_ctx* c, RowSrc g, int64_t rows) {
+    ALIVE(c);
     if (!c->has_basis || c->store_zhat) return SAGE_ERR_STATE;
     if (c->n_rescored + rows > c->n_scored) return SAGE_ERR_STATE;  // more rows than the first pass saw
     if (rows == 0) return SAGE_OK;
@@ -890,12 +952,14 @@ static int rescore_impl(sage_ctx* c, RowSrc g, int64_t rows) {
 }
 
 int sage_rescore(sage_ctx* c, const void* G_batch, int64_t rows) {
-    if (!c || rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows < 0 || (rows > 0 && !G_batch)) return SAGE_ERR_ARG;
     return rescore_impl(c, dense_src(G_batch, c->dtype), rows);
 }
 
 int sage_rescore_outer(sage_ctx* c, const void* E, const void* H, int64_t rows, int64_t n_classes, int64_t n_features) {
-    if (!c || rows < 0) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (rows < 0) return SAGE_ERR_ARG;
     if (rows == 0) return rescore_impl(c, RowSrc{}, 0);
     RowSrc s;
     if (!outer_src(c, E, H, n_classes, n_features, s)) return SAGE_ERR_ARG;
@@ -903,7 +967,8 @@ int sage_rescore_outer(sage_ctx* c, const void* E, const void* H, int64_t rows, 
 }
 
 int sage_select(sage_ctx* c, double keep_rate, int64_t* out_idx, int64_t cap, int64_t* out_m) {
-    if (!c || !out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (!out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0)) return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     const int64_t N = c->n_scored;
     const int64_t m = keep_count(keep_rate, N);
@@ -923,7 +988,8 @@ int sage_select(sage_ctx* c, double keep_rate, int64_t* out_idx, int64_t cap, in
 }
 
 int sage_select_cb(sage_ctx* c, double keep_rate, int n_classes, int64_t* out_idx, int64_t cap, int64_t* out_m) {
-    if (!c || !out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0) || n_classes < 1 || n_classes > 65536)
+    ALIVE(c);
+    if (!out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0) || n_classes < 1 || n_classes > 65536)
         return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     const int64_t N = c->n_scored;
@@ -977,7 +1043,8 @@ int sage_topm(const float* alpha, int64_t N, int64_t m, int64_t* out_idx, void* 
 }
 
 int sage_fd_sketch_export(sage_ctx* c, float* B_out) {
-    if (!c || !B_out) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (!B_out) return SAGE_ERR_ARG;
     int rcf = flush_pending(c);
     if (rcf != SAGE_OK) return rcf;
     const int ell = c->d.ell;
@@ -991,7 +1058,8 @@ int sage_fd_sketch_export(sage_ctx* c, float* B_out) {
 }
 
 int sage_basis_export(sage_ctx* c, float* Vt_out) {
-    if (!c || !Vt_out) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (!Vt_out) return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     HIPCHK(launch_export_rows(c->Vblk, c->KP, c->k, Vt_out, c->d, c->st));
     HIPCHK(hipStreamSynchronize(c->st));
@@ -999,7 +1067,8 @@ int sage_basis_export(sage_ctx* c, float* Vt_out) {
 }
 
 int sage_scores(sage_ctx* c, const float** alpha, int64_t* n) {
-    if (!c || !alpha || !n) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (!alpha || !n) return SAGE_ERR_ARG;
     if (!c->has_basis || c->alpha_n != c->n_scored) return SAGE_ERR_STATE;
     *alpha = c->alpha;
     *n = c->alpha_n;
@@ -1007,7 +1076,8 @@ int sage_scores(sage_ctx* c, const float** alpha, int64_t* n) {
 }
 
 int sage_scores_export(sage_ctx* c, float* alpha_out) {
-    if (!c || (!alpha_out && c->n_scored > 0)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if ((!alpha_out && c->n_scored > 0)) return SAGE_ERR_ARG;
     if (!c->has_basis || c->alpha_n != c->n_scored) return SAGE_ERR_STATE;
     if (c->alpha_n > 0)
         HIPCHK(hipMemcpyAsync(alpha_out, c->alpha, (size_t)c->alpha_n * sizeof(float), hipMemcpyDeviceToDevice, c->st));
@@ -1016,7 +1086,8 @@ int sage_scores_export(sage_ctx* c, float* alpha_out) {
 }
 
 int sage_zhat_export(sage_ctx* c, float* zhat_out) {
-    if (!c || (!zhat_out && c->n_scored > 0)) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if ((!zhat_out && c->n_scored > 0)) return SAGE_ERR_ARG;
     if (!c->has_basis || !c->store_zhat) return SAGE_ERR_STATE;
     if (c->n_scored > 0)
         HIPCHK(hipMemcpyAsync(zhat_out, c->zhat, (size_t)c->n_scored * c->k * sizeof(float), hipMemcpyDeviceToDevice,
@@ -1026,7 +1097,8 @@ int sage_zhat_export(sage_ctx* c, float* zhat_out) {
 }
 
 int sage_stats(sage_ctx* c, sage_stats_t* out) {
-    if (!c || !out) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (!out) return SAGE_ERR_ARG;
     int rcf = flush_pending(c);
     if (rcf != SAGE_OK) return rcf;
     double acc[8];
@@ -1038,7 +1110,7 @@ int sage_stats(sage_ctx* c, sage_stats_t* out) {
         hipError_t e = launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp, c->d, c->st);
         if (e == hipSuccess)
             e = launch_gram_reduce(c->gram_partial, c->gp, nullptr, nullptr, c->ew.C, false, c->ew.known, c->d, c->st);
-        if (e != hipSuccess) return SAGE_ERR_HIP;
+        if (e != hipSuccess) return hip_failed(c);
         const int NP = c->d.NP, LP = c->d.LP;
         double* diag = (double*)malloc(sizeof(double) * NP);
         if (!diag) return SAGE_ERR_ALLOC;
@@ -1047,7 +1119,7 @@ int sage_stats(sage_ctx* c, sage_stats_t* out) {
         if (e == hipSuccess) e = hipStreamSynchronize(c->st);
         if (e != hipSuccess) {
             free(diag);
-            return SAGE_ERR_HIP;
+            return hip_failed(c);
         }
         for (int r = c->cnt_top; r < c->fill_top; ++r) pending += diag[r];
         for (int r = c->cnt_new; r < c->fill_new; ++r) pending += diag[LP + r];
@@ -1060,12 +1132,14 @@ int sage_stats(sage_ctx* c, sage_stats_t* out) {
     out->frob2 = acc[1] + pending;
     out->last_delta = acc[2];
     out->last_sweeps = (int)acc[3];
+    out->n_unconverged = (int64_t)acc[4];
+    out->last_offdiag = acc[5];
     out->fill = c->fill_top + c->fill_new;
     return SAGE_OK;
 }
 
 int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, double* lam_out, int* n_pad) {
-    if (!c) return SAGE_ERR_ARG;
+    ALIVE(c);
     const int NP = c->d.NP, LP = c->d.LP, ell = c->d.ell;
     if (n_pad) *n_pad = NP;
     if (!C_out && !eig) return SAGE_OK;
@@ -1088,7 +1162,7 @@ int sage_probe_gram_eig(sage_ctx* c, double* C_out, int eig, double* Y_out, doub
 }
 
 int sage_probe_gram_split(sage_ctx* c, double* C_out, int* n_pad) {
-    if (!c) return SAGE_ERR_ARG;
+    ALIVE(c);
     const int NP = c->d.NP, LP = c->d.LP, ell = c->d.ell;
     if (n_pad) *n_pad = NP;
     if (c->gp_cross_split.tiles <= 0 || c->gp_new2_split.tiles <= 0) return SAGE_ERR_STATE;
@@ -1106,7 +1180,8 @@ int sage_probe_gram_split(sage_ctx* c, double* C_out, int* n_pad) {
 }
 
 int sage_probe_eig_matrix(sage_ctx* c, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out) {
-    if (!c || !C_in) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (!C_in) return SAGE_ERR_ARG;
     const int NP = c->d.NP;
     HIPCHK(hipMemcpyAsync(c->ew.C, C_in, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
     HIPCHK(launch_eig(c->ew, NP, JACOBI_TOL_BASIS, MAX_SWEEPS, c->st));
@@ -1120,24 +1195,23 @@ int sage_probe_eig_matrix(sage_ctx* c, const double* C_in, double* Y_out, double
     return SAGE_OK;
 }
 
-int sage_probe_eig_psd(sage_ctx* c, const double* C_in, double* Y_out, double* lam_out, double* sweep_stat_out) {
-    if (!c || !C_in) return SAGE_ERR_ARG;
-    const int NP = c->d.NP;
-    HIPCHK(hipMemcpyAsync(c->ew.C, C_in, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
-    HIPCHK(launch_eig_precond(c->ew, NP, JACOBI_TOL_SHRINK, MAX_SWEEPS, c->st));
-    if (Y_out) HIPCHK(hipMemcpyAsync(Y_out, c->ew.Y, (size_t)NP * NP * sizeof(double), hipMemcpyDeviceToDevice, c->st));
-    if (lam_out)
-        HIPCHK(hipMemcpy2DAsync(lam_out, sizeof(double), c->ew.C, (size_t)(NP + 1) * sizeof(double), sizeof(double), NP,
-                                hipMemcpyDeviceToDevice, c->st));
-    if (sweep_stat_out)
-        HIPCHK(hipMemcpyAsync(sweep_stat_out, c->ew.stat, 18 * sizeof(double), hipMemcpyDeviceToDevice, c->st));
-    HIPCHK(hipStreamSynchronize(c->st));
+int sage_set_sweep_policy(sage_ctx* c, int policy) {
+    ALIVE(c);
+    if (policy != SAGE_SWEEPS_ADAPTIVE && policy != SAGE_SWEEPS_ALL) return SAGE_ERR_ARG;
+    c->sweeps_all = policy == SAGE_SWEEPS_ALL;
     return SAGE_OK;
 }
 
-int sage_set_eig_precondition(sage_ctx* c, int on) {
-    if (!c) return SAGE_ERR_ARG;
-    c->precond = on != 0 && c->d.NP >= 64;
+int sage_set_debug_checks(sage_ctx* c, int on) {
+    ALIVE(c);
+    c->debug_checks = on != 0;
+    return SAGE_OK;
+}
+
+int sage_debug_fail_launch(sage_ctx* c, int nth) {
+    ALIVE(c);
+    if (nth < 0) return SAGE_ERR_ARG;
+    c->fail_in = nth;
     return SAGE_OK;
 }
 
@@ -1148,13 +1222,14 @@ int sage_copy_probe(void* dst, const void* src, int64_t bytes, void* hip_stream)
 }
 
 int sage_profile_enable(sage_ctx* c, int on) {
-    if (!c) return SAGE_ERR_ARG;
+    ALIVE(c);
     c->prof = on != 0;
     return SAGE_OK;
 }
 
 int sage_profile_read(sage_ctx* c, int which, double* ms, int64_t* launches) {
-    if (!c || which < 0 || which >= NCLASS || !ms || !launches) return SAGE_ERR_ARG;
+    ALIVE(c);
+    if (which < 0 || which >= NCLASS || !ms || !launches) return SAGE_ERR_ARG;
     HIPCHK(hipStreamSynchronize(c->st));
     *ms = c->prof_ms[which];
     *launches = c->prof_n[which];

@@ -66,6 +66,8 @@ __device__ __forceinline__ void split3_bf16(float x, float y, unsigned& hi, unsi
 }
 
 // ---- kernel launchers (each enqueues on `st` and returns hipGetLastError()) ---------------------------------
+// launch_util.hip: raise a kernel's dynamic LDS limit, once per (device, kernel); thread-safe
+hipError_t ensure_dynamic_lds(const void* kernel, int bytes);
 // fd_insert.hip
 // copy `rows` batch rows into rows row0.. of a half buffer (half_rows rows per slab)
 hipError_t launch_insert(const void* G, int dtype, int64_t rows, int row0, float* half, int half_rows, const Dims& d,
@@ -78,6 +80,8 @@ hipError_t launch_insert_outer(const void* E, const void* H, int dtype, int64_t 
 hipError_t launch_expand_outer(const void* E, const void* H, int dtype, int64_t C, int64_t dh, int64_t rows, void* out,
                                const Dims& d, hipStream_t st);
 hipError_t launch_plain_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
+// *count += entries of p (n values of the row type) that are not finite
+hipError_t launch_count_nonfinite(const void* p, int dtype, int64_t n, unsigned* count, hipStream_t st);
 hipError_t launch_probe_permute(const double* in, double* out, int NP, int LP, int ell, bool both, hipStream_t st);
 hipError_t launch_export_rows(const float* Bblk, int NPsrc, int nrows, float* out, const Dims& d, hipStream_t st);
 hipError_t launch_import_rows(const float* in, int nrows, float* Bblk, int NPdst, const Dims& d, hipStream_t st);
@@ -101,7 +105,8 @@ GramPlan gram_plan_split(const GramPlan& base, const Dims& d, int groups);
 GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_per_cu);
 hipError_t launch_gram(const float* top, const float* nw, int nfill, float* partial, const GramPlan& p, const Dims& d,
                        hipStream_t st);
-// C = sum of the partial tiles of launch a and (if given) launch b; known_top: the top x top block is diag(known)
+// C = sum of the partial tiles of launch a and (if given) launch b; known_top: the top x top block is `known`
+// (LP x LP, the Gram matrix of the rows the last shrink wrote, see EigWork::known)
 hipError_t launch_gram_reduce(const float* partial_a, const GramPlan& a, const float* partial_b, const GramPlan* b,
                               double* C, bool known_top, const double* known, const Dims& d, hipStream_t st);
 
@@ -116,11 +121,8 @@ struct EigWork {
     double* stat;   // [0] trace, [1..MAXSWEEP] per-sweep max |off| / trace
     int* pos;       // NP: pos[rank] = column of Y holding the rank-th largest eigenvalue
     double* lam;    // NP: eigenvalues sorted descending
-    double* known;  // NP: squared norms of the rows the last shrink wrote (lambda_j - delta, 0 from row ell-1 on)
-    double* L;      // NP x NP: Cholesky factor (launch_eig_precond)
-    double* Ld;     // NP x 64: its diagonal blocks while the factorisation runs
-    int* perm;      // NP: diagonal order of the factorisation
-    double* scal;   // [0] the diagonal shift of the factorisation
+    double* known;  // LP x LP: Gram matrix of the rows the last shrink wrote, diag(w) (Y^T C Y) diag(w): diagonal
+                    // lambda_j - delta (0 from row ell-1 on), off-diagonal whatever the eigensolve left (<= its tolerance)
 };
 constexpr int MAX_SWEEPS = 14;
 // Stopping rule: a sweep records the largest |c_pq| / trace(C) it met before rotating; the solve ends after the
@@ -129,12 +131,11 @@ constexpr int MAX_SWEEPS = 14;
 constexpr double JACOBI_TOL_SHRINK = 1e-7;
 constexpr double JACOBI_TOL_BASIS = 1e-9;
 // max_sweeps <= MAX_SWEEPS sweeps are launched (sweeps after convergence return at once). acc[3] of the coefficient
-// kernels then holds the sweeps that were needed, or max_sweeps + SWEEPS_NOT_CONVERGED when they did not suffice.
+// kernels then holds the sweeps that were needed, or max_sweeps + SWEEPS_NOT_CONVERGED when they did not suffice;
+// acc[4] counts the solves that ended above their tolerance, acc[5] is the last solve's final off-diagonal record.
 constexpr int SWEEPS_NOT_CONVERGED = 100;
 hipError_t launch_eig(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st);
-// fd_chol.hip: the same for a positive semi-definite matrix, through one Cholesky step (fewer sweeps)
-hipError_t launch_eig_precond(const EigWork& w, int NP, double tol, int max_sweeps, hipStream_t st);
-// scalars on device: acc[0] sum_delta, acc[1] frob2, acc[2] last_delta, acc[3] sweeps used (as double)
+// scalars on device: acc[0] sum_delta, acc[1] frob2, acc[2] last_delta, acc[3] sweeps used (as double), acc[4], acc[5]
 // frob2 += diag0 over matrix indices [ra0, ra1) and [rb0, rb1) (the rows not yet counted in ||A||_F^2)
 hipError_t launch_shrink_coeffs(const EigWork& w, int NP, int LP, int ell, int ra0, int ra1, int rb0, int rb1, float* Mt,
                                 double* acc, double tol, hipStream_t st);

@@ -369,12 +369,7 @@ static hipError_t launch_split_t(const T* G, int64_t R, const void* img, float* 
                                  const Dims& d, hipStream_t st) {
     constexpr int KC = 128 / (int)sizeof(T);
     constexpr size_t LDS = (size_t)4 * 2 * NT * 32 * (KC / 8) * 16;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)project_split_kernel<NT, T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)LDS);
-        attr_set = true;
-    }
+    if (hipError_t ea = ensure_dynamic_lds((const void*)project_split_kernel<NT, T>, (int)LDS); ea != hipSuccess) return ea;
     const int64_t chunks = (d.D + KC - 1) / KC;
     dim3 grid((unsigned)(p.row_tiles * p.splits));
     hipLaunchKernelGGL((project_split_kernel<NT, T>), grid, dim3(512), LDS, st, G, R, (const u32x4*)img, partial,
@@ -727,12 +722,7 @@ static hipError_t launch_outer_t(const T* E, const T* H, int64_t R, int64_t C, i
                                  const float* Vblk, float* partial, const ScorePlan& p, hipStream_t st) {
     constexpr int KC = 128 / (int)sizeof(T);
     constexpr size_t LDS = (size_t)3 * 2 * NT * 32 * (KC / 8) * 16;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)project_outer_kernel<NT, T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)LDS);
-        attr_set = true;
-    }
+    if (hipError_t ea = ensure_dynamic_lds((const void*)project_outer_kernel<NT, T>, (int)LDS); ea != hipSuccess) return ea;
     const int64_t Rp = (int64_t)p.row_tiles * 512;
     hipLaunchKernelGGL(transpose_errors_kernel<T>, dim3((unsigned)(Rp / 64), (unsigned)((C + 63) / 64)), dim3(256), 0, st, E,
                        R, (int)C, Rp, (T*)work);

@@ -1,6 +1,8 @@
 // Class-balanced selection (Algorithm 1, "if class balance required"; "Agreement Scoring and Selection", CB-SAGE):
 // per class c the unit centroid u_c of the normalised projections of its rows, alpha_i = <zhat_i, u_c(i)>, and the
-// top k_c rows of every class, k_c = floor(keep * N_c + 0.5).
+// top k_c rows of every class. The k_c share out the budget m = floor(keep * N + 0.5) of the plain selection in
+// proportion to the class sizes (largest-remainder rule, see cb_quota_kernel), so that sum_c k_c = m as Algorithm 1
+// requires.
 //
 // Everything that decides the result is integer work, so the outcome does not depend on timing:
 //   * class sums are accumulated in 64-bit fixed point (zhat * 2^40, |zhat| <= 1, up to 2^23 rows per class) with
@@ -50,11 +52,9 @@ __global__ __launch_bounds__(256) void cb_accumulate_kernel(const float* __restr
     }
 }
 
-// one work-group per class: u_c = S_c / ||S_c|| (0 if S_c = 0), k_c, and the start state of the selects
-__global__ __launch_bounds__(128) void cb_unit_kernel(const long long* __restrict__ sums, const uint32_t* __restrict__ counts,
-                                                      int k, double keep, double* __restrict__ ucls,
-                                                      uint32_t* __restrict__ kc, uint32_t* __restrict__ prefix,
-                                                      uint32_t* __restrict__ remain, uint32_t* __restrict__ misc) {
+// one work-group per class: u_c = S_c / ||S_c|| (0 if S_c = 0)
+__global__ __launch_bounds__(128) void cb_unit_kernel(const long long* __restrict__ sums, int k,
+                                                      double* __restrict__ ucls) {
     __shared__ double red[128];
     const int c = blockIdx.x, j = threadIdx.x;
     const double s = j < k ? (double)sums[(int64_t)c * 128 + j] / CB_SCALE : 0.0;
@@ -66,15 +66,129 @@ __global__ __launch_bounds__(128) void cb_unit_kernel(const long long* __restric
     }
     const double nrm = sqrt(red[0]);
     ucls[(int64_t)c * 128 + j] = nrm > 0.0 ? s / nrm : 0.0;
-    if (j == 0) {
+}
+
+// The class budgets (Algorithm 1, class-balanced branch: sum_c k_c = k). With N_c rows in class c and N in all,
+// m = floor(keep * N + 0.5) as in the plain selection, quota q_c = keep * N_c (fp64), k_c = floor(q_c), and the
+// m - sum_c floor(q_c) rows still to hand out go one each to the classes with the largest fractional part
+// q_c - floor(q_c) (equal parts: the lower class first) among those with k_c < N_c. All of it is exact integer or
+// correctly rounded fp64 work, so the host-side definition gives the same numbers. One work-group of 1024 threads;
+// also sets the start state of the selects (prefix 0, remain k_c) and misc[0] = sum_c k_c.
+__global__ __launch_bounds__(1024) void cb_quota_kernel(const uint32_t* __restrict__ counts, int C, double keep,
+                                                        uint32_t* __restrict__ kc, uint32_t* __restrict__ prefix,
+                                                        uint32_t* __restrict__ remain, uint32_t* __restrict__ misc) {
+#pragma clang fp contract(off)
+    __shared__ unsigned long long red[1024];
+    __shared__ uint32_t hist[256];
+    __shared__ unsigned long long s_pre;
+    __shared__ uint32_t s_rem;
+    const int t = threadIdx.x;
+    auto block_sum = [&](unsigned long long v) {
+        red[t] = v;
+        __syncthreads();
+        for (int w = 512; w >= 1; w >>= 1) {
+            if (t < w) red[t] += red[t + w];
+            __syncthreads();
+        }
+        const unsigned long long r = red[0];
+        __syncthreads();
+        return r;
+    };
+    // The product keep * N_c must be rounded before floor() is subtracted from it. Contracted into a fused
+    // multiply-add (the compiler's default, and __dmul_rn does not stop it) the difference comes from the unrounded
+    // product: other bits than the host-side definition, even a negative "fraction" when keep * N_c rounds up to an
+    // integer.
+    auto quota = [&](uint32_t n) {
+#pragma clang fp contract(off)
+        return keep * (double)n;
+    };
+    auto frac_key = [&](uint32_t n) {  // order-preserving bits of the fractional part (a double in [0, 1))
+#pragma clang fp contract(off)
+        const double q = keep * (double)n;
+        const double f = q - floor(q);
+        return (unsigned long long)__double_as_longlong(f);
+    };
+    unsigned long long nsum = 0, bsum = 0, cand = 0;
+    for (int c = t; c < C; c += 1024) {
         const uint32_t n = counts[c];
-        double x = floor(keep * (double)n + 0.5);
-        uint32_t m = x <= 0.0 ? 0u : (x >= (double)n ? n : (uint32_t)x);
-        kc[c] = m;
-        prefix[c] = 0;
-        remain[c] = m;
-        if (m) atomicAdd(&misc[0], m);
+        const double f = floor(quota(n));
+        const uint32_t b = f <= 0.0 ? 0u : (f >= (double)n ? n : (uint32_t)f);
+        kc[c] = b;
+        nsum += n;
+        bsum += b;
+        cand += b < n;
     }
+    const unsigned long long N = block_sum(nsum), base = block_sum(bsum), ncand = block_sum(cand);
+    double x;
+    {
+#pragma clang fp contract(off)
+        const double kn = keep * (double)N;
+        x = floor(kn + 0.5);
+    }
+    const unsigned long long m = x <= 0.0 ? 0ull : (x >= (double)N ? N : (unsigned long long)x);
+    unsigned long long rem = m > base ? m - base : 0ull;
+    if (rem > ncand) rem = ncand;
+    if (rem > 0) {
+        // radix select of the rem-th largest key among the candidates, a byte at a time from the top
+        if (t == 0) { s_pre = 0ull; s_rem = (uint32_t)rem; }
+        for (int shift = 56; shift >= 0; shift -= 8) {
+            if (t < 256) hist[t] = 0;
+            __syncthreads();
+            const unsigned long long pre = s_pre;
+            for (int c = t; c < C; c += 1024) {
+                if (kc[c] >= counts[c]) continue;
+                const unsigned long long key = frac_key(counts[c]);
+                if (shift == 56 || (key >> (shift + 8)) == pre) atomicAdd(&hist[(key >> shift) & 255ull], 1u);
+            }
+            __syncthreads();
+            if (t == 0) {
+                uint32_t want = s_rem, cum = 0;
+                int chosen = 0;
+                for (int b = 255; b >= 0; --b) {
+                    if (cum + hist[b] >= want) { chosen = b; break; }
+                    cum += hist[b];
+                }
+                s_pre = (pre << 8) | (unsigned long long)chosen;
+                s_rem = want - cum;
+            }
+            __syncthreads();
+        }
+        const unsigned long long T = s_pre;
+        const uint32_t take = s_rem;  // classes exactly on the threshold that still get a row, lowest class first
+        // ordered count of the threshold classes: every thread owns a contiguous run of classes
+        const int chunk = (C + 1023) / 1024;
+        const int c0 = t * chunk, c1 = c0 + chunk < C ? c0 + chunk : C;
+        unsigned long long eq = 0;
+        for (int c = c0; c < c1; ++c) eq += (kc[c] < counts[c] && frac_key(counts[c]) == T);
+        red[t] = eq;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {  // Hillis-Steele inclusive scan
+            const unsigned long long a = t >= o ? red[t - o] : 0ull;
+            __syncthreads();
+            red[t] += a;
+            __syncthreads();
+        }
+        unsigned long long before = red[t] - eq;
+        __syncthreads();
+        for (int c = c0; c < c1; ++c) {
+            if (kc[c] >= counts[c]) continue;
+            const unsigned long long key = frac_key(counts[c]);
+            if (key > T) kc[c] += 1;
+            else if (key == T) {
+                if (before < take) kc[c] += 1;
+                before += 1;
+            }
+        }
+        __syncthreads();
+    }
+    unsigned long long tot = 0;
+    for (int c = t; c < C; c += 1024) {
+        prefix[c] = 0;
+        remain[c] = kc[c];
+        tot += kc[c];
+    }
+    tot = block_sum(tot);
+    if (t == 0) misc[0] = (uint32_t)tot;
 }
 
 // alpha_i = clamp(<zhat_i, u_c(i)>, -1, 1), -0 stored as +0; one wave per row
@@ -281,8 +395,8 @@ hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int
         hipLaunchKernelGGL(cb_accumulate_kernel, dim3((unsigned)blocks), dim3(256), 0, st, zhat, labels, N, k, C, w.counts,
                            w.sums, w.misc);
     }
-    hipLaunchKernelGGL(cb_unit_kernel, dim3(C), dim3(128), 0, st, w.sums, w.counts, k, keep, w.ucls, w.kc, w.prefix,
-                       w.remain, w.misc);
+    hipLaunchKernelGGL(cb_unit_kernel, dim3(C), dim3(128), 0, st, w.sums, k, w.ucls);
+    hipLaunchKernelGGL(cb_quota_kernel, dim3(1), dim3(1024), 0, st, w.counts, C, keep, w.kc, w.prefix, w.remain, w.misc);
     if (N > 0) {
         int64_t blocks = (N + 3) / 4;
         if (blocks > 8192) blocks = 8192;

@@ -1,8 +1,8 @@
 """GPU checks at the full row width of the benchmark workload (config 5: D = 2,049,000 bf16 rows, ell = 256, k = 128,
 batches of 1024), in the launch configuration bench.py times. The CPU oracle cannot run a whole pass at this width
-in a test, so the checks are: the scoring arithmetic against a plain fp64 computation on the same bytes (numpy
-matmul as the one library step, column block by column block), sampled Gram entries computed one by one, and
-properties of the sketch that hold at any size (Method, FD paragraph; Algorithm 1).
+in a test, so it is asked for what it can compute one by one: the projection of sampled rows, Gram entries of sampled
+row pairs, and the consensus / cosine / selection steps on the k-column problem the GPU's projections define; the
+rest are properties of the sketch that hold at any size (Method, FD paragraph; Algorithm 1).
 """
 import numpy as np
 import pytest
@@ -10,19 +10,35 @@ import pytest
 torch = pytest.importorskip("torch")
 
 import oracle  # noqa: E402
+from oracle import Oracle  # noqa: E402
 from paper_2510_02470_amd import inputs  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
 
-def _f64_rows(Gd, lo, hi):
-    """Columns [lo, hi) of a device batch as float64 on the host (bf16 / fp32 widened exactly)."""
-    return Gd[:, lo:hi].to(torch.float32).cpu().numpy().astype(np.float64)
+def _host_rows(Gd, rows):
+    """Rows of a device batch on the host in the oracle's input form (float32, or uint16 bf16 bit patterns)."""
+    sub = Gd[torch.as_tensor(rows, device=Gd.device)]
+    if sub.dtype == torch.bfloat16:
+        return sub.view(torch.int16).cpu().numpy().view(np.uint16)
+    return sub.cpu().numpy()
 
 
-def test_scoring_at_full_width_matches_fp64():
-    """z = V^T g, zhat, consensus, cosine and selection for 2 x 1024 rows of full width against fp64 on the same bytes.
-    Both sides use the same given basis (random rows: the arithmetic does not need it to be orthonormal)."""
+def _oracle_consensus_scores(zhat, keep):
+    """Consensus, cosine and selection by the oracle on stored normalised projections: they are rows of a k-column
+    problem whose basis is the identity (normalising unit rows again changes them by rounding only)."""
+    k = zhat.shape[1]
+    o = Oracle(2, k, 1)
+    o.set_basis(np.eye(k))
+    o.score(np.ascontiguousarray(zhat, dtype=np.float32))
+    idx = o.select(keep)
+    return o.alpha, idx
+
+
+def test_scoring_at_full_width_matches_the_oracle():
+    """z = V^T g and zhat for sampled rows of 2 x 1024 full-width rows against the oracle's projection of the same bytes
+    on the same given basis (random rows: the arithmetic does not need it to be orthonormal); consensus, cosine and
+    selection of all 2048 rows against the oracle run on the stored projections."""
     from paper_2510_02470_amd.binding import Sage
 
     w = inputs.WORKLOADS[5]
@@ -38,33 +54,28 @@ def test_scoring_at_full_width_matches_fp64():
     idx = s.select(0.05).cpu().numpy()
     alpha = s.scores().cpu().numpy()
     zhat = s.zhat().cpu().numpy()
-    # plain definition in fp64, column blocks of 2^16
     N = 2 * w.batch
-    Z = np.zeros((N, w.k))
-    step = 1 << 16
-    for lo in range(0, w.D, step):
-        hi = min(w.D, lo + step)
-        Vb = V[:, lo:hi].cpu().numpy().astype(np.float64)
-        for i, b in enumerate(batches):
-            Z[i * w.batch:(i + 1) * w.batch] += _f64_rows(b, lo, hi) @ Vb.T
-    q = np.sqrt((Z * Z).sum(axis=1))
-    Zh = np.where(q[:, None] > 0, Z / np.where(q > 0, q, 1.0)[:, None], 0.0)
-    ssum = Zh.sum(axis=0)
-    u = ssum / np.sqrt((ssum * ssum).sum())
-    al = np.clip(Zh @ u, -1.0, 1.0)
-    assert np.abs(zhat - Zh).max() <= 1e-5
+    # sampled rows through the oracle's own projection (first and last row of each launch tile included)
+    rng = np.random.default_rng(11)
+    sample = sorted(set(rng.choice(N, size=8, replace=False).tolist()) | {0, 511, 512, w.batch - 1, w.batch, N - 1})
+    o = Oracle(w.ell, w.D, 1)
+    o.set_basis(V.cpu().numpy())
+    for i in sample:
+        o.score(_host_rows(batches[i // w.batch], [i % w.batch]))
+    assert np.abs(zhat[sample] - o.zhat).max() <= 1e-5
+    del o
+    al, oidx = _oracle_consensus_scores(zhat, 0.05)
     assert np.abs(alpha - al).max() <= 1e-4
     m = int(np.floor(0.05 * N + 0.5))
     assert len(idx) == m and idx.tolist() == oracle.topm_f32(alpha, m).tolist()
-    ref = set(np.lexsort((np.arange(N), -al))[:m].tolist())
-    tau = np.sort(al)[::-1][m - 1]
-    for i in set(idx.tolist()) ^ ref:
+    tau = float(np.min(al[oidx]))
+    for i in set(idx.tolist()) ^ set(oidx.tolist()):
         assert abs(al[i] - tau) <= 1e-4
 
 
 def test_update_at_full_width_properties_and_sampled_gram():
     """Three batches (11 shrink cycles, the side-stream path included) at full width: sampled Gram entries against
-    fp64 dot products of the exported rows; after the stream the shrunk rows are orthogonal, row ell-1 on is zero,
+    the oracle's Gram entries (fp64 dot products, one by one) of the exported rows; after the stream the shrunk rows are orthogonal, row ell-1 on is zero,
     and the energy bookkeeping holds: frob2 = sum ||g||^2, ell * sum(delta) <= ||A||_F^2 - ||B||_F^2."""
     from paper_2510_02470_amd.binding import Sage
 
@@ -96,7 +107,7 @@ def test_update_at_full_width_properties_and_sampled_gram():
     rng = np.random.default_rng(5)
     rows = sorted(set(rng.integers(0, ell + 100, size=10).tolist()) | {0, ell - 2, ell, ell + 99})
     Bs = B[rows].cpu().numpy().astype(np.float64)
-    ref = Bs @ Bs.T
+    ref = np.array([[oracle.row_dot(a, b) for b in Bs] for a in Bs])
     got = Cm[np.ix_(rows, rows)]
     scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref))).max()
     assert np.abs(got - ref).max() <= 2e-5 * scale  # fp32 accumulation of ~25,000 products per split
@@ -106,7 +117,7 @@ def test_update_at_full_width_properties_and_sampled_gram():
     cols = sorted(set(rows) | {1, ell - 3})
     Bn = B[rows_new].cpu().numpy().astype(np.float64)
     Bc = B[cols].cpu().numpy().astype(np.float64)
-    ref2 = Bn @ Bc.T
+    ref2 = np.array([[oracle.row_dot(a, b) for b in Bc] for a in Bn])
     got2 = Cs[np.ix_(rows_new, cols)]
     sc2 = np.sqrt(np.outer((Bn * Bn).sum(axis=1), (Bc * Bc).sum(axis=1))).max()
     assert np.abs(got2 - ref2).max() <= 2e-5 * sc2
@@ -119,8 +130,8 @@ def test_update_at_full_width_properties_and_sampled_gram():
 
 def test_factored_scoring_at_full_width():
     """sage_score_outer at the headline shape (1000 classes x 2048 features + 1000 biases = 2,049,000 columns, bf16,
-    k = 128, 2 x 1024 rows): zhat of sampled rows against fp64 on the rows the oracle writes out from the factors, and
-    all scores against the row-major entry point fed with the same rows written out on the device."""
+    k = 128, 2 x 1024 rows): zhat of sampled rows against the oracle's projection of the rows it writes out from the
+    factors, and all scores against the row-major entry point fed with the same rows written out on the device."""
     from paper_2510_02470_amd.binding import Sage
 
     w = inputs.WORKLOADS[5]
@@ -139,22 +150,17 @@ def test_factored_scoring_at_full_width():
     alpha = s.scores().cpu().numpy()
     zhat = s.zhat().cpu().numpy()
     assert idx.tolist() == oracle.topm_f32(alpha, len(idx)).tolist()
-    # fp64 projection of sampled rows, written out by the oracle's definition of the rows
+    # sampled rows, written out by the oracle's definition of the rows and projected by the oracle
     rng = np.random.default_rng(8)
-    sample = np.sort(rng.choice(2 * w.batch, size=24, replace=False))
+    sample = np.sort(rng.choice(2 * w.batch, size=12, replace=False))
     Eh = torch.cat([f[0] for f in fac]).view(torch.int16).cpu().numpy().view(np.uint16)
     Hh = torch.cat([f[1] for f in fac]).view(torch.int16).cpu().numpy().view(np.uint16)
-    Z = np.zeros((len(sample), w.k))
-    for lo in range(0, len(sample), 8):
-        rows = inputs.bf16_bits_to_f32(oracle.last_layer_rows(Eh[sample[lo:lo + 8]], Hh[sample[lo:lo + 8]]))
-        step = 1 << 18
-        for c0 in range(0, w.D, step):
-            c1 = min(w.D, c0 + step)
-            Z[lo:lo + 8] += rows[:, c0:c1].astype(np.float64) @ V[:, c0:c1].cpu().numpy().astype(np.float64).T
-        del rows
-    q = np.sqrt((Z * Z).sum(axis=1))
-    Zh = Z / q[:, None]
-    assert np.abs(zhat[sample] - Zh).max() <= 1e-5
+    o = Oracle(w.ell, w.D, 1)
+    o.set_basis(V.cpu().numpy())
+    for lo in range(0, len(sample), 4):
+        o.score(oracle.last_layer_rows(Eh[sample[lo:lo + 4]], Hh[sample[lo:lo + 4]]))
+    assert np.abs(zhat[sample] - o.zhat).max() <= 1e-5
+    del o
     # the row-major entry point on the same rows (written out on the device, rounded to bf16 like stored rows)
     s.set_basis(V)
     for E, H, _ in fac:

@@ -178,6 +178,43 @@ def test_modes_agree_on_cfg1_shape():
     assert res[0][2].tolist() == res[1][2].tolist()
 
 
+def test_row_dot_is_the_plain_dot_product():
+    """The Gram entry the Gram route forms: exact on integer vectors, and equal to the correctly rounded sum
+    (math.fsum) to a few ulp on random ones."""
+    import math
+
+    rng = np.random.default_rng(2)
+    a = rng.integers(-1000, 1000, size=5000).astype(np.float64)
+    b = rng.integers(-1000, 1000, size=5000).astype(np.float64)
+    assert oracle.row_dot(a, b) == float(int(a.astype(np.int64) @ b.astype(np.int64)))
+    x, y = rng.standard_normal(20000), rng.standard_normal(20000)
+    exact = math.fsum((x * y).tolist())     # each product rounded once, then summed exactly
+    assert abs(oracle.row_dot(x, y) - exact) <= 1e-13 * float(np.abs(x * y).sum())
+    assert oracle.row_dot(x, x) > 0 and oracle.row_dot(x, y) == oracle.row_dot(y, x)
+
+
+@pytest.mark.parametrize("ell,D,cycles,dtype", [(64, 1024, 4, "f32"), (128, 600, 3, "bf16")])
+def test_modes_agree_at_larger_sketch_sizes(ell, D, cycles, dtype):
+    """The Gram route (mode 1), which the long GPU parity runs and the full-size fixtures use, against the one-sided
+    Jacobi on the rows (mode 0, the definition) at ell = 64 and ell = 128, on slowly decaying spectra like those of the
+    second and third workload: the same sketch covariance and sum(delta) to 1e-10 relative, and the same top-k energy."""
+    w = inputs.WORKLOADS[3].scaled(N=ell * (cycles + 1) + 29, D=D, ell=ell, k=ell // 2, batch=300, r=3 * ell // 2, dtype=dtype)
+    G = inputs.generate_numpy(w)
+    A = inputs.bf16_bits_to_f32(G) if G.dtype == np.uint16 else G
+    fro = (A.astype(np.float64) ** 2).sum()
+    res = []
+    for mode in (0, 1):
+        o = Oracle(w.ell, w.D, mode)
+        for lo in range(0, w.N, w.batch):
+            o.update(G[lo:lo + w.batch])
+        o.basis(w.k)
+        res.append((o.B.T @ o.B, o.sum_delta, o.sig2.copy(), o.n_shrinks))
+    assert res[0][3] == res[1][3] == cycles
+    assert np.abs(res[0][0] - res[1][0]).max() <= 1e-10 * fro
+    assert abs(res[0][1] - res[1][1]) <= 1e-10 * fro
+    assert np.abs(res[0][2] - res[1][2]).max() <= 1e-10 * fro
+
+
 def test_orthogonal_invariance():
     """Right-multiplying every row by an orthogonal Q leaves sum(delta), the scores and the selection unchanged."""
     rng = np.random.default_rng(13)
@@ -416,8 +453,9 @@ def test_weighted_basis_is_the_sketch_a_shrink_would_write(mode):
 # ---------------------------------------------------------------- class-balanced selection (CB-SAGE)
 def test_cb_selection_matches_per_class_plain_selection():
     """Algorithm 1, "if class balance required". Pins: (1) with one class it is the plain selection; (2) class by class
-    it equals the plain (already pinned) scoring + selection run on that class's rows alone with the same basis;
-    (3) k_c = floor(keep*N_c + 0.5) rows per class exactly; (4) renaming the classes changes nothing."""
+    the scores equal the plain (already pinned) scoring run on that class's rows alone with the same basis, and the kept
+    rows are the plain top-m of those scores with m = the class budget; (3) the budgets sum to the plain selection's m;
+    (4) renaming the classes leaves every score unchanged."""
     rng = np.random.default_rng(77)
     ell, D, k, N, Cn = 8, 30, 4, 90, 5
     A = lowrank_rows(rng, N, D, 6, noise=0.1)
@@ -438,23 +476,60 @@ def test_cb_selection_matches_per_class_plain_selection():
     # (2), (3) class by class through the plain path
     al, idx = o.select_cb(0.3, labels, Cn)
     got = set(idx.tolist())
+    budgets = oracle.cb_budgets([int((labels == c).sum()) for c in range(Cn)], 0.3)
+    assert budgets.sum() == len(plain_idx) == len(idx)
     for c in range(Cn):
         rows = np.nonzero(labels == c)[0]
         if rows.size == 0:
+            assert budgets[c] == 0
             continue
         oc = Oracle(ell, D, 1)
         oc.set_basis(V)
         oc.score(A[rows])
-        sub = oc.select(0.3)
+        oc.select(0.3)
         assert np.abs(oc.alpha - al[rows]).max() <= 1e-12
+        sub = oracle.topm_f32(oc.alpha.astype(np.float32), int(budgets[c]))
         assert sorted(rows[sub].tolist()) == sorted(i for i in got if labels[i] == c)
-        assert len(sub) == oracle.keep_count(0.3, rows.size)
     assert idx.tolist() == sorted(idx.tolist())
     assert (al <= 1).all() and (al >= -1).all()
     # (4) renaming classes
     perm = rng.permutation(Cn)
     al2, idx2 = o.select_cb(0.3, perm[labels], Cn)
-    assert np.array_equal(al2, al) and idx2.tolist() == idx.tolist()
+    assert np.array_equal(al2, al) and len(idx2) == len(idx)
+
+
+def test_cb_budgets_sum_to_the_subset_size():
+    """Algorithm 1, class-balanced branch: "sum_c k_c = k". The largest-remainder budgets against an exact rational
+    re-statement of the rule (keep rates that are dyadic, so that keep * N_c is exact in fp64 too), and the properties
+    that hold for any rate: the sum is the plain m, every class is within one row of its share, none above its size."""
+    from fractions import Fraction
+
+    rng = np.random.default_rng(5)
+    for keep in (0.25, 0.375, 0.0625, 0.5, 1.0, 0.0):
+        for trial in range(20):
+            Cn = int(rng.integers(1, 40))
+            counts = rng.integers(0, 30, size=Cn)
+            got = oracle.cb_budgets(counts, keep)
+            kf = Fraction(keep)
+            N = int(counts.sum())
+            m = min(N, max(0, int(kf * N + Fraction(1, 2))))          # floor(keep N + 1/2), exactly
+            base = [int(kf * int(n)) for n in counts]
+            frac = [kf * int(n) - b for n, b in zip(counts, base)]
+            order = sorted((c for c in range(Cn) if base[c] < counts[c]), key=lambda c: (-frac[c], c))
+            for c in order[: m - sum(base)]:
+                base[c] += 1
+            assert got.tolist() == base and got.sum() == m
+    for keep in (0.01, 0.05, 0.1, 0.3, 0.77):
+        counts = rng.integers(0, 200, size=300)
+        got = oracle.cb_budgets(counts, keep)
+        assert got.sum() == oracle.keep_count(keep, int(counts.sum()))
+        assert (got <= counts).all() and (np.abs(got - keep * counts) < 1.0).all()
+    # many small classes at a low rate: rounding every class on its own would keep nothing at all
+    counts = np.full(1000, 20)
+    counts[:480] += 1                                                   # 20,480 rows
+    got = oracle.cb_budgets(counts, 0.01)
+    assert got.sum() == 205 and got.max() == 1
+    assert got[:480].sum() == 205                                       # the larger classes have the larger remainders
 
 
 def test_sketches_merge_with_added_bounds():
