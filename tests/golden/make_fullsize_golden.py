@@ -16,8 +16,10 @@ the oracle's sketch that are in use (stored as float32: a relative change of 6e-
 covariance), its counters, the squared singular values of the frozen buffer, the consensus direction, every score and
 the selection.
 
-Run from the repository root:   python tests/golden/make_fullsize_golden.py [cfg2_full] [ell256_cycles] [--mode 0|1]
-(mode 1, the default: fp64 Gram + two-sided Jacobi; mode 0: one-sided Jacobi on the rows, several times slower.)
+Run from the repository root:   python tests/golden/make_fullsize_golden.py [names ...] [--mode 0|1]
+mode 1 (fp64 Gram + two-sided Jacobi) or mode 0 (one-sided Jacobi on the rows: the definition, several times slower).
+Without --mode every stream takes the route its committed fixture was written with: cfg2_full mode 0 (eight minutes on
+eight cores; tests/test_golden.py holds the Gram route to it), the other two mode 1.
 Calls only oracle/ and the seeded input generator; never the HIP library.
 """
 import os
@@ -77,8 +79,11 @@ def run(name, mode):
     print("wrote %s (%d bytes)" % (path, os.path.getsize(path)), flush=True)
 
 
+DEFAULT_MODE = {"cfg2_full": 0, "cfg3_full": 1, "ell256_cycles": 1}
+
+
 def main(argv):
-    mode = 1
+    mode = None
     names = []
     it = iter(argv)
     for a in it:
@@ -87,7 +92,7 @@ def main(argv):
         else:
             names.append(a)
     for name in names or list(workloads()):
-        run(name, mode)
+        run(name, DEFAULT_MODE[name] if mode is None else mode)
 
 
 if __name__ == "__main__":
