@@ -21,6 +21,10 @@ def build_oracle(force=False):
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
+        # the sanitizer driver (tests build it again with -fsanitize): compiled here so that a build covers every C file
+        os.makedirs(os.path.join(_HERE, "_build"), exist_ok=True)
+        subprocess.run(["gcc", "-O2", "-fopenmp", "-std=c11", "-o", os.path.join(_HERE, "_build", "sanitize_check"),
+                        os.path.join(_HERE, "sanitize_check.c"), _SRC, "-lm"], check=True)
     return _LIB
 
 

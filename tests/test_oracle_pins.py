@@ -602,3 +602,23 @@ def test_last_layer_rows_gram_closed_form_and_bf16_rounding():
     prod = (e[:, :, None] * h[:, None, :]).reshape(16, -1)  # exact in float32
     ref = torch.cat([prod, e], dim=1).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(got, ref)
+
+
+# ---------------------------------------------------------------- host-side sanitizer run
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """oracle/sanitize_check.c drives every entry point of the oracle (both SVD routes, shrink cycles, bases, scoring of
+    fp32 and bf16 rows, selection, error returns) in a build with -fsanitize=address,undefined: an out-of-bounds
+    access, a leak or an undefined operation anywhere in it ends the run with a non-zero status."""
+    import os
+    import subprocess
+
+    src = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)))
+    exe = str(tmp_path / "sanitize_check")
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-static-libasan", "-o", exe, os.path.join(src, "sanitize_check.c"), os.path.join(src, "sage_oracle.c"), "-lm"]
+    b = subprocess.run(cmd, capture_output=True, text=True)
+    if b.returncode != 0 and "asan" in b.stderr.lower():
+        pytest.skip("this gcc has no AddressSanitizer runtime: " + b.stderr.strip().splitlines()[-1])
+    assert b.returncode == 0, b.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "sanitize_check ok" in r.stdout, r.stdout + r.stderr
