@@ -1,5 +1,6 @@
-"""GPU checks at the full row width of the benchmark workload (config 5: D = 2,049,000 bf16 rows, ell = 256, k = 128,
-batches of 1024), in the launch configuration bench.py times. The CPU oracle cannot run a whole pass at this width
+"""GPU checks at the full row width of the two workloads at the metric's sketch size (config 5, the benchmark's headline:
+D = 2,049,000 bf16 rows, ell = 256, k = 128, batches of 1024; config 4: D = 1,048,576 fp32 rows, batches of 512), in
+the launch configuration bench.py times. The CPU oracle cannot run a whole pass at this width
 in a test, so it is asked for what it can compute one by one: the projection of sampled rows, Gram entries of sampled
 row pairs, and the consensus / cosine / selection steps on the k-column problem the GPU's projections define; the
 rest are properties of the sketch that hold at any size (Method, FD paragraph; Algorithm 1).
@@ -35,15 +36,17 @@ def _oracle_consensus_scores(zhat, keep):
     return o.alpha, idx
 
 
-def test_scoring_at_full_width_matches_the_oracle():
-    """z = V^T g and zhat for sampled rows of 2 x 1024 full-width rows against the oracle's projection of the same bytes
+@pytest.mark.parametrize("cfg", [5, 4])
+def test_scoring_at_full_width_matches_the_oracle(cfg):
+    """z = V^T g and zhat for sampled rows of two full-width batches against the oracle's projection of the same bytes
     on the same given basis (random rows: the arithmetic does not need it to be orthonormal); consensus, cosine and
-    selection of all 2048 rows against the oracle run on the stored projections."""
+    selection of all rows against the oracle run on the stored projections."""
     from paper_2510_02470_amd.binding import Sage
 
-    w = inputs.WORKLOADS[5]
+    w = inputs.WORKLOADS[cfg]
     ds = inputs.DeviceStream(w, w_dtype=torch.bfloat16)
     batches = [ds.batch(b) for b in range(2)]
+    del ds
     g = torch.Generator(device="cuda")
     g.manual_seed(12345)
     V = torch.randn((w.k, w.D), generator=g, device="cuda", dtype=torch.float32) / np.sqrt(w.D)
@@ -57,7 +60,7 @@ def test_scoring_at_full_width_matches_the_oracle():
     N = 2 * w.batch
     # sampled rows through the oracle's own projection (first and last row of each launch tile included)
     rng = np.random.default_rng(11)
-    sample = sorted(set(rng.choice(N, size=8, replace=False).tolist()) | {0, 511, 512, w.batch - 1, w.batch, N - 1})
+    sample = sorted(set(rng.choice(N, size=8, replace=False).tolist()) | {0, 511, 512 % N, w.batch - 1, w.batch, N - 1})
     o = Oracle(w.ell, w.D, 1)
     o.set_basis(V.cpu().numpy())
     for i in sample:
@@ -73,28 +76,29 @@ def test_scoring_at_full_width_matches_the_oracle():
         assert abs(al[i] - tau) <= 1e-4
 
 
-def test_update_at_full_width_properties_and_sampled_gram():
-    """Three batches (11 shrink cycles, the side-stream path included) at full width: sampled Gram entries against
+@pytest.mark.parametrize("cfg,n_batches,cycles", [(5, 3, 11), (4, 6, 11)])
+def test_update_at_full_width_properties_and_sampled_gram(cfg, n_batches, cycles):
+    """3 x 1024 (config 5) or 6 x 512 (config 4) rows, 11 shrink cycles, the side-stream path included, at full width: sampled Gram entries against
     the oracle's Gram entries (fp64 dot products, one by one) of the exported rows; after the stream the shrunk rows are orthogonal, row ell-1 on is zero,
     and the energy bookkeeping holds: frob2 = sum ||g||^2, ell * sum(delta) <= ||A||_F^2 - ||B||_F^2."""
     from paper_2510_02470_amd.binding import Sage
 
-    w = inputs.WORKLOADS[5]
+    w = inputs.WORKLOADS[cfg]
     ell = w.ell
     ds = inputs.DeviceStream(w, w_dtype=torch.bfloat16)
     s = Sage(ell, w.D, dtype=w.dtype)
     fro = 0.0
-    for b in range(3):
+    for b in range(n_batches):
         G = ds.batch(b)
         fro += float((G.to(torch.float32).double() ** 2).sum())
         s.fd_update(G)
     # 100 more rows so that the buffer holds shrunk rows and raw rows
-    G = ds.batch(3, rows=100)
+    G = ds.batch(n_batches, rows=100)
     fro += float((G.to(torch.float32).double() ** 2).sum())
     s.fd_update(G)
     del G
     st = s.stats()
-    assert st.n_shrinks == 11 and st.fill == ell + 100 and st.rows_seen == 3 * w.batch + 100
+    assert st.n_shrinks == cycles and st.fill == ell + 100 and st.rows_seen == n_batches * w.batch + 100
     assert abs(st.frob2 - fro) <= 1e-5 * fro
     assert 0.0 <= st.sum_delta <= fro / ell
     B = s.sketch()
@@ -174,3 +178,37 @@ def test_factored_scoring_at_full_width():
     s.select(0.05)
     assert np.abs(s.zhat().cpu().numpy() - zhat).max() <= 1e-5
     assert np.abs(s.scores().cpu().numpy() - alpha).max() <= 1e-4
+
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_one_shrink_at_full_width_against_the_oracle(cfg):
+    """The exact shapes of the two workloads at the metric's sketch size (config 4: D = 1,048,576 fp32 rows; config 5:
+    D = 2,049,000 bf16 rows; ell = 256): the first 612 rows of the stream -- buffer fill, one shrink, 100 more rows --
+    through the oracle's Gram route on the host (half a minute to a minute: a full-width shrink is 1 to 2e12 fp64 flop
+    in plain loops) and through the GPU path in the launch configuration of the benchmark; sketch covariance to the
+    1e-4 bar, sum(delta), counters."""
+    from paper_2510_02470_amd.binding import Sage
+    from helpers import cov_diff_spec_norm
+
+    w = inputs.WORKLOADS[cfg]
+    ds = inputs.DeviceStream(w, w_dtype=torch.bfloat16)
+    parts = [ds.batch(0, rows=2 * w.ell), ds.batch(1, rows=100)]
+    del ds
+    s = Sage(w.ell, w.D, dtype=w.dtype)
+    o = Oracle(w.ell, w.D, 1)
+    fro = 0.0
+    for G in parts:
+        s.fd_update(G)
+        Gh = _host_rows(G, list(range(G.shape[0])))
+        fro += float((G.to(torch.float32).double() ** 2).sum())
+        print("oracle: %d rows of width %d ..." % (Gh.shape[0], w.D), flush=True)
+        o.update(Gh)
+        del Gh
+    del parts
+    st = s.stats()
+    assert st.n_shrinks == o.n_shrinks == 1 and st.fill == o.fill == w.ell + 100 and st.n_unconverged == 0
+    # (frob2 is the sum of the Gram diagonal: dot products of D terms with fp32 accumulation inside a column range)
+    assert abs(st.sum_delta - o.sum_delta) <= 1e-5 * fro and abs(st.frob2 - fro) <= 5e-5 * fro
+    Bg = s.sketch().cpu().numpy()[:st.fill]
+    err = cov_diff_spec_norm(Bg, o.B[:o.fill]) / fro
+    print("one shrink at D = %d: covariance error %.3g" % (w.D, err), flush=True)
+    assert err <= 1e-4, err
