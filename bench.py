@@ -168,6 +168,11 @@ def run_workload(torch, inputs, Sage, w, K, W, split=True, labels_classes=None, 
     score_bytes_row = esz * D + 4.0 * k * D / w.batch + 4.0 * k
     LP = padded(ell)
     split_rebuild, split_gram = split and LP in (128, 256), split and LP == 256
+    # Rows of a bf16 stream have one bf16 part, not three: the split kernels issue 3 products (not 6) where a buffered
+    # stream row is one factor and 1 where both are (the products left out are exact zeros).
+    one_part = w.dtype == "bf16"
+    rebuild_products = (6.0 + 3.0) / 2.0 if one_part else 6.0                  # top half 6, new half 3
+    gram_products = (16 * 3.0 + 10 * 1.0) / 26.0 if one_part else 6.0          # 16 tiles new x top, 10 tiles new x new
     res.update({
         "K": K, "W": W, "rows": rows, "value": rows / (total_ms * 1e-3), "ms_per_step": total_ms / K,
         "update_rows_per_s": upd_rows_s,
@@ -183,7 +188,9 @@ def run_workload(torch, inputs, Sage, w, K, W, split=True, labels_classes=None, 
         "ms": {"update": ms_update, "basis": ms_basis, "score": ms_score, "select": ms_select, "wall": wall * 1e3},
         "selected": int(idx.numel()), "jacobi_sweeps_last": st.last_sweeps, "n_shrinks": int(st.n_shrinks),
         "unconverged_solves": int(st.n_unconverged),
-        "update_arithmetic": ("fp32 values as three bf16 parts, 6 bf16 MFMA products per fp32 product (fp32 accuracy)"
+        "update_arithmetic": (("fp32 values as three bf16 parts, 6 bf16 MFMA products per fp32 product (fp32 accuracy)"
+                               + ("; bf16 stream rows have one part: 3 products where one factor is such a row, 1 where "
+                                  "both are (same bits)" if one_part else ""))
                               if split_rebuild else "fp32 MFMA"),
     })
     s.close()
@@ -198,8 +205,8 @@ def run_workload(torch, inputs, Sage, w, K, W, split=True, labels_classes=None, 
         mm_peak_g = PEAK_MFMA_BF16 if split_gram else PEAK_MFMA_F32
         mm_peak_r = PEAK_MFMA_BF16 if split_rebuild else PEAK_MFMA_F32
         algo = {   # (bound, algorithmic work per launch / cycle, peak of the unit that executes it, instructions' factor)
-            "gram": ("mfma", gram_tiles * tile_flop, mm_peak_g, 6.0 if split_gram else 1.0),
-            "rebuild": ("mfma", rebuild_flop, mm_peak_r, 6.0 if split_rebuild else 1.0),
+            "gram": ("mfma", gram_tiles * tile_flop, mm_peak_g, gram_products if split_gram else 1.0),
+            "rebuild": ("mfma", rebuild_flop, mm_peak_r, rebuild_products if split_rebuild else 1.0),
             "project": ("hbm", w.batch * (esz * D + 4.0 * k) + 4.0 * k * D, PEAK_HBM, 1.0),
             "insert": ("hbm", (esz + 4.0) * ell * D, PEAK_HBM, 1.0),
         }
@@ -238,7 +245,8 @@ def run_workload(torch, inputs, Sage, w, K, W, split=True, labels_classes=None, 
                 e["frac"] = rate / peak
                 e["peak"] = peak / (1e12 if bound == "mfma" else 1e9)
                 if bound == "mfma":
-                    e["executed_frac"] = rate * factor / peak   # matrix-core instructions issued (x6 when emulating fp32)
+                    e["executed_frac"] = rate * factor / peak   # matrix-core instructions issued (emulating fp32: x6,
+                    e["products_per_fp32_product"] = factor     # less where a factor has one bf16 part)
             if traffic and name in traffic:
                 e["traffic"] = traffic[name]
             kern[name] = e
@@ -248,7 +256,8 @@ def run_workload(torch, inputs, Sage, w, K, W, split=True, labels_classes=None, 
             fp32_equiv = rebuild_flop / (g["avg_ms"] * 1e-3)
             res["roofline"] = {
                 "kernel": ("rebuild_split_kernel (B[0:ell] <- diag(w) Y^T B on the bf16 matrix cores: fp32 values as three "
-                           "bf16 parts, 6 bf16 products per fp32 product; the longest single kernel of a cycle)")
+                           "bf16 parts, %.1f bf16 products per fp32 product; the longest single kernel of a cycle)"
+                           % rebuild_products)
                 if split_rebuild else "rebuild_kernel (B[0:ell] <- diag(w) Y^T B, fp32 MFMA; the longest single kernel of a cycle)",
                 "bound": "mfma", "achieved": g["achieved"], "peak": g["peak"], "unit": "TFLOP/s",
                 # the method's flops (2 ell n D per launch) over the peak of the unit that executes them
@@ -258,7 +267,7 @@ def run_workload(torch, inputs, Sage, w, K, W, split=True, labels_classes=None, 
                 "fp32_equivalent_over_fp32_peak": fp32_equiv / PEAK_MFMA_F32,
                 "traffic": g.get("traffic"), "avg_launch_ms": g["avg_ms"], "launches": g["launches"],
                 "algorithmic_flop_per_launch": rebuild_flop,
-                "executed_flop_per_launch": rebuild_flop * (6.0 if split_rebuild else 1.0),
+                "executed_flop_per_launch": rebuild_flop * (rebuild_products if split_rebuild else 1.0),
             }
     del batches, labels
     torch.cuda.empty_cache()

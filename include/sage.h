@@ -247,9 +247,13 @@ int sage_set_projection_mode(sage_ctx* ctx, int mode);
  * fp32 -- the fp32 result to within a few 2^-24 per term, at a multiple of the fp32 matrix-core rate. It is used where
  * a kernel exists: the rebuild for ell >= 97 (padded sketch size 128 or 256), the Gram blocks of the steady state
  * (new rows x top rows, new rows x new rows) for ell >= 193 (padded size 256); everything else, and everything under
- * SAGE_MM_F32, runs on the fp32 matrix cores. May be changed at any time between calls.
+ * SAGE_MM_F32, runs on the fp32 matrix cores. Rows that arrive through sage_fd_update or sage_fd_update_outer in a bf16 context
+ * are bf16 values kept as fp32: they have one part, not three, and the split kernels leave out the products with their (zero) second
+ * and third parts -- three products instead of six wherever a buffered row of the stream is a factor, with the same
+ * bits as the result. SAGE_MM_SPLIT_ALL_PARTS is SAGE_MM_SPLIT without that shortcut (a check that the bits are indeed
+ * the same, and the rate fp32 rows would see). May be changed at any time between calls.
  */
-typedef enum { SAGE_MM_F32 = 0, SAGE_MM_SPLIT = 1 } sage_mm_mode;
+typedef enum { SAGE_MM_F32 = 0, SAGE_MM_SPLIT = 1, SAGE_MM_SPLIT_ALL_PARTS = 2 } sage_mm_mode;
 int sage_set_update_arithmetic(sage_ctx* ctx, int mode);
 
 /* View of the scores of the last sage_select: *alpha receives a DEVICE pointer to N fp32 owned by the library,

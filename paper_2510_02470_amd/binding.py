@@ -157,8 +157,9 @@ class Sage:
         _check(self.L.sage_fd_merge(self.h, _ptr(B_other), B_other.shape[0]), "sage_fd_merge")
 
     def set_update_arithmetic(self, split):
-        """True: the rebuild runs on the bf16 matrix cores with three-way split factors; False: fp32 matrix cores."""
-        _check(self.L.sage_set_update_arithmetic(self.h, 1 if split else 0), "sage_set_update_arithmetic")
+        """True / 1: the shrink's dense products run on the bf16 matrix cores with three-way split factors; False / 0:
+        fp32 matrix cores; 2: split factors without the one-part shortcut for bf16 rows (same bits as 1)."""
+        _check(self.L.sage_set_update_arithmetic(self.h, int(split)), "sage_set_update_arithmetic")
 
     def _factors(self, E, H):
         for t in (E, H):

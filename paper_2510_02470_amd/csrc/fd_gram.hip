@@ -304,6 +304,10 @@ __global__ __launch_bounds__(256, 2) void gram_cross8_kernel(const float* __rest
 // instructions (all waves of a work-group run in step: conversions done in one block would leave the matrix cores
 // idle), from registers that were loaded a stage earlier and are reloaded, for the slab after next, as soon as they
 // have been consumed.
+// NEW1: every new row in use is a bf16 value stored as fp32 (rows of a bf16 stream): its mid and lo parts are zero, so
+// only its hi part is staged and only the three products with it are issued. The three left out would add exact
+// zeros: the result has the same bits either way.
+template <bool NEW1>
 __global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* __restrict__ top,
                                                                    const float* __restrict__ nw, int nfill,
                                                                    float* __restrict__ partial, int64_t slabs_total,
@@ -356,10 +360,14 @@ __global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* 
         pre[it] = src[it] >= 0 ? base[src[it]] : f32x4{0.f, 0.f, 0.f, 0.f};
     };
     auto store1 = [&](int it, int buf) __attribute__((always_inline)) {
+        uint2* d = reinterpret_cast<uint2*>(ldsx + buf * STAGE16) + dst8[it];
+        if (NEW1 && it >= 2) {  // new rows (pieces 1024 ..)
+            d[0] = make_uint2(hi_bf16(pre[it][0], pre[it][1]), hi_bf16(pre[it][2], pre[it][3]));
+            return;
+        }
         unsigned a0, a1, a2, b0, b1, b2;
         split3_bf16(pre[it][0], pre[it][1], a0, a1, a2);
         split3_bf16(pre[it][2], pre[it][3], b0, b1, b2);
-        uint2* d = reinterpret_cast<uint2*>(ldsx + buf * STAGE16) + dst8[it];
         d[0] = make_uint2(a0, b0);
         d[2 * PART16] = make_uint2(a1, b1);
         d[4 * PART16] = make_uint2(a2, b2);
@@ -375,28 +383,42 @@ __global__ __launch_bounds__(512, 1) void gram_cross8_split_kernel(const float* 
     }
     __syncthreads();
 
+    constexpr int AP = NEW1 ? 1 : 3;  // parts of a new row
+    constexpr int NQ = NEW1 ? 3 : 6;  // products
     for (int64_t s = s0; s < s1; ++s) {
         const int cur = (int)((s - s0) & 1);
         const u32x4* st = ldsx + cur * STAGE16 + h * HREG;
-        u32x4 a[4][3], b[2][3];
+        u32x4 a[4][AP], b[2][3];
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
+            if (p < AP) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i][p] = st[p * PART16 + arow + 32 * i];
+                for (int i = 0; i < 4; ++i) a[i][p] = st[p * PART16 + arow + 32 * i];
+            }
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) b[cb][p] = st[p * PART16 + brow + 32 * cb];
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {  // in the order the parts were read: the first group needs the hi parts only
+        for (int q = 0; q < NQ; ++q) {  // in the order the parts were read: the first group needs the hi parts only
             constexpr int PA[6] = {0, 0, 1, 1, 0, 2}, PB[6] = {0, 1, 0, 1, 2, 0};
+            const int pa = NEW1 ? 0 : PA[q], pb = NEW1 ? q : PB[q];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb) acc[i][cb] = mfma_bf16(a[i][PA[q]], b[cb][PB[q]], acc[i][cb]);
-            if (q < 4) {  // slab s + 1 into the other buffer, slab s + 2 on its way
+                for (int cb = 0; cb < 2; ++cb) acc[i][cb] = mfma_bf16(a[i][pa], b[cb][pb], acc[i][cb]);
+            // slab s + 1 into the other buffer, slab s + 2 on its way
+            if (!NEW1 && q < 4) {
                 store1(q, cur ^ 1);
                 fetch1(q, s + 2);
+            }
+            if (NEW1) {
+                store1(q, cur ^ 1);
+                fetch1(q, s + 2);
+                if (q == 2) {
+                    store1(3, cur ^ 1);
+                    fetch1(3, s + 2);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -554,8 +576,8 @@ __global__ __launch_bounds__(256, 2) void gram_new8_kernel(const float* __restri
 // The same triangle on the bf16 matrix cores with three-way split values (see gram_cross8_split_kernel): the new rows
 // of a slab are split when they are staged ([part][k-half][row] pieces, 24 KB per stage), a wave's six operand row
 // blocks are 18 LDS reads per 54 matrix-core instructions, and the next slab is split and stored between the six
-// groups of matrix-core instructions.
-template <int W>
+// groups of matrix-core instructions. NEW1 (see gram_cross8_split_kernel): one part, one product.
+template <int W, bool NEW1>
 __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ Nv, int nfill, float* __restrict__ partial,
                                                      int group, int64_t s0, int64_t s1, u32x4* lds) {
     using M = New8Map<W>;
@@ -585,10 +607,14 @@ __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ N
         pre[it] = src[it] >= 0 ? Nv[sc * HALF4 + src[it]] : f32x4{0.f, 0.f, 0.f, 0.f};
     };
     auto store1 = [&](int it, int buf) __attribute__((always_inline)) {
+        uint2* d = reinterpret_cast<uint2*>(lds + buf * STAGE16) + dst8[it];
+        if (NEW1) {
+            d[0] = make_uint2(hi_bf16(pre[it][0], pre[it][1]), hi_bf16(pre[it][2], pre[it][3]));
+            return;
+        }
         unsigned a0, a1, a2, b0, b1, b2;
         split3_bf16(pre[it][0], pre[it][1], a0, a1, a2);
         split3_bf16(pre[it][2], pre[it][3], b0, b1, b2);
-        uint2* d = reinterpret_cast<uint2*>(lds + buf * STAGE16) + dst8[it];
         d[0] = make_uint2(a0, b0);
         d[2 * PART16] = make_uint2(a1, b1);
         d[4 * PART16] = make_uint2(a2, b2);
@@ -607,18 +633,25 @@ __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ N
     for (int64_t s = s0; s < s1; ++s) {
         const int cur = (int)((s - s0) & 1);
         const u32x4* st = lds + cur * STAGE16 + h * HREG + l32;
-        u32x4 op[6][3];
+        constexpr int NP3 = NEW1 ? 1 : 3, NQ = NEW1 ? 1 : 6;
+        u32x4 op[6][NP3];
 #pragma unroll
-        for (int p = 0; p < 3; ++p)
+        for (int p = 0; p < NP3; ++p)
 #pragma unroll
             for (int o = 0; o < 6; ++o) op[o][p] = st[p * PART16 + M::rows[o] * 32];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int k = 0; k < 6; ++k) {  // in the order the parts were read
+        for (int k = 0; k < NQ; ++k) {  // in the order the parts were read
             constexpr int PA[6] = {0, 0, 1, 1, 0, 2}, PB[6] = {0, 1, 0, 1, 2, 0};
 #pragma unroll
             for (int q = 0; q < 9; ++q) acc[q] = mfma_bf16(op[M::pa[q]][PA[k]], op[M::pb[q]][PB[k]], acc[q]);
-            if (k < 4) {
+            if (NEW1) {
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    store1(it, cur ^ 1);
+                    fetch1(it, s + 2);
+                }
+            } else if (k < 4) {
                 store1(k, cur ^ 1);
                 fetch1(k, s + 2);
             }
@@ -643,6 +676,7 @@ __device__ __forceinline__ void gram_new8_split_wave(const f32x4* __restrict__ N
     }
 }
 
+template <bool NEW1>
 __global__ __launch_bounds__(256, 2) void gram_new8_split_kernel(const float* __restrict__ nw, int nfill,
                                                                  float* __restrict__ partial, int64_t slabs_total,
                                                                  int64_t slabs_per_group) {
@@ -654,10 +688,10 @@ __global__ __launch_bounds__(256, 2) void gram_new8_split_kernel(const float* __
     if (s0 > s1) s0 = s1;
     const f32x4* Nv = reinterpret_cast<const f32x4*>(nw);
     switch (threadIdx.x >> 6) {  // wave-uniform
-        case 0: gram_new8_split_wave<0>(Nv, nfill, partial, group, s0, s1, ldsn); break;
-        case 1: gram_new8_split_wave<1>(Nv, nfill, partial, group, s0, s1, ldsn); break;
-        case 2: gram_new8_split_wave<2>(Nv, nfill, partial, group, s0, s1, ldsn); break;
-        default: gram_new8_split_wave<3>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+        case 0: gram_new8_split_wave<0, NEW1>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+        case 1: gram_new8_split_wave<1, NEW1>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+        case 2: gram_new8_split_wave<2, NEW1>(Nv, nfill, partial, group, s0, s1, ldsn); break;
+        default: gram_new8_split_wave<3, NEW1>(Nv, nfill, partial, group, s0, s1, ldsn); break;
     }
 }
 
@@ -766,15 +800,20 @@ GramPlan gram_plan_split(const GramPlan& base, const Dims& d, int groups) {
 }
 
 hipError_t launch_gram(const float* top, const float* nw, int nfill, float* partial, const GramPlan& p, const Dims& d,
-                       hipStream_t st) {
+                       hipStream_t st, bool new_one) {
     if (p.tiles <= 0) return hipSuccess;
     dim3 grid((unsigned)(p.groups * p.wg_per_group));
     size_t lds = (size_t)2 * d.NP * 64;
     if (p.mode == 1 && d.NP == 512 && p.split) {
         constexpr int LDS_SPLIT = 2 * 3 * 2 * (512 + 8) * 16;  // two stages of [part][k-half][row + pad] pieces
-        if (hipError_t ea = ensure_dynamic_lds((const void*)gram_cross8_split_kernel, LDS_SPLIT); ea != hipSuccess) return ea;
-        hipLaunchKernelGGL(gram_cross8_split_kernel, grid, dim3(512), LDS_SPLIT, st, top, nw, nfill, partial, d.S,
-                           p.slabs_per_group);
+        const void* kern = new_one ? (const void*)gram_cross8_split_kernel<true> : (const void*)gram_cross8_split_kernel<false>;
+        if (hipError_t ea = ensure_dynamic_lds(kern, LDS_SPLIT); ea != hipSuccess) return ea;
+        if (new_one)
+            hipLaunchKernelGGL(gram_cross8_split_kernel<true>, grid, dim3(512), LDS_SPLIT, st, top, nw, nfill, partial, d.S,
+                               p.slabs_per_group);
+        else
+            hipLaunchKernelGGL(gram_cross8_split_kernel<false>, grid, dim3(512), LDS_SPLIT, st, top, nw, nfill, partial,
+                               d.S, p.slabs_per_group);
         return hipGetLastError();
     }
     if (p.mode == 1 && d.NP == 512) {
@@ -787,8 +826,12 @@ hipError_t launch_gram(const float* top, const float* nw, int nfill, float* part
         // purpose) never shares a CU with one of these work-groups when the launch runs beside it
         constexpr int LDS_SPLIT = 65536;
         static_assert(2 * 3 * 2 * (256 + 8) * 16 <= LDS_SPLIT, "two stages must fit");
-        hipLaunchKernelGGL(gram_new8_split_kernel, grid, dim3(256), LDS_SPLIT, st, nw, nfill, partial, d.S,
-                           p.slabs_per_group);
+        if (new_one)
+            hipLaunchKernelGGL(gram_new8_split_kernel<true>, grid, dim3(256), LDS_SPLIT, st, nw, nfill, partial, d.S,
+                               p.slabs_per_group);
+        else
+            hipLaunchKernelGGL(gram_new8_split_kernel<false>, grid, dim3(256), LDS_SPLIT, st, nw, nfill, partial, d.S,
+                               p.slabs_per_group);
         return hipGetLastError();
     }
     if (p.mode == 2 && d.NP == 512 && p.wg_per_group == 1) {

@@ -13,6 +13,8 @@
 // streams through LDS in chunks of 16 buffer rows shared by the 4 waves of the work-group; it is stored in the
 // order the matrix cores consume it (see coeff_offset), so a lane fetches the 8 coefficients of a chunk with two
 // 16-byte LDS reads.
+#include <type_traits>
+
 #include "sage_internal.h"
 
 namespace sage {
@@ -193,7 +195,9 @@ __global__ __launch_bounds__(256) void coeff_split_kernel(const float* __restric
     dst[4 * MP] = lo;
 }
 
-template <int MT>
+// NPT > 0: the buffer has NPT rows and the new rows in use hold bf16 values; their stages take the hi part alone and
+// three products (the other three would add exact zeros). NPT = 0: any buffer, all parts.
+template <int MT, int NPT>
 __global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* top, const float* __restrict__ nw, int nfill,
                                                                const u32x4* __restrict__ Mc3, float* out, int NP,
                                                                int out_NP, int64_t Dp) {
@@ -240,7 +244,8 @@ __global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* top,
         for (int i = 0; i < 16; ++i) acc[m][i] = 0.f;
 
     // One stage: 16 buffer rows. b: its column operand (requested two stages ago); bfar receives that of stage + 2.
-    auto stage = [&](const float (&b)[8], float (&bfar)[8], int stg, int cur) __attribute__((always_inline)) {
+    auto stage = [&](auto one_c, const float (&b)[8], float (&bfar)[8], int stg, int cur) __attribute__((always_inline)) {
+        constexpr bool one = decltype(one_c)::value;  // a stage of new rows with one part
         const u32x4* A = Ms + cur * STAGE16 + h * MP + c;  // + part * 2 * MP + tile * 32
         u32x4 a[2][2][3];  // [buffer][tile of the pair][part]
 #pragma unroll
@@ -254,11 +259,17 @@ __global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* top,
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float x = 4 * e < limit ? b[2 * e] : 0.f, y = 4 * e + 2 < limit ? b[2 * e + 1] : 0.f;
-            unsigned p0, p1, p2;
-            split3_bf16(x, y, p0, p1, p2);
-            bh[e] = p0;
-            bm[e] = p1;
-            bl[e] = p2;
+            if constexpr (one) {
+                bh[e] = hi_bf16(x, y);
+                bm[e] = 0u;
+                bl[e] = 0u;
+            } else {
+                unsigned p0, p1, p2;
+                split3_bf16(x, y, p0, p1, p2);
+                bh[e] = p0;
+                bm[e] = p1;
+                bl[e] = p2;
+            }
         }
         fetch_m(stg + 2, cur == 0 ? 2 : cur - 1);
         fetch_b(stg + 2, bfar);
@@ -274,13 +285,20 @@ __global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* top,
             }
             __builtin_amdgcn_sched_barrier(0);  // the reads go out before this pair's matrix-core instructions, not after
             const int bsel = (i >> 1) & 1;
+            if constexpr (one) {
 #pragma unroll
-            for (int q = 0; q < 6; ++q) {  // smallest terms first
-                constexpr int PA[6] = {2, 0, 1, 1, 0, 0};  // part of the coefficient
-                constexpr int PB[6] = {0, 2, 1, 0, 1, 0};  // part of the column operand
-                const u32x4 bb = PB[q] == 0 ? bh : (PB[q] == 1 ? bm : bl);
+                for (int q = 2; q >= 0; --q)  // smallest terms first
 #pragma unroll
-                for (int t = 0; t < 2; ++t) acc[i + t] = mfma_bf16(a[bsel][t][PA[q]], bb, acc[i + t]);
+                    for (int t = 0; t < 2; ++t) acc[i + t] = mfma_bf16(a[bsel][t][q], bh, acc[i + t]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 6; ++q) {  // smallest terms first
+                    constexpr int PA[6] = {2, 0, 1, 1, 0, 0};  // part of the coefficient
+                    constexpr int PB[6] = {0, 2, 1, 0, 1, 0};  // part of the column operand
+                    const u32x4 bb = PB[q] == 0 ? bh : (PB[q] == 1 ? bm : bl);
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) acc[i + t] = mfma_bf16(a[bsel][t][PA[q]], bb, acc[i + t]);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -296,21 +314,53 @@ __global__ __launch_bounds__(256, 2) void rebuild_split_kernel(const float* top,
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // Stage s uses LDS buffer and row registers s mod 3 (+ a fixed offset, below).
     float b0[8], b1[8], b2[8];
-    fetch_m(0, 0);
-    fetch_m(1, 1);
-    fetch_b(0, b0);
-    fetch_b(1, b1);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    int s = 0;
-    for (; s + 2 < nstage; s += 3) {
-        stage(b0, b2, s, 0);
-        stage(b1, b0, s + 1, 1);
-        stage(b2, b1, s + 2, 2);
+    constexpr std::false_type all_parts{};
+    constexpr std::true_type one_part{};
+    auto triples = [&](auto one_c, int s, int end) __attribute__((always_inline)) {  // from ring position 0
+        for (; s + 2 < end; s += 3) {
+            stage(one_c, b0, b2, s, 0);
+            stage(one_c, b1, b0, s + 1, 1);
+            stage(one_c, b2, b1, s + 2, 2);
+        }
+        if (s < end) stage(one_c, b0, b2, s, 0);
+        if (s + 1 < end) stage(one_c, b1, b0, s + 1, 1);
+    };
+    if constexpr (NPT == 0) {
+        fetch_m(0, 0);
+        fetch_m(1, 1);
+        fetch_b(0, b0);
+        fetch_b(1, b1);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        triples(all_parts, 0, nstage);
+    } else {
+        // The top half's NPT / 32 stages start at the ring position that lets the new half's start at position 0.
+        constexpr int S1 = NPT / 32, R = S1 % 3;
+        static_assert(R == 1 || R == 2, "buffers of 256 or 512 rows");
+        if constexpr (R == 1) {
+            fetch_m(0, 2);
+            fetch_m(1, 0);
+            fetch_b(0, b2);
+            fetch_b(1, b0);
+        } else {
+            fetch_m(0, 1);
+            fetch_m(1, 2);
+            fetch_b(0, b1);
+            fetch_b(1, b2);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if constexpr (R == 1) {
+            stage(all_parts, b2, b1, 0, 2);
+        } else {
+            stage(all_parts, b1, b0, 0, 1);
+            stage(all_parts, b2, b1, 1, 2);
+        }
+        triples(all_parts, R, S1);
+        triples(one_part, S1, 2 * S1);
     }
-    if (s < nstage) stage(b0, b2, s, 0);
-    if (s + 1 < nstage) stage(b1, b0, s + 1, 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing on its way to LDS when the work-group ends
 
     if (!live) return;
@@ -328,26 +378,30 @@ bool rebuild_split_ok(int MP) { return MP == 128 || MP == 256; }
 
 size_t rebuild_split_bytes(const Dims& d, int MP) { return (size_t)(d.NP / 16) * 3 * 2 * MP * 16; }
 
-template <int MT>
+template <int MT, int NPT>
 static hipError_t launch_rebuild_split_t(const float* top, const float* nw, int nfill, const float* Mc, void* Mc3,
                                          float* out, int out_NP, const Dims& d, hipStream_t st) {
     constexpr int MP = MT * 32;
     constexpr size_t LDS = (size_t)3 * 3 * 2 * MP * 16;
-    if (hipError_t ea = ensure_dynamic_lds((const void*)rebuild_split_kernel<MT>, (int)LDS); ea != hipSuccess) return ea;
+    if (hipError_t ea = ensure_dynamic_lds((const void*)rebuild_split_kernel<MT, NPT>, (int)LDS); ea != hipSuccess)
+        return ea;
     const int n = (d.NP / 16) * 2 * MP;
     hipLaunchKernelGGL(coeff_split_kernel<MT>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, Mc, d.NP, (u32x4*)Mc3);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((d.Dp + 127) / 128));
-    hipLaunchKernelGGL(rebuild_split_kernel<MT>, grid, dim3(256), LDS, st, top, nw, nfill, (const u32x4*)Mc3, out, d.NP,
-                       out_NP, d.Dp);
+    hipLaunchKernelGGL((rebuild_split_kernel<MT, NPT>), grid, dim3(256), LDS, st, top, nw, nfill, (const u32x4*)Mc3, out,
+                       d.NP, out_NP, d.Dp);
     return hipGetLastError();
 }
 
 hipError_t launch_rebuild_split(const float* top, const float* nw, int nfill, const float* Mc, void* Mc3, float* out,
-                                int out_NP, int MP, const Dims& d, hipStream_t st) {
-    if (MP == 256) return launch_rebuild_split_t<8>(top, nw, nfill, Mc, Mc3, out, out_NP, d, st);
-    if (MP == 128) return launch_rebuild_split_t<4>(top, nw, nfill, Mc, Mc3, out, out_NP, d, st);
+                                int out_NP, int MP, const Dims& d, hipStream_t st, bool new_one) {
+    if (MP == 256 && new_one && d.NP == 512) return launch_rebuild_split_t<8, 512>(top, nw, nfill, Mc, Mc3, out, out_NP, d, st);
+    if (MP == 256) return launch_rebuild_split_t<8, 0>(top, nw, nfill, Mc, Mc3, out, out_NP, d, st);
+    if (MP == 128 && new_one && d.NP == 512) return launch_rebuild_split_t<4, 512>(top, nw, nfill, Mc, Mc3, out, out_NP, d, st);
+    if (MP == 128 && new_one && d.NP == 256) return launch_rebuild_split_t<4, 256>(top, nw, nfill, Mc, Mc3, out, out_NP, d, st);
+    if (MP == 128) return launch_rebuild_split_t<4, 0>(top, nw, nfill, Mc, Mc3, out, out_NP, d, st);
     return hipErrorInvalidValue;
 }
 

@@ -50,6 +50,11 @@ struct sage_ctx {
     float* Mt = nullptr;
     void* Mt3 = nullptr;   // the rebuild's coefficients split into bf16 parts (SAGE_MM_SPLIT)
     int mm_mode = SAGE_MM_SPLIT;
+    // Rows of a bf16 stream are kept as fp32 but have one bf16 part, not three: the split-arithmetic kernels then skip
+    // the products with the new rows' mid and lo parts (exact zeros; same bits). nw_bf16[i]: every row in use in nw[i]
+    // came from a bf16 batch (row-major or factored; not sage_fd_merge's fp32 rows). one_part: the shortcut is allowed (off under SAGE_MM_SPLIT_ALL_PARTS).
+    bool nw_bf16[2] = {false, false};
+    bool one_part = true;
     double* acc = nullptr;  // [0] sum_delta [1] frob2 [2] last_delta [3] sweeps [4] unconverged solves [5] last off-diagonal
 
     bool poisoned = false;   // a HIP call failed while work of a call was partly enqueued: the state is not trustworthy
@@ -195,6 +200,13 @@ hipError_t insert_rows(const RowSrc& s, int64_t rows, int row0, float* half, int
     return launch_insert(s.G, s.dtype, rows, row0, half, half_rows, d, st);
 }
 
+// Rows of `s` are about to be stored in nw[i] from row row0 on.
+void note_new_rows(sage_ctx* c, int i, int row0, const RowSrc& s) {
+    const bool b = s.dtype == SAGE_BF16;  // factored rows of a bf16 context are rounded to bf16 when they are stored
+    c->nw_bf16[i] = row0 == 0 ? b : (c->nw_bf16[i] && b);
+}
+bool new_one(const sage_ctx* c, int i) { return c->one_part && c->nw_bf16[i]; }
+
 constexpr int SWEEP_RING = 4;
 
 // Pick up the sweep counts that have arrived and set the number of sweeps to launch next.
@@ -257,9 +269,10 @@ int decompose(sage_ctx* c, double tol, bool full) {
         !c->new_block_ready && !c->pre_stored) {
         // the two blocks that are not known, with the split-arithmetic kernels (the side stream is idle here: its
         // partial buffer of the current half is free)
-        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp_cross_split, c->d, c->st));
+        const bool one = new_one(c, c->cur);
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp_cross_split, c->d, c->st, one));
         RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial_new[c->cur], c->gp_new2_split, c->d,
-                                c->st));
+                                c->st, one));
         RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, c->gp_cross_split, c->gram_partial_new[c->cur], &c->gp_new2_split,
                                          c->ew.C, true, c->ew.known, c->d, c->st));
     } else {
@@ -281,9 +294,10 @@ int side_ahead(sage_ctx* c, const RowSrc* next) {
     const int LP = c->d.LP, ell = c->d.ell, o = c->cur ^ 1;
     HIPCHK(hipEventRecord(c->ev_mark, c->st));
     HIPCHK(hipStreamWaitEvent(c->st2, c->ev_mark, 0));
+    note_new_rows(c, o, 0, *next);
     HIPCHK(insert_rows(*next, ell, 0, c->nw[o], LP, c->d, c->st2));
     c->gp_side_used[o] = c->mm_mode == SAGE_MM_SPLIT && c->gp_new_split.tiles > 0 ? &c->gp_new_split : &c->gp_new;
-    HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], *c->gp_side_used[o], c->d, c->st2));
+    HIPCHK(launch_gram(c->top, c->nw[o], ell, c->gram_partial_new[o], *c->gp_side_used[o], c->d, c->st2, new_one(c, o)));
     HIPCHK(hipEventRecord(c->ev_side[o], c->st2));
     return SAGE_OK;
 }
@@ -300,10 +314,11 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
             HIPCHK(hipStreamWaitEvent(c->st, c->ev_side[c->cur], 0));
         } else {
             gn = split && c->gp_new2_split.tiles > 0 ? &c->gp_new2_split : &c->gp_new2;
-            RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial_new[c->cur], *gn, c->d, c->st));
+            RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial_new[c->cur], *gn, c->d, c->st,
+                                    new_one(c, c->cur)));
         }
         const GramPlan& gc = split && c->gp_cross_split.tiles > 0 ? c->gp_cross_split : c->gp_cross;
-        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, gc, c->d, c->st));
+        RUN(K_GRAM, launch_gram(c->top, c->nw[c->cur], ell, c->gram_partial, gc, c->d, c->st, new_one(c, c->cur)));
         RUN(K_REDUCE, launch_gram_reduce(c->gram_partial, gc, c->gram_partial_new[c->cur], gn, c->ew.C, true,
                                          c->ew.known, c->d, c->st));
     } else {
@@ -325,7 +340,8 @@ int shrink(sage_ctx* c, const RowSrc* next, int64_t next_rows) {
     RUN(K_COEFF, launch_shrink_coeffs(c->ew, c->d.NP, LP, ell, c->cnt_top, c->fill_top, LP + c->cnt_new, LP + c->fill_new,
                                       c->Mt, c->acc, JACOBI_TOL_SHRINK, c->st));
     if (c->mm_mode == SAGE_MM_SPLIT && c->Mt3)
-        RUN(K_REBUILD, launch_rebuild_split(c->top, c->nw[c->cur], ell, c->Mt, c->Mt3, c->top, LP, LP, c->d, c->st));
+        RUN(K_REBUILD, launch_rebuild_split(c->top, c->nw[c->cur], ell, c->Mt, c->Mt3, c->top, LP, LP, c->d, c->st,
+                                            new_one(c, c->cur)));
     else
         RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], ell, c->Mt, c->top, LP, LP, c->d, c->st));
     post_sweeps(c);
@@ -606,6 +622,7 @@ static int update_rows(sage_ctx* c, RowSrc g, int64_t rows) {
             c->fill_new = ell;
         } else {
             take = (int)((int64_t)(ell - c->fill_new) < rows ? (ell - c->fill_new) : rows);
+            note_new_rows(c, c->cur, c->fill_new, g);
             RUN(K_INSERT, insert_rows(g, take, c->fill_new, c->nw[c->cur], LP, c->d, c->st));
             c->fill_new += take;
         }
@@ -706,7 +723,8 @@ static int basis_impl(sage_ctx* c, int k, bool weighted) {
     c->cnt_top = c->fill_top;
     c->cnt_new = c->fill_new;
     if (c->mm_mode == SAGE_MM_SPLIT && c->Mt3 && rebuild_split_ok(KP) && KP <= c->d.LP)
-        RUN(K_REBUILD, launch_rebuild_split(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Mt3, c->Vblk, KP, KP, c->d, c->st));
+        RUN(K_REBUILD, launch_rebuild_split(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Mt3, c->Vblk, KP, KP, c->d, c->st,
+                                            c->fill_new > 0 && new_one(c, c->cur)));
     else
         RUN(K_REBUILD, launch_rebuild(c->top, c->nw[c->cur], c->fill_new, c->Mt, c->Vblk, KP, KP, c->d, c->st));
     c->k = k;
@@ -728,8 +746,9 @@ int sage_set_projection_mode(sage_ctx* c, int mode) {
 
 int sage_set_update_arithmetic(sage_ctx* c, int mode) {
     ALIVE(c);
-    if ((mode != SAGE_MM_F32 && mode != SAGE_MM_SPLIT)) return SAGE_ERR_ARG;
-    c->mm_mode = mode;
+    if (mode != SAGE_MM_F32 && mode != SAGE_MM_SPLIT && mode != SAGE_MM_SPLIT_ALL_PARTS) return SAGE_ERR_ARG;
+    c->mm_mode = mode == SAGE_MM_F32 ? SAGE_MM_F32 : SAGE_MM_SPLIT;
+    c->one_part = mode != SAGE_MM_SPLIT_ALL_PARTS;
     return SAGE_OK;
 }
 
@@ -1170,8 +1189,9 @@ int sage_probe_gram_split(sage_ctx* c, double* C_out, int* n_pad) {
     int rcf = flush_pending(c);
     if (rcf != SAGE_OK) return rcf;
     if (c->new_block_ready || c->pre_stored) return SAGE_ERR_STATE;  // (never after flush_pending)
-    HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp_cross_split, c->d, c->st));
-    HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial_new[c->cur], c->gp_new2_split, c->d, c->st));
+    const bool one = c->fill_new > 0 && new_one(c, c->cur);
+    HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial, c->gp_cross_split, c->d, c->st, one));
+    HIPCHK(launch_gram(c->top, c->nw[c->cur], c->fill_new, c->gram_partial_new[c->cur], c->gp_new2_split, c->d, c->st, one));
     HIPCHK(launch_gram_reduce(c->gram_partial, c->gp_cross_split, c->gram_partial_new[c->cur], &c->gp_new2_split, c->ew.C,
                               false, c->ew.known, c->d, c->st));
     HIPCHK(launch_probe_permute(c->ew.C, C_out, NP, LP, ell, true, c->st));

@@ -65,6 +65,11 @@ __device__ __forceinline__ void split3_bf16(float x, float y, unsigned& hi, unsi
     lo = pack_bf16(rx - __uint_as_float(mid << 16), ry - __uint_as_float(mid & 0xffff0000u));
 }
 
+// The upper halves of an fp32 pair as a bf16 pair: exact when both are bf16 values (rows of a bf16 stream kept as fp32).
+__device__ __forceinline__ unsigned hi_bf16(float x, float y) {
+    return __builtin_amdgcn_perm(__float_as_uint(y), __float_as_uint(x), 0x07060302u);
+}
+
 // ---- kernel launchers (each enqueues on `st` and returns hipGetLastError()) ---------------------------------
 // launch_util.hip: raise a kernel's dynamic LDS limit, once per (device, kernel); thread-safe
 hipError_t ensure_dynamic_lds(const void* kernel, int bytes);
@@ -103,8 +108,10 @@ struct GramPlan {
 // tiles; groups > 0 overrides the group count (tiles = 0 in the result: not available for this sketch size).
 GramPlan gram_plan_split(const GramPlan& base, const Dims& d, int groups);
 GramPlan gram_plan(const Dims& d, int num_cu, int mode, bool skip_top, int wg_per_cu);
+// new_one: every new row in use holds bf16 values (one part instead of three in the split-arithmetic kernels; the
+// result has the same bits)
 hipError_t launch_gram(const float* top, const float* nw, int nfill, float* partial, const GramPlan& p, const Dims& d,
-                       hipStream_t st);
+                       hipStream_t st, bool new_one = false);
 // C = sum of the partial tiles of launch a and (if given) launch b; known_top: the top x top block is `known`
 // (LP x LP, the Gram matrix of the rows the last shrink wrote, see EigWork::known)
 hipError_t launch_gram_reduce(const float* partial_a, const GramPlan& a, const float* partial_b, const GramPlan* b,
@@ -162,8 +169,9 @@ hipError_t launch_rebuild(const float* top, const float* nw, int nfill, const fl
 // split coefficients). Only for MP = 128 or 256 (rebuild_split_ok).
 bool rebuild_split_ok(int MP);
 size_t rebuild_split_bytes(const Dims& d, int MP);
+// new_one: as for launch_gram (three products instead of six for the new half).
 hipError_t launch_rebuild_split(const float* top, const float* nw, int nfill, const float* Mc, void* Mc3, float* out,
-                                int out_NP, int MP, const Dims& d, hipStream_t st);
+                                int out_NP, int MP, const Dims& d, hipStream_t st, bool new_one = false);
 
 // score.hip
 struct ScorePlan {

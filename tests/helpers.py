@@ -37,11 +37,13 @@ def to_dev(G, torch):
     return torch.from_numpy(G).cuda()
 
 
-def run_gpu(w, G, k=None, keep=None, score=True):
+def run_gpu(w, G, k=None, keep=None, score=True, arithmetic=None):
     import torch
     from paper_2510_02470_amd.binding import Sage
 
     s = Sage(w.ell, w.D, dtype=w.dtype)
+    if arithmetic is not None:
+        s.set_update_arithmetic(arithmetic)
     Gd = to_dev(G, torch)
     for lo in range(0, G.shape[0], w.batch):
         s.fd_update(Gd[lo:lo + w.batch])

@@ -5,7 +5,8 @@
   * sketches at ell = 64 and ell = 128 against the oracle's one-sided Jacobi on the rows (mode 0), which shares neither
     the Gram matrix nor the two-sided rotations with the GPU path;
   * a stream whose spectrum changes abruptly between cycles (the eigensolve must still converge);
-  * bit-equal results of two runs with the same cut of the stream at ell = 256, side stream active.
+  * bit-equal results of two runs with the same cut of the stream at ell = 256, side stream active;
+  * bit-equal results with and without the one-part shortcut the split kernels take for rows of a bf16 stream.
 
 Bars as in tests/test_gpu_parity.py.
 """
@@ -171,3 +172,62 @@ def test_same_cut_gives_the_same_bits_at_full_sketch_size():
     assert torch.equal(s1.basis(), s2.basis())
     assert torch.equal(s1.scores(), s2.scores()) and torch.equal(i1, i2)
     assert s1.stats().sum_delta == s2.stats().sum_delta
+
+
+@pytest.mark.parametrize("ell,D,batch", [(256, 3000, 1024), (256, 2064, 700), (128, 1500, 2048)])
+def test_one_part_shortcut_for_bf16_rows_changes_no_bit(ell, D, batch):
+    """Rows of a bf16 stream have one bf16 part; the split-arithmetic kernels leave out the products with the other
+    two (exact zeros). With the shortcut (mode 1, the default) and without it (mode 2): the same bits in the sketch, the
+    basis, the scores and the selection. Batches that do and do not cut the stream at multiples of ell."""
+    w = inputs.WORKLOADS[5].scaled(N=ell * 7 + 77, D=D, ell=ell, k=ell // 2, batch=batch, r=200, keep=0.1)
+    G = inputs.generate_numpy(w)
+    s1, i1 = run_gpu(w, G, arithmetic=1)
+    s2, i2 = run_gpu(w, G, arithmetic=2)
+    assert s1.stats().n_shrinks == s2.stats().n_shrinks == 6
+    assert torch.equal(s1.sketch(), s2.sketch())
+    assert torch.equal(s1.basis(), s2.basis())
+    assert torch.equal(s1.scores(), s2.scores()) and torch.equal(i1, i2)
+    assert s1.stats().sum_delta == s2.stats().sum_delta
+
+
+def test_one_part_shortcut_is_dropped_for_rows_that_are_not_bf16_values():
+    """A bf16 context that also receives fp32 rows (sage_fd_merge) and factored rows (stored rounded to bf16) between
+    its bf16 batches: a half buffer that holds any fp32 row takes all three parts. Same bits as without the shortcut,
+    and the covariance of the whole stream against the oracle."""
+    from paper_2510_02470_amd.binding import Sage
+
+    ell, C, dh = 256, 12, 171
+    D = C * (dh + 1)
+    rng = np.random.default_rng(5)
+    w = inputs.WORKLOADS[5].scaled(N=ell * 4, D=D, ell=ell, k=64, batch=512, r=100)
+    G = inputs.generate_numpy(w)                                    # bf16 bits
+    Gd = to_dev(G, torch)
+    F = torch.from_numpy((rng.standard_normal((300, D)) * 0.05).astype(np.float32)).cuda()
+    E = torch.from_numpy(rng.standard_normal((200, C)).astype(np.float32)).cuda().bfloat16()
+    H = torch.from_numpy((rng.standard_normal((200, dh)) * 0.05).astype(np.float32)).cuda().bfloat16()
+    out = []
+    for mode in (1, 2):
+        s = Sage(ell, D, dtype="bf16")
+        s.set_update_arithmetic(mode)
+        s.fd_update(Gd[:700])          # fills the top half, 188 rows short of the first shrink
+        s.fd_merge(F)                  # fp32 rows complete that buffer and start the next new half
+        s.fd_update(Gd[700:])          # bf16 rows on top of them in the same half, then whole halves of bf16 rows
+        s.fd_update_outer(E, H)
+        s.fd_update(Gd[:400])
+        s.fd_basis(64)
+        out.append((s.sketch().clone(), s.basis().clone(), s.stats()))
+    assert out[0][2].n_shrinks == out[1][2].n_shrinks and out[0][2].n_shrinks >= 5
+    assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
+    assert out[0][2].sum_delta == out[1][2].sum_delta
+    # the oracle on the same rows, in the same order
+    Eh, Hh = E.float().cpu().numpy().astype(np.float64), H.float().cpu().numpy().astype(np.float64)
+    outer = np.concatenate([(Eh[:, :, None] * Hh[:, None, :]).reshape(200, C * dh), Eh], axis=1)
+    outer = torch.from_numpy(outer).float().bfloat16().float().numpy().astype(np.float64)   # rounded as a stored row
+    A = inputs.bf16_bits_to_f32(G).astype(np.float64)
+    rows = np.concatenate([A[:700], F.cpu().numpy().astype(np.float64), A[700:], outer, A[:400]])
+    o = Oracle(ell, D, 1)
+    o.update(rows.astype(np.float32))      # (every one of them is an fp32 value)
+    fro = (rows ** 2).sum()
+    st = out[0][2]
+    assert st.n_shrinks == o.n_shrinks and st.fill == o.fill
+    assert cov_diff_spec_norm(out[0][0].cpu().numpy(), o.B) / fro <= COV_TOL
