@@ -626,8 +626,10 @@ def test_argument_and_state_errors():
     s.fd_update(g)  # invalidates the basis
     assert L.sage_score(s.h, C.c_void_p(g.data_ptr()), 1) == B.SAGE_ERR_STATE
     assert B.lib().sage_strerror(B.SAGE_ERR_STATE) == b"call not allowed in this state"
-    assert L.sage_set_update_arithmetic(s.h, 2) == B.SAGE_ERR_ARG and L.sage_set_update_arithmetic(None, 0) == B.SAGE_ERR_ARG
-    assert L.sage_set_update_arithmetic(s.h, 0) == 0 and L.sage_set_update_arithmetic(s.h, 1) == 0
+    assert L.sage_set_update_arithmetic(s.h, 3) == B.SAGE_ERR_ARG and L.sage_set_update_arithmetic(None, 0) == B.SAGE_ERR_ARG
+    assert L.sage_set_update_arithmetic(s.h, -1) == B.SAGE_ERR_ARG
+    assert L.sage_set_update_arithmetic(s.h, 0) == 0 and L.sage_set_update_arithmetic(s.h, 2) == 0
+    assert L.sage_set_update_arithmetic(s.h, 1) == 0
     # factored rows: classes * (features + 1) must be D = 40; null factors; negative row count
     assert L.sage_fd_update_outer(s.h, C.c_void_p(g.data_ptr()), C.c_void_p(g.data_ptr()), 2, 4, 8) == B.SAGE_ERR_ARG
     assert L.sage_fd_update_outer(s.h, None, C.c_void_p(g.data_ptr()), 2, 4, 9) == B.SAGE_ERR_ARG
