@@ -268,16 +268,32 @@ def cb_alpha(zhat, labels, n_classes):
     return alpha
 
 
-def cb_budgets(counts, keep_rate):
-    """The class budgets k_c (Algorithm 1, class-balanced branch: "sum_c k_c = k"). The subset size is that of the plain
-    selection, m = floor(keep*N + 0.5); class c gets floor(keep*N_c), and the rows still missing from m go one each to
-    the classes with the largest fractional part keep*N_c - floor(keep*N_c) (equal parts: the lower class first) that
-    are not yet full (largest-remainder rule). Returns an int64 array with sum m."""
+def cb_budgets(counts, keep_rate, rule="proportional"):
+    """The class budgets k_c (Algorithm 1, class-balanced branch: "sum_c k_c = k"; the paper leaves the k_c open). The
+    subset size is that of the plain selection, m = floor(keep*N + 0.5). Returns an int64 array with sum m.
+    rule "proportional": class c gets floor(keep*N_c), and the rows still missing from m go one each to the classes
+    with the largest fractional part keep*N_c - floor(keep*N_c) (equal parts: the lower class first) that are not yet
+    full (largest-remainder rule).
+    rule "equal": the m rows are dealt one at a time to the classes in turn, lowest class first, a class that has
+    none left to give being passed over: every class ends with the same budget, up to one row and up to its size."""
     counts = np.asarray(counts, dtype=np.int64)
+    m = keep_count(keep_rate, int(counts.sum()))
+    if rule == "equal":
+        kc = np.zeros(counts.size, dtype=np.int64)
+        left = m
+        while left > 0:
+            for c in range(counts.size):
+                if left == 0:
+                    break
+                if kc[c] < counts[c]:
+                    kc[c] += 1
+                    left -= 1
+        return kc
+    if rule != "proportional":
+        raise ValueError("rule must be 'proportional' or 'equal'")
     q = float(keep_rate) * counts.astype(np.float64)
     kc = np.minimum(np.floor(q).astype(np.int64), counts)
     frac = q - np.floor(q)
-    m = keep_count(keep_rate, int(counts.sum()))
     rem = m - int(kc.sum())
     open_classes = [c for c in range(counts.size) if kc[c] < counts[c]]
     for c in sorted(open_classes, key=lambda c: (-frac[c], c))[:max(rem, 0)]:
@@ -285,13 +301,13 @@ def cb_budgets(counts, keep_rate):
     return kc
 
 
-def cb_select_from_alpha(alpha, labels, n_classes, keep_rate):
+def cb_select_from_alpha(alpha, labels, n_classes, keep_rate, rule="proportional"):
     """Per class the k_c (cb_budgets) rows greatest under (float32 alpha descending, index ascending); all kept indices
     ascending."""
     a32 = np.asarray(alpha).astype(np.float32)
     a32 = np.where(a32 == 0, np.float32(0), a32)     # -0 -> +0
     labels = np.asarray(labels)
-    budgets = cb_budgets([int((labels == c).sum()) for c in range(int(n_classes))], keep_rate)
+    budgets = cb_budgets([int((labels == c).sum()) for c in range(int(n_classes))], keep_rate, rule)
     kept = []
     for c in range(int(n_classes)):
         rows = np.nonzero(labels == c)[0]
@@ -303,9 +319,9 @@ def cb_select_from_alpha(alpha, labels, n_classes, keep_rate):
     return np.array(sorted(kept), dtype=np.int64)
 
 
-def cb_scores_and_selection(zhat, labels, n_classes, keep_rate):
+def cb_scores_and_selection(zhat, labels, n_classes, keep_rate, rule="proportional"):
     alpha = cb_alpha(zhat, labels, n_classes)
-    return alpha, cb_select_from_alpha(alpha, labels, n_classes, keep_rate)
+    return alpha, cb_select_from_alpha(alpha, labels, n_classes, keep_rate, rule)
 
 
 def keep_count(keep_rate, N):

@@ -532,6 +532,50 @@ def test_cb_budgets_sum_to_the_subset_size():
     assert got[:480].sum() == 205                                       # the larger classes have the larger remainders
 
 
+def test_cb_equal_budgets_are_the_most_even_split():
+    """Rule "equal" of the class budgets. Against brute force on tiny inputs: among all integer vectors with
+    0 <= k_c <= N_c and sum m, the budgets are the one with the smallest sum of squares (the most even split), and
+    among those of that sum of squares the lexicographically greatest (spare rows go to the lower classes). Then the
+    closed form for classes that are all large enough, and the properties that hold for any input."""
+    import itertools
+
+    rng = np.random.default_rng(17)
+    for trial in range(60):
+        Cn = int(rng.integers(1, 5))
+        counts = rng.integers(0, 6, size=Cn)
+        N = int(counts.sum())
+        for keep in (0.0, 0.2, 0.5, 0.8, 1.0):
+            m = oracle.keep_count(keep, N)
+            got = oracle.cb_budgets(counts, keep, "equal")
+            feas = [v for v in itertools.product(*[range(int(n) + 1) for n in counts]) if sum(v) == m]
+            best = min(sum(x * x for x in v) for v in feas)
+            want = max(v for v in feas if sum(x * x for x in v) == best)
+            assert tuple(got.tolist()) == want, (counts, keep, got, want)
+    # every class large enough: floor(m / C) each, the m mod C spare rows to the first classes
+    counts = np.full(7, 1000)
+    got = oracle.cb_budgets(counts, 0.0147, "equal")             # m = 103
+    assert got.tolist() == [15, 15, 15, 15, 15, 14, 14]
+    for keep in (0.01, 0.1, 0.33, 0.9):
+        counts = rng.integers(0, 120, size=200)
+        got = oracle.cb_budgets(counts, keep, "equal")
+        assert got.sum() == oracle.keep_count(keep, int(counts.sum())) and (got <= counts).all() and (got >= 0).all()
+        open_c = got < counts                                     # classes that could have given more
+        if open_c.any():
+            lvl = got[open_c]
+            assert lvl.max() - lvl.min() <= 1
+            assert (got[~open_c] <= lvl.max()).all()              # a class is full only at or below the common level
+            hi = np.nonzero(open_c & (got == lvl.max()))[0]
+            lo = np.nonzero(open_c & (got == lvl.min()))[0]
+            if lvl.max() > lvl.min():
+                assert hi.max() < lo.min()                        # the spare rows went to the lower classes
+    # the two rules differ where class sizes do: proportional follows the sizes, equal does not
+    counts = np.array([1000, 100, 10])
+    assert oracle.cb_budgets(counts, 0.1, "proportional").tolist() == [100, 10, 1]
+    assert oracle.cb_budgets(counts, 0.1, "equal").tolist() == [51, 50, 10]
+    with pytest.raises(ValueError):
+        oracle.cb_budgets(counts, 0.1, "other")
+
+
 def test_sketches_merge_with_added_bounds():
     """Mergeability (a property of Frequent Directions, the sketch the Method section uses): feeding the rows of the
     sketch of A2 to the sketch of A1 as data gives B with 0 <= A^T A - B^T B and
