@@ -147,14 +147,20 @@ int sage_select(sage_ctx* ctx, double keep_rate, int64_t* out_idx, int64_t cap, 
  * (alpha descending, index ascending) are kept. The paper asks for sum_c k_c = k and leaves the k_c open; here the
  * subset size is the plain selection's m = floor(keep_rate * N + 0.5), class c gets floor(keep_rate * N_c), and the rows
  * still missing from m go one each to the classes with the largest fractional part of keep_rate * N_c (equal parts:
- * the lower class first) that are not yet full -- proportional budgets that sum to m exactly. All kept indices are
+ * the lower class first) that are not yet full -- proportional budgets that sum to m exactly (SAGE_CB_PROPORTIONAL,
+ * what sage_select_cb uses). sage_select_cb_ex takes the rule: SAGE_CB_EQUAL deals the m rows one at a time to the classes
+ * in turn, lowest class first, passing over a class that is full -- every class ends with the same budget up to one
+ * row and up to its size. All kept indices are
  * written in ascending order. out_idx: DEVICE, room for `cap` int64 (SAGE_ERR_CAPACITY if sum(k_c) > cap); out_m: HOST, receives
  * sum(k_c). 1 <= n_classes <= 65536. A label outside [0, n_classes) gives SAGE_ERR_ARG. Waits for the stream.
  * sage_scores / sage_scores_export then give these class-wise scores. Class sums are accumulated in 64-bit fixed
  * point (2^-40 resolution), so the result does not depend on the order in which the device adds.
  */
 int sage_score_labeled(sage_ctx* ctx, const void* G_batch, const int32_t* labels, int64_t rows);
+typedef enum { SAGE_CB_PROPORTIONAL = 0, SAGE_CB_EQUAL = 1 } sage_cb_rule;
 int sage_select_cb(sage_ctx* ctx, double keep_rate, int n_classes, int64_t* out_idx, int64_t cap, int64_t* out_m);
+int sage_select_cb_ex(sage_ctx* ctx, double keep_rate, int n_classes, int rule, int64_t* out_idx, int64_t cap,
+                      int64_t* out_m);
 
 /*
  * Scoring without the N x k store of zhat (Abstract: O(l D) memory, no explicit N x l store). With

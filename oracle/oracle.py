@@ -137,11 +137,11 @@ class Oracle:
             raise RuntimeError("select failed rc=%d" % rc)
         return out[: m.value].copy()
 
-    def select_cb(self, keep_rate, labels, n_classes):
+    def select_cb(self, keep_rate, labels, n_classes, rule="proportional"):
         """Class-balanced selection (Algorithm 1, "if class balance required"): per class c the unit centroid u_c of the
         stored zhat of its rows, alpha_i = <zhat_i, u_c(i)> clamped, and the k_c (cb_budgets: they sum to the plain
         selection's m) rows of the class greatest under (alpha as float32 descending, index ascending). Returns (alpha float64, indices ascending)."""
-        return cb_scores_and_selection(self.zhat, labels, n_classes, keep_rate)
+        return cb_scores_and_selection(self.zhat, labels, n_classes, keep_rate, rule)
 
     # ---- views (copies) ----
     def _arr(self, ptr, shape):

@@ -11,13 +11,14 @@ LIB_PATH = os.path.join(_HERE, "libsage_hip.so")
 
 SAGE_F32, SAGE_BF16 = 0, 1
 SAGE_OK, SAGE_ERR_ARG, SAGE_ERR_STATE, SAGE_ERR_ALLOC, SAGE_ERR_HIP, SAGE_ERR_CAPACITY = 0, -1, -2, -3, -4, -5
+CB_PROPORTIONAL, CB_EQUAL = 0, 1  # sage_cb_rule
 
 KERNEL_CLASSES = ("gram", "gram_reduce", "eigensolve", "coefficients", "rebuild", "insert", "project",
                   "score_finalize", "select")
 
 # every symbol include/sage.h declares
 EXPORTS = (
-    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_update_arithmetic", "sage_probe_gram_split", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb",
+    "sage_fd_create", "sage_fd_create_ex", "sage_fd_update", "sage_fd_merge", "sage_set_update_arithmetic", "sage_probe_gram_split", "sage_fd_update_outer", "sage_score_outer", "sage_rescore_outer", "sage_set_score_store", "sage_rescore", "sage_fd_basis", "sage_fd_basis_weighted", "sage_score", "sage_select", "sage_score_labeled", "sage_select_cb", "sage_select_cb_ex",
     "sage_destroy", "sage_sync", "sage_set_projection_mode", "sage_fd_sketch_export", "sage_basis_export", "sage_set_basis", "sage_scores",
     "sage_scores_export", "sage_zhat_export", "sage_stats", "sage_topm", "sage_topm_static", "sage_probe_gram_eig", "sage_probe_eig_matrix",
     "sage_profile_enable", "sage_copy_probe", "sage_set_debug_checks", "sage_debug_fail_launch", "sage_set_sweep_policy",
@@ -67,6 +68,7 @@ def lib():
     L.sage_select.argtypes = [vp, dbl, vp, i64, C.POINTER(i64)]
     L.sage_score_labeled.argtypes = [vp, vp, vp, i64]
     L.sage_select_cb.argtypes = [vp, dbl, i32, vp, i64, C.POINTER(i64)]
+    L.sage_select_cb_ex.argtypes = [vp, dbl, i32, i32, vp, i64, C.POINTER(i64)]
     L.sage_destroy.argtypes = [vp]
     L.sage_destroy.restype = None
     L.sage_sync.argtypes = [vp]
@@ -209,13 +211,15 @@ class Sage:
         assert labels.numel() == G.shape[0]
         _check(self.L.sage_score_labeled(self.h, _ptr(G), _ptr(labels), G.shape[0]), "sage_score_labeled")
 
-    def select_cb(self, keep_rate, n_classes, cap=None):
+    def select_cb(self, keep_rate, n_classes, cap=None, rule="proportional"):
+        """Class-balanced selection; rule: how the subset size is shared out ("proportional" or "equal")."""
         st = self.stats()
         cap = st.n_scored if cap is None else int(cap)
         out = self.torch.empty(max(cap, 1), dtype=self.torch.int64, device="cuda")
         m = C.c_int64(0)
-        _check(self.L.sage_select_cb(self.h, float(keep_rate), int(n_classes), _ptr(out), cap, C.byref(m)),
-               "sage_select_cb")
+        code = {"proportional": CB_PROPORTIONAL, "equal": CB_EQUAL}[rule]
+        _check(self.L.sage_select_cb_ex(self.h, float(keep_rate), int(n_classes), code, _ptr(out), cap, C.byref(m)),
+               "sage_select_cb_ex")
         return out[: m.value]
 
     def select(self, keep_rate, cap=None):

@@ -1007,8 +1007,14 @@ int sage_select(sage_ctx* c, double keep_rate, int64_t* out_idx, int64_t cap, in
 }
 
 int sage_select_cb(sage_ctx* c, double keep_rate, int n_classes, int64_t* out_idx, int64_t cap, int64_t* out_m) {
+    return sage_select_cb_ex(c, keep_rate, n_classes, SAGE_CB_PROPORTIONAL, out_idx, cap, out_m);
+}
+
+int sage_select_cb_ex(sage_ctx* c, double keep_rate, int n_classes, int rule, int64_t* out_idx, int64_t cap,
+                      int64_t* out_m) {
     ALIVE(c);
-    if (!out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0) || n_classes < 1 || n_classes > 65536)
+    if (!out_m || cap < 0 || !(keep_rate >= 0.0 && keep_rate <= 1.0) || n_classes < 1 || n_classes > 65536 ||
+        (rule != SAGE_CB_PROPORTIONAL && rule != SAGE_CB_EQUAL))
         return SAGE_ERR_ARG;
     if (!c->has_basis) return SAGE_ERR_STATE;
     const int64_t N = c->n_scored;
@@ -1030,7 +1036,7 @@ int sage_select_cb(sage_ctx* c, double keep_rate, int n_classes, int64_t* out_id
         c->cb_work_bytes = need;
     }
     const CbWork w = cb_work_layout(c->cb_work, n_classes, N);
-    RUN(K_SELECT, launch_cb_scores(c->zhat, c->labels, N, c->k, n_classes, keep_rate, c->alpha, w, c->st));
+    RUN(K_SELECT, launch_cb_scores(c->zhat, c->labels, N, c->k, n_classes, keep_rate, rule, c->alpha, w, c->st));
     c->alpha_n = N;
     uint32_t misc[2] = {0, 0};
     HIPCHK(hipMemcpyAsync(misc, w.misc, sizeof(misc), hipMemcpyDeviceToHost, c->st));

@@ -238,8 +238,9 @@ struct CbWork {
 };
 size_t cb_work_bytes(int C, int64_t N);
 CbWork cb_work_layout(void* base, int C, int64_t N);
-hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int k, int C, double keep, float* alpha,
-                            const CbWork& w, hipStream_t st);
+// rule: sage_cb_rule (how the subset size is shared out among the classes)
+hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int k, int C, double keep, int rule,
+                            float* alpha, const CbWork& w, hipStream_t st);
 hipError_t launch_cb_select(const float* alpha, const int* labels, int64_t N, int C, int64_t* out_idx, const CbWork& w,
                             hipStream_t st);
 

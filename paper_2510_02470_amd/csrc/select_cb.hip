@@ -191,6 +191,101 @@ __global__ __launch_bounds__(1024) void cb_quota_kernel(const uint32_t* __restri
     if (t == 0) misc[0] = (uint32_t)tot;
 }
 
+// The other budget rule: equal budgets. The m = floor(keep * N + 0.5) rows are dealt one at a time to the classes in
+// turn, lowest class first, a full class being passed over. In closed form: with q the largest level for which
+// sum_c min(N_c, q) <= m, class c gets min(N_c, q), and the m - sum_c min(N_c, q) rows left (fewer than there are
+// classes larger than q) go one each to the lowest-numbered classes with N_c > q. Integer work throughout. One
+// work-group of 1024 threads; also sets the start state of the selects and misc[0] = sum_c k_c, like cb_quota_kernel.
+__global__ __launch_bounds__(1024) void cb_quota_equal_kernel(const uint32_t* __restrict__ counts, int C, double keep,
+                                                              uint32_t* __restrict__ kc, uint32_t* __restrict__ prefix,
+                                                              uint32_t* __restrict__ remain, uint32_t* __restrict__ misc) {
+#pragma clang fp contract(off)
+    __shared__ unsigned long long red[1024];
+    const int t = threadIdx.x;
+    auto block_sum = [&](unsigned long long v) {
+        red[t] = v;
+        __syncthreads();
+        for (int w = 512; w >= 1; w >>= 1) {
+            if (t < w) red[t] += red[t + w];
+            __syncthreads();
+        }
+        const unsigned long long r = red[0];
+        __syncthreads();
+        return r;
+    };
+    auto block_max = [&](unsigned long long v) {
+        red[t] = v;
+        __syncthreads();
+        for (int w = 512; w >= 1; w >>= 1) {
+            if (t < w) red[t] = red[t] > red[t + w] ? red[t] : red[t + w];
+            __syncthreads();
+        }
+        const unsigned long long r = red[0];
+        __syncthreads();
+        return r;
+    };
+    unsigned long long nsum = 0, nmax = 0;
+    for (int c = t; c < C; c += 1024) {
+        const unsigned long long n = counts[c];
+        nsum += n;
+        nmax = n > nmax ? n : nmax;
+    }
+    const unsigned long long N = block_sum(nsum), top = block_max(nmax);
+    double x;
+    {
+#pragma clang fp contract(off)
+        const double kn = keep * (double)N;
+        x = floor(kn + 0.5);
+    }
+    const unsigned long long m = x <= 0.0 ? 0ull : (x >= (double)N ? N : (unsigned long long)x);
+    auto dealt = [&](unsigned long long q) {  // sum_c min(N_c, q)
+        unsigned long long s = 0;
+        for (int c = t; c < C; c += 1024) {
+            const unsigned long long n = counts[c];
+            s += n < q ? n : q;
+        }
+        return block_sum(s);
+    };
+    unsigned long long lo = 0, hi = top;  // dealt(lo) <= m always (dealt(0) = 0); the answer is in [lo, hi]
+    while (lo < hi) {                     // (every thread sees the same sums, so the loop is uniform)
+        const unsigned long long mid = lo + (hi - lo + 1) / 2;
+        if (dealt(mid) <= m) lo = mid;
+        else hi = mid - 1;
+    }
+    const unsigned long long q = lo;
+    const unsigned long long spare = m - dealt(q);  // < number of classes with N_c > q
+    // ordered count of the classes that can take a spare row: every thread owns a contiguous run of classes
+    const int chunk = (C + 1023) / 1024;
+    const int c0 = t * chunk, c1 = c0 + chunk < C ? c0 + chunk : C;
+    unsigned long long open = 0;
+    for (int c = c0; c < c1; ++c) open += counts[c] > q;
+    red[t] = open;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {  // Hillis-Steele inclusive scan
+        const unsigned long long a = t >= o ? red[t - o] : 0ull;
+        __syncthreads();
+        red[t] += a;
+        __syncthreads();
+    }
+    unsigned long long before = red[t] - open;
+    __syncthreads();
+    unsigned long long tot = 0;
+    for (int c = c0; c < c1; ++c) {
+        const unsigned long long n = counts[c];
+        unsigned long long b = n < q ? n : q;
+        if (n > q) {
+            if (before < spare) b += 1;
+            before += 1;
+        }
+        kc[c] = (uint32_t)b;
+        prefix[c] = 0;
+        remain[c] = (uint32_t)b;
+        tot += b;
+    }
+    tot = block_sum(tot);
+    if (t == 0) misc[0] = (uint32_t)tot;
+}
+
 // alpha_i = clamp(<zhat_i, u_c(i)>, -1, 1), -0 stored as +0; one wave per row
 __global__ __launch_bounds__(256) void cb_cosine_kernel(const float* __restrict__ zhat, const int* __restrict__ labels,
                                                         int64_t N, int k, int C, const double* __restrict__ ucls,
@@ -384,8 +479,8 @@ CbWork cb_work_layout(void* base, int C, int64_t N) {
 }
 
 // Stage 1: class counts, sums, centroids, k_c, scores. Afterwards misc[0] = total kept, misc[1] = bad label seen.
-hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int k, int C, double keep, float* alpha,
-                            const CbWork& w, hipStream_t st) {
+hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int k, int C, double keep, int rule,
+                            float* alpha, const CbWork& w, hipStream_t st) {
     const int64_t zi = (int64_t)C * 256;
     hipLaunchKernelGGL(cb_zero_kernel, dim3((unsigned)((zi + 255) / 256)), dim3(256), 0, st, w.counts, w.sums, w.hist,
                        w.misc, C);
@@ -396,7 +491,11 @@ hipError_t launch_cb_scores(const float* zhat, const int* labels, int64_t N, int
                            w.sums, w.misc);
     }
     hipLaunchKernelGGL(cb_unit_kernel, dim3(C), dim3(128), 0, st, w.sums, k, w.ucls);
-    hipLaunchKernelGGL(cb_quota_kernel, dim3(1), dim3(1024), 0, st, w.counts, C, keep, w.kc, w.prefix, w.remain, w.misc);
+    if (rule == SAGE_CB_EQUAL)
+        hipLaunchKernelGGL(cb_quota_equal_kernel, dim3(1), dim3(1024), 0, st, w.counts, C, keep, w.kc, w.prefix, w.remain,
+                           w.misc);
+    else
+        hipLaunchKernelGGL(cb_quota_kernel, dim3(1), dim3(1024), 0, st, w.counts, C, keep, w.kc, w.prefix, w.remain, w.misc);
     if (N > 0) {
         int64_t blocks = (N + 3) / 4;
         if (blocks > 8192) blocks = 8192;

@@ -939,6 +939,44 @@ def test_class_budgets_sum_to_the_subset_size_with_many_small_classes():
         assert got.tolist() == oracle.cb_budgets(np.bincount(labels, minlength=Cn), keep).tolist()
 
 
+@pytest.mark.parametrize("Cn,sizes", [(7, "skewed"), (1000, "small"), (40, "some_empty"), (1, "one")])
+def test_class_budgets_under_the_equal_rule(Cn, sizes):
+    """sage_select_cb_ex with SAGE_CB_EQUAL: budgets class by class against the oracle's (rows dealt one at a time to
+    the classes in turn), the selection against the oracle's on the GPU's scores, for class sizes that are very uneven,
+    tiny, partly zero, and for one class; the proportional rule through the same entry point; a rule that does not exist."""
+    import ctypes as C
+
+    B = _binding()
+    D, k, N = 64, 8, 12_000
+    rng = np.random.default_rng(31)
+    V = np.ascontiguousarray(np.linalg.qr(rng.standard_normal((D, k)))[0].T.astype(np.float32))
+    G = rng.standard_normal((N, D)).astype(np.float32)
+    if sizes == "skewed":
+        p = np.array([0.6, 0.2, 0.1, 0.05, 0.03, 0.015, 0.005])
+    elif sizes == "some_empty":
+        p = np.where(np.arange(Cn) % 3 == 0, 0.0, rng.random(Cn))
+        p /= p.sum()
+    else:
+        p = np.full(Cn, 1.0 / Cn)
+    labels = rng.choice(Cn, size=N, p=p).astype(np.int32)
+    counts = np.bincount(labels, minlength=Cn)
+    s = B.Sage(8, D)
+    s.set_basis(torch.from_numpy(V).cuda())
+    s.score_labeled(torch.from_numpy(G).cuda(), torch.from_numpy(labels).cuda())
+    for keep in (0.0, 0.004, 0.05, 0.4, 0.97, 1.0):
+        idx = s.select_cb(keep, Cn, rule="equal").cpu().numpy()
+        al = s.scores().cpu().numpy()
+        want = oracle.cb_budgets(counts, keep, "equal")
+        assert np.bincount(labels[idx], minlength=Cn).tolist() == want.tolist(), (keep, Cn)
+        assert len(idx) == oracle.keep_count(keep, N)
+        assert idx.tolist() == oracle.cb_select_from_alpha(al, labels, Cn, keep, "equal").tolist()
+        pidx = s.select_cb(keep, Cn, rule="proportional").cpu().numpy()
+        assert pidx.tolist() == s.select_cb(keep, Cn).cpu().numpy().tolist()
+        assert pidx.tolist() == oracle.cb_select_from_alpha(s.scores().cpu().numpy(), labels, Cn, keep).tolist()
+    m = C.c_int64(0)
+    assert B.lib().sage_select_cb_ex(s.h, 0.5, Cn, 2, None, 0, C.byref(m)) == B.SAGE_ERR_ARG
+
+
 def test_first_pass_memory_does_not_grow_with_the_stream():
     """Abstract / complexity paragraph: O(ell D) memory, independent of N. After the first batches have been sketched,
     further batches of the first pass must not change the device memory the process holds."""
